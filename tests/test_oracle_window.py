@@ -1,0 +1,86 @@
+"""Pins of the windowed distributor: a hand-worked example and structural properties."""
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_06362_amd import workloads as W
+
+GOLDEN = Path(__file__).parent / "golden" / "window_worked_example.txt"
+
+
+def read_golden():
+    out = {}
+    for line in GOLDEN.read_text().splitlines():
+        if line.startswith("#") or not line.strip():
+            continue
+        key, vals = line.split(":")
+        out[key.strip()] = [float(v) for v in vals.split()]
+    return out
+
+
+def worked_example_workload(g):
+    full = lambda v: np.full((1, 5), v, np.float32)
+    return W.Workload(
+        name="worked", seed=0, tp_degree=np.array([1], np.uint32), b_cap=4,
+        prefill_a=full(0.25), prefill_p=full(2.0**-10), tbt=full(2.0**-6),
+        d_ttft=np.array([2.0], np.float32), d_tbt=np.array([0.125], np.float32),
+        prompt_len=np.array(g["prompt_len"], np.uint32), out_len=np.array(g["out_len"], np.uint32),
+        slo_class=np.zeros(6, np.uint8), arrival_ticks=np.array(g["arrival_ticks"], np.uint32),
+        n_inst=np.array([1], np.uint32), tp_idx=np.zeros((1, 1), np.uint8),
+        max_batch=np.array([[4]], np.uint16), occ=np.zeros((1, 1), np.int32),
+        q_ticks=np.zeros((1, 1), np.uint64), s_bar=np.float32(64.0), window=int(g["window"][0]))
+
+
+def test_hand_worked_windows():
+    g = read_golden()
+    r = oracle.score_assign(worked_example_workload(g))
+    assert r["chosen"].tolist() == g["chosen"]
+    assert r["slack"].tolist() == g["slack"]
+    assert r["ttft"].tolist() == g["ttft"]
+    assert r["e2e"].tolist() == g["e2e"]
+    assert r["n_satisfied"] == g["n_satisfied"][0]
+    assert r["occ"].tolist() == g["final_occ"] and r["q_ticks"].tolist() == g["final_q_ticks"]
+
+
+def test_one_window_over_everything_scores_like_the_static_call():
+    w = W.random_small(21, 1, 12, 300)
+    w = W.replace(w, n_inst=np.array([12], np.uint32))
+    a = oracle.score_assign(w, window=0)
+    b = oracle.score_assign(w, window=w.n_req)
+    c = oracle.score_assign(w, window=w.n_req + 77)
+    for k in ("chosen", "slack", "ttft", "e2e"):
+        assert np.array_equal(a[k], b[k], equal_nan=True) and np.array_equal(a[k], c[k], equal_nan=True)
+    assert a["n_satisfied"] == b["n_satisfied"]
+    # the static call leaves the state alone; the single window loads it and does not drain
+    assert np.array_equal(a["occ"], w.occ[0]) and np.array_equal(a["q_ticks"], w.q_ticks[0])
+    adm = b["slack"] >= 0
+    assert np.array_equal(b["occ"] - w.occ[0], np.bincount(b["chosen"][adm], minlength=12))
+    assert np.array_equal(b["occ"], c["occ"]) and np.array_equal(b["q_ticks"], c["q_ticks"])
+    assert (b["q_ticks"] >= w.q_ticks[0]).all()
+
+
+def test_a_blocked_request_leaves_the_state_untouched():
+    g = read_golden()
+    w = worked_example_workload(g)
+    w = W.replace(w.with_requests(3, 4), window=1)            # only the 4096-token request
+    r = oracle.score_assign(w)
+    assert r["n_satisfied"] == 0 and r["slack"][0] < 0
+    assert r["occ"].tolist() == [0] and r["q_ticks"].tolist() == [0]
+
+
+def test_window_state_accounting():
+    # Over all windows: admitted requests either still occupy an instance or were drained; occupancy
+    # never goes negative; queue ticks never exceed the admitted prefill work.
+    w = W.config2(n_req=16384, window=512)
+    r = oracle.score_assign(w)
+    adm = r["slack"] >= 0
+    assert (r["occ"] >= 0).all()
+    assert r["occ"].sum() <= adm.sum()
+    assert r["n_satisfied"] == adm.sum()
+    per_inst = np.bincount(r["chosen"][adm], minlength=64)
+    assert (r["occ"] <= per_inst).all()
+    # the last window is loaded but not drained
+    last = np.arange(w.n_req) >= (w.n_req - 512)
+    assert (r["occ"] >= np.bincount(r["chosen"][adm & last], minlength=64)).all()
