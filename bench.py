@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the MaaSO scoring path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input that is already resident in
+HBM: maaso_placement_sweep over every candidate deployment (profile evaluation, queue wait, SLO
+fetch, per-triple latency, SLO check, per-request feasibility, per-candidate reduction, best
+candidate) followed by maaso_score_assign of the same requests on the winning deployment (best
+instance per request, admitted count).  The default workload is the placer sweep with 4096
+candidates over a 32-GPU budget and 65,536 requests.
+
+Prints ONE JSON line: scored (candidate, request, instance) triples per second, the roofline of the
+dominant kernel (timed with HIP events recorded inside the library directly around that kernel, on
+the stream it is launched on) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+# MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 single-issue fp32 lane
+# operations per second.  (The published 157.3 TFLOP/s counts a packed dual fused multiply-add,
+# 4 flop per lane per issue; packed fp32 instructions are compiled out of this library.)
+VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+HBM_PEAK_GBS = 8000.0
+
+# Algorithmic work of the sweep per (request, instance) triple: prefill fma, wait add, min.
+SWEEP_LANEOPS_PER_TRIPLE = 3
+SWEEP_FLOP_PER_TRIPLE = 4  # the fma counts two
+# Algorithmic work of the distributor per triple: 2 fma, 1 add, 3 sub, 3 mul, 2 min, compare,
+# 2 selects (slack and index).
+ASSIGN_LANEOPS_PER_TRIPLE = 14
+# Algorithmic HBM bytes of the distributor per request: prompt_len 4 + out_len 4 + class 1 in,
+# chosen 4 + slack 4 out.
+ASSIGN_BYTES_PER_REQUEST = 17
+
+
+def make_workload(name: str):
+    from paper_2509_06362_amd import workloads as W
+    if name == "cfg1":
+        return W.config1()
+    if name == "cfg3":
+        return W.config3()
+    if name == "cfg4":
+        return W.config4()
+    if name == "cfg0":
+        return W.config0()
+    if name == "cfg2":
+        return W.config2()
+    if name == "stream":
+        return W.streaming_shape()
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(w, kind: str, budget_triples: float):
+    """The oracle as it stands, single-threaded, on a bounded sample of the workload."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    if kind == "sweep":
+        per_cand = w.n_req * w.n_inst.astype(np.int64)
+        n = int(np.searchsorted(np.cumsum(per_cand), budget_triples)) + 1
+        n = max(1, min(n, w.n_cand))
+        t0 = time.perf_counter()
+        oracle.placement_sweep(w, 0, n)
+        dt = time.perf_counter() - t0
+        triples = int(per_cand[:n].sum())
+        sample = f"candidates [0,{n}) of {w.n_cand} x all {w.n_req} requests, {triples:.3e} triples"
+    else:
+        n = int(min(w.n_req, max(1, budget_triples // max(1, int(w.n_inst[0])))))
+        if w.window:
+            n = max(w.window, (n // w.window) * w.window)
+            n = min(n, w.n_req)
+        ws = w.with_requests(0, n)
+        t0 = time.perf_counter()
+        oracle.score_assign(ws, latencies=False)
+        dt = time.perf_counter() - t0
+        triples = n * int(w.n_inst[0])
+        sample = f"requests [0,{n}) of {w.n_req} x {int(w.n_inst[0])} instances, {triples:.3e} triples"
+    return {"value": triples / dt, "unit": "triples/s", "cores": 1, "kind": "oracle",
+            "sample": sample, "seconds": dt}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg1",
+                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "stream"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-triples", type=float, default=1.0e9,
+                    help="size of the oracle's timed sample, in triples")
+    ap.add_argument("--sweep-q", type=int, default=0)
+    ap.add_argument("--sweep-chunk", type=int, default=0)
+    ap.add_argument("--window-blocks", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2509_06362_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    binding.load_library()
+    w = make_workload(args.workload)
+    kind = "sweep" if w.n_cand > 1 else "assign"
+    dw = binding.DeviceWorkload(w)
+    binding.maaso_ctx_set_launch_shape(dw.ctx, args.sweep_q, args.sweep_chunk, args.window_blocks)
+    dev = dw.prompt_len.device
+    stream = torch.cuda.current_stream()
+
+    # outputs allocated once, outside the timed region
+    sweep_out = (torch.empty(w.n_cand, dtype=torch.int32, device=dev),
+                 torch.empty(w.n_cand, dtype=torch.float32, device=dev),
+                 torch.empty(1, dtype=torch.int32, device=dev))
+    assign_out = dict(chosen=torch.empty(w.n_req, dtype=torch.int32, device=dev),
+                      slack=torch.empty(w.n_req, dtype=torch.float32, device=dev),
+                      n_satisfied=torch.empty(1, dtype=torch.int64, device=dev))
+
+    if kind == "sweep":
+        # the distributor runs on the winning deployment; its index is fixed by a first sweep so
+        # that the timed steps need no device-to-host copy
+        dw.sweep(out=sweep_out)
+        torch.cuda.synchronize()
+        best = int(sweep_out[2].item())
+        triples_sweep = w.valid_triples()
+        triples_assign = w.n_req * int(w.n_inst[best])
+
+        def step():
+            dw.sweep(out=sweep_out, stream=stream)
+            dw.assign(cand=best, window=0, latencies=False, out=assign_out, stream=stream)
+    else:
+        best = 0
+        triples_sweep = 0
+        triples_assign = w.n_req * int(w.n_inst[0])
+
+        def step():
+            dw.assign(cand=0, window=w.window, latencies=False, out=assign_out, stream=stream)
+
+    triples_step = triples_sweep + triples_assign
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = triples_step * args.steps / dt
+
+    # dominant kernel: event pairs recorded inside the library around that kernel only
+    binding.maaso_ctx_kernel_timing(dw.ctx, True)
+    n_timed = min(args.steps, 100)
+    for _ in range(n_timed):
+        if kind == "sweep":
+            dw.sweep(out=sweep_out, stream=stream)
+        else:
+            step()
+    torch.cuda.synchronize()
+    k_ms, k_n = binding.maaso_ctx_kernel_elapsed(dw.ctx)
+    binding.maaso_ctx_kernel_timing(dw.ctx, False)
+    k_avg_s = k_ms / max(k_n, 1) * 1e-3
+    if kind == "sweep":
+        laneops = SWEEP_LANEOPS_PER_TRIPLE * triples_sweep
+        roofline = {
+            "kernel": "sweep_kernel", "bound": "alu",
+            "achieved": laneops / k_avg_s / 1e12, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
+            "frac": laneops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS, "traffic": None,
+            "kernel_ms": k_avg_s * 1e3, "launches_timed": k_n,
+            "laneops_per_triple": SWEEP_LANEOPS_PER_TRIPLE,
+            "tflops": SWEEP_FLOP_PER_TRIPLE * triples_sweep / k_avg_s / 1e12,
+            "frac_of_fp32_vector_peak": SWEEP_FLOP_PER_TRIPLE * triples_sweep / k_avg_s / 1e12
+            / FP32_VECTOR_PEAK_TFLOPS,
+            "kernel_triples_per_s": triples_sweep / k_avg_s,
+        }
+    else:
+        nbytes = ASSIGN_BYTES_PER_REQUEST * w.n_req
+        laneops = ASSIGN_LANEOPS_PER_TRIPLE * triples_assign
+        hbm_frac = nbytes / k_avg_s / 1e9 / HBM_PEAK_GBS
+        alu_frac = laneops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS
+        name = "assign_window_kernel" if w.window else "assign_static_kernel"
+        roofline = {
+            "kernel": name, "bound": "hbm", "achieved": nbytes / k_avg_s / 1e9,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac, "traffic": None,
+            "kernel_ms": k_avg_s * 1e3, "launches_timed": k_n, "alu_frac": alu_frac,
+            "bytes_per_request": ASSIGN_BYTES_PER_REQUEST,
+        }
+
+    status = binding.maaso_ctx_device_status(dw.ctx)
+    result = {
+        "metric": "scored (candidate,request,instance) triples/sec", "value": value,
+        "unit": "triples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n_cand": w.n_cand, "i_pad": w.i_pad, "n_req": w.n_req,
+                   "n_slo": w.n_slo, "window": int(w.window), "seed": w.seed,
+                   "triples_per_step": triples_step, "padded_triples": w.padded_triples(),
+                   "step": "placement_sweep + score_assign(best candidate)" if kind == "sweep"
+                   else "score_assign"},
+        "roofline": roofline,
+        "device_status": status,
+    }
+    if kind == "sweep":
+        cnt = sweep_out[0].cpu().numpy().view(np.uint32)
+        result["config"]["best_cand"] = best
+        result["config"]["best_ratio"] = float(cnt[best]) / max(w.n_req, 1)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, kind, args.cpu_triples)
+        result["cpu_baseline"]["gpu_over_cpu"] = value / result["cpu_baseline"]["value"]
+    print(json.dumps(result))
+    dw.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,196 @@
+/* maaso.h - C ABI of the MI355X scoring path of MaaSO's placer and distributor.
+ *
+ * The library evaluates the profiler's performance model for every (candidate deployment, request,
+ * instance) triple, checks the request's deadlines, and reduces the result either to a chosen
+ * instance per request (distributor) or to an SLO-satisfaction ratio per candidate (placer).
+ * All kernels are HIP for gfx950; there is no CPU fallback: without a GPU every compute entry point
+ * returns MAASO_E_HIP.
+ *
+ * Conventions
+ *   - Every function returns 0 (MAASO_OK) or a negative maaso_status.  Nothing throws, aborts or
+ *     prints.  maaso_strerror() names a status.
+ *   - "HOST" pointers are read during the call and may be freed afterwards.  "DEVICE" pointers are
+ *     caller-owned device memory (for example torch tensors) on the context's device; the library
+ *     never frees or reallocates them.  The only memory the library owns is the context (device
+ *     copies of the tables, a scratch workspace, a status word).
+ *   - Compute calls are asynchronous on the given HIP stream (NULL = the default stream) and do no
+ *     host synchronisation, except that a call needing a larger workspace than any call before it
+ *     on that context grows the workspace first (one hipMalloc).  Outputs are valid once the stream
+ *     has been synchronised.
+ *   - A context may be used from one thread at a time; calls on one context that overlap in time
+ *     (different streams) race on its workspace.  Use one context per concurrent stream.
+ *   - Time is counted in ticks of 2^-20 s where integers are used (arrival_ticks, q_ticks).
+ *   - Arithmetic is IEEE-754 binary32, round to nearest even, one rounding per operation (fused
+ *     multiply-add where the model has one), so results do not depend on the launch configuration.
+ */
+#ifndef MAASO_H
+#define MAASO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MAASO_OK = 0,
+  MAASO_E_INVALID_ARG = -1, /* NULL where a pointer is required, n_cand != 1 for the distributor, ... */
+  MAASO_E_SHAPE = -2,       /* a size beyond MAASO_MAX_* or beyond what fits the LDS staging         */
+  MAASO_E_TABLE = -3,       /* non-finite or non-positive table entry / deadline outside [2^-20,2^20] */
+  MAASO_E_HIP = -4,         /* a HIP runtime call failed (no device, launch failure, ...)             */
+  MAASO_E_NOMEM = -5,       /* host or device allocation failed                                       */
+  MAASO_E_TIMEOUT = -6      /* reported by maaso_ctx_device_status: an inter-window wait gave up      */
+} maaso_status;
+
+#define MAASO_MAX_INSTANCES 256u   /* i_pad: instance slots per candidate                      */
+#define MAASO_MAX_SLO 16u          /* K: SLO classes                                            */
+#define MAASO_MAX_TABLE_CELLS 2048u /* n_tp * (b_cap + 1): cells per profile table (LDS-resident) */
+#define MAASO_MAX_REQUESTS 2147483648u /* R: requests per call                                  */
+#define MAASO_MAX_LEN 16777215u    /* prompt_len / out_len: exactly representable in binary32   */
+
+/* bits of the device status word (maaso_ctx_device_status) */
+#define MAASO_DEV_BAD_CLASS 1u     /* a request with slo_class >= n_slo was skipped (never satisfied) */
+#define MAASO_DEV_BAD_INSTANCE 2u  /* an instance with tp_idx >= n_tp or max_batch outside 1..b_cap was
+                                      treated as absent */
+#define MAASO_DEV_WAIT_TIMEOUT 4u  /* the windowed distributor's inter-window wait exceeded its spin
+                                      limit; outputs of that call are incomplete */
+
+typedef struct maaso_ctx maaso_ctx; /* opaque */
+
+/* Profile tables and SLO classes.  HOST pointers, copied at load.
+ *
+ * The profiler's throughput-decay function F(M,P,B,W) depends on the strategy P and on min(B,W)
+ * (Sec. IV-B, Eq. 1), so a profile is tabulated per (strategy row t, effective batch b), b = 1..b_cap.
+ * Row-major [n_tp][b_cap+1]; column 0 is never read and may hold anything.
+ *   prefill_a + prefill_p * prompt_len = prefill seconds;  tbt = seconds per output token (= 1/F).
+ * An SLO class k carries a first-token deadline d_ttft[k] and a between-token deadline d_tbt[k]; the
+ * end-to-end deadline of a request is d_ttft + out_len * d_tbt (normalised deadline, Sec. III-C). */
+typedef struct {
+  uint32_t n_tp;             /* T >= 1                                                   */
+  uint32_t b_cap;            /* >= 1; T * (b_cap + 1) <= MAASO_MAX_TABLE_CELLS           */
+  const uint32_t* tp_degree; /* [T] GPUs per instance N(P); informational, may be NULL   */
+  const float* prefill_a;    /* [T*(b_cap+1)] seconds, > 0 and finite for b >= 1         */
+  const float* prefill_p;    /* [T*(b_cap+1)] seconds per prompt token, > 0, finite      */
+  const float* tbt;          /* [T*(b_cap+1)] seconds per output token, > 0, finite      */
+  uint32_t n_slo;            /* K, 1..MAASO_MAX_SLO                                      */
+  const float* d_ttft;       /* [K] seconds, within [2^-20, 2^20]                        */
+  const float* d_tbt;        /* [K] seconds, within [2^-20, 2^20]                        */
+} maaso_profile_desc;
+
+/* Validates and copies the tables to `device` (a HIP device ordinal) and creates a context.
+ * Profiles are the placer's and distributor's input F(.) (Alg. 1 and Alg. 2, "Model profiles").
+ * Errors: INVALID_ARG (NULL), SHAPE, TABLE, HIP, NOMEM.  On error *out_ctx is set to NULL. */
+int maaso_profile_tables_load(const maaso_profile_desc* desc, int device, maaso_ctx** out_ctx);
+
+/* Frees the context and everything it owns.  NULL is allowed.  Synchronises the device. */
+void maaso_ctx_destroy(maaso_ctx* ctx);
+
+/* Synchronises the context's device, returns the MAASO_DEV_* bits raised by kernels since the last
+ * call in *bits (may be NULL) and clears them.  Returns MAASO_E_TIMEOUT if MAASO_DEV_WAIT_TIMEOUT is
+ * among them, MAASO_E_INVALID_ARG if another bit is, else MAASO_OK. */
+int maaso_ctx_device_status(maaso_ctx* ctx, uint32_t* bits);
+
+const char* maaso_strerror(int status);
+
+/* Performance knobs; they never change a result.  0 selects the library's own choice.
+ *   sweep_requests_per_lane: requests a lane of the sweep kernel keeps in registers (0, 2, 4, 8, 16);
+ *   sweep_chunk: candidates one block of the sweep kernel walks;
+ *   window_blocks: blocks of the windowed distributor's persistent kernel (at most one per compute
+ *   unit is used).  Errors: INVALID_ARG. */
+int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane, uint32_t sweep_chunk,
+                               uint32_t window_blocks);
+
+/* Number of polls after which a block of the windowed distributor stops waiting for the other
+ * blocks at a window boundary, raises MAASO_DEV_WAIT_TIMEOUT and leaves the kernel (all other blocks
+ * then leave too; the call's outputs are incomplete).  The default, 2^22, is seconds of waiting.
+ * Errors: INVALID_ARG. */
+int maaso_ctx_set_wait_limit(maaso_ctx* ctx, uint32_t polls);
+
+/* Instrumentation.  With timing enabled, each compute call records a pair of HIP events on its
+ * stream directly around its dominant kernel (the sweep kernel of maaso_placement_sweep, the scoring
+ * kernel of maaso_score_assign), for up to 256 calls.  maaso_ctx_kernel_elapsed waits for the
+ * recorded events, returns the sum of the kernel durations in milliseconds and their number, and
+ * starts a new series.  Enabling allocates the events once; no other call is affected.
+ * Errors: INVALID_ARG, HIP. */
+int maaso_ctx_kernel_timing(maaso_ctx* ctx, int enable);
+int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches);
+
+/* Requests as structure-of-arrays streams (Sec. IV-C: a request r decodes S_r tokens before its
+ * deadline; Sec. V-A: arrivals over time).  DEVICE pointers, read only. */
+typedef struct {
+  uint32_t n_req;                /* R, 0..MAASO_MAX_REQUESTS                                      */
+  const uint32_t* prompt_len;    /* [R] tokens, <= MAASO_MAX_LEN                                  */
+  const uint32_t* out_len;       /* [R] tokens, <= MAASO_MAX_LEN                                  */
+  const uint8_t* slo_class;      /* [R] < n_slo                                                   */
+  const uint32_t* arrival_ticks; /* [R] non-decreasing; read only when window > 0, else may be NULL */
+} maaso_requests;
+
+/* Candidate deployments: n_cand rows of i_pad instance slots, row-major [n_cand][i_pad]; the valid
+ * instances of candidate c are the slots j < n_inst[c].  An instance is configured by its strategy
+ * and inference batch size (P_i, B_i) and carries its live workload level W_i (Sec. IV-C) and the
+ * prefill work already queued on it (the pending time of Sec. III-C).  DEVICE pointers. */
+typedef struct {
+  uint32_t n_cand;           /* C >= 1                                                      */
+  uint32_t i_pad;            /* 1..MAASO_MAX_INSTANCES                                      */
+  const uint32_t* n_inst;    /* [C] <= i_pad; 0 is allowed (nothing can be served)          */
+  const uint8_t* tp_idx;     /* [C*i_pad] row of the profile tables, < n_tp                 */
+  const uint16_t* max_batch; /* [C*i_pad] B_j, 1..b_cap                                     */
+  int32_t* occ;              /* [C*i_pad] W_j >= 0: requests on the instance; written only by
+                                maaso_score_assign with window > 0                           */
+  uint64_t* q_ticks;         /* [C*i_pad] queued prefill time in ticks; written as occ is    */
+} maaso_placements;
+
+typedef struct {
+  float s_bar;       /* E[S_r] > 0: expected output length, used for the slot wait of an instance past
+                        its batch cap and for the fluid drain between windows (Eq. 2)             */
+  float pen_kappa;   /* >= 0: per-token latency is scaled by 1 + kappa * max(4w - 3B, 0) / B, i.e. it
+                        grows linearly once the batch is more than 75 % full; 0 disables           */
+  uint32_t tbt_mode; /* 0: profile row at the effective batch w = min(B, W + 1) (Eq. 1);
+                        1: worst case w = B (the distributor's conservative estimate, Sec. IV-F)   */
+  uint32_t window;   /* 0: every request is scored against the state as given (static);
+                        n > 0: requests are taken n at a time and the state advances in between    */
+} maaso_params;
+
+/* Per-request outputs of the distributor.  DEVICE pointers; any of them may be NULL (not written),
+ * except that at least n_satisfied or chosen must be given. */
+typedef struct {
+  int32_t* chosen;       /* [R] instance with the largest slack, lowest index on ties; -1 iff the
+                            placement has no valid instance                                     */
+  float* slack;          /* [R] its slack = min of the three relative margins; the request is
+                            admitted iff slack >= 0; -inf iff chosen == -1                       */
+  float* ttft;           /* [R] first-token latency on the chosen instance (NaN iff none)       */
+  float* tbt;            /* [R] between-token latency of the chosen instance (NaN iff none)     */
+  float* e2e;            /* [R] end-to-end latency on the chosen instance (NaN iff none)        */
+  uint64_t* n_satisfied; /* [1] number of admitted requests                                     */
+} maaso_assign_out;
+
+/* Distributor: instance assignment and overflow protection (Sec. IV-F, steps 2 and 3) for one
+ * placement (pl->n_cand must be 1).  For each request and each valid instance j:
+ *   prefill = p_j*L + a_j (fused);  ttft = wait_j + prefill;  e2e = S*tbt_j + ttft (fused);
+ *   margins (D - latency) / D against the TTFT, TBT and end-to-end deadlines;  slack = their min
+ * (L_r = L_q + L_d against the deadline, Eq. 2 and Eq. 3).  The request goes to the instance of
+ * largest slack and is admitted iff that slack is >= 0 (equality counts, Eq. 3), else blocked.
+ * With window > 0 the state (occ, q_ticks) is advanced after every window from the admitted
+ * requests: occupancy and queued prefill ticks are added, the queue drains by the arrival time that
+ * passed, and min(W,B) * elapsed / (s_bar * tbt_j) requests complete; blocked requests add no load.
+ * After the last window the load is added and nothing drains.  window >= R behaves as one window.
+ * Errors: INVALID_ARG, SHAPE, HIP, NOMEM - all detected on the host before any launch. */
+int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                       const maaso_params* prm, const maaso_assign_out* out, void* hip_stream);
+
+/* Placer: SLO-satisfaction count and ratio of every candidate deployment against the whole request
+ * set, and the best candidate - the evaluation of Phi_S^n(I', R_x) that Alg. 1 performs for each
+ * candidate deployment I' (Eq. 3, Eq. 6).  A request counts for candidate c iff some valid instance
+ * of c has slack >= 0 (the same triple arithmetic as maaso_score_assign, static state).
+ * Outputs, DEVICE pointers: sat_count [C] (required), sat_ratio [C] = count / R (0 when R == 0; may
+ * be NULL), best_cand [1] = lowest index among the largest counts (may be NULL).
+ * prm->window must be 0.  The placements are not written.
+ * Errors: INVALID_ARG, SHAPE, HIP, NOMEM. */
+int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                          const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
+                          uint32_t* best_cand, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAASO_H */

@@ -233,7 +233,7 @@ int oracle_score_assign(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
 }
 
 // Placer: static score of candidates [c_begin, c_end) of a [n_cand][i_pad] placement table against
-// all requests.  sat_count / sat_ratio are indexed by absolute candidate; best_cand is the lowest
+// all requests.  sat_count / sat_ratio (count / R; 0 for R == 0) are indexed by absolute candidate; best_cand is the lowest
 // candidate of the range with the largest count.  Returns 0, -1 bad profile.
 int oracle_placement_sweep(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
                            const float* prefill_p, const float* tbt, uint32_t n_slo,
@@ -275,7 +275,7 @@ int oracle_placement_sweep(uint32_t n_tp, uint32_t b_cap, const float* prefill_a
       if (best >= 0.0f) ++cnt;
     }
     sat_count[c] = cnt;
-    sat_ratio[c] = (float)cnt / (float)n_req;
+    sat_ratio[c] = (n_req == 0) ? 0.0f : (float)cnt / (float)n_req;  // empty request set: 0
     if (!have || cnt > best_n) { best_n = cnt; best_c = c; have = true; }
   }
   if (best_cand) *best_cand = best_c;

@@ -1,0 +1,328 @@
+"""Thin ctypes binding of libmaaso (include/maaso.h).  Argument marshalling only.
+
+Functions carry the names of the C entry points.  Device buffers are torch tensors (PyTorch is used
+for device memory and streams, nothing else); every step of the scoring path runs in the library's
+HIP kernels.  There is no fallback: if the shared library has not been built, or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+from typing import Optional
+
+import numpy as np
+
+LIB_PATH = Path(__file__).resolve().parent / "libmaaso.so"
+
+MAASO_MAX_INSTANCES = 256
+MAASO_MAX_SLO = 16
+MAASO_MAX_TABLE_CELLS = 2048
+
+EXPORTS = (
+    "maaso_profile_tables_load", "maaso_ctx_destroy", "maaso_ctx_device_status", "maaso_strerror",
+    "maaso_ctx_set_launch_shape", "maaso_ctx_set_wait_limit", "maaso_ctx_kernel_timing",
+    "maaso_ctx_kernel_elapsed", "maaso_score_assign", "maaso_placement_sweep",
+)
+
+
+class MaasoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class ProfileDesc(C.Structure):
+    _fields_ = [("n_tp", C.c_uint32), ("b_cap", C.c_uint32), ("tp_degree", C.c_void_p),
+                ("prefill_a", C.c_void_p), ("prefill_p", C.c_void_p), ("tbt", C.c_void_p),
+                ("n_slo", C.c_uint32), ("d_ttft", C.c_void_p), ("d_tbt", C.c_void_p)]
+
+
+class Requests(C.Structure):
+    _fields_ = [("n_req", C.c_uint32), ("prompt_len", C.c_void_p), ("out_len", C.c_void_p),
+                ("slo_class", C.c_void_p), ("arrival_ticks", C.c_void_p)]
+
+
+class Placements(C.Structure):
+    _fields_ = [("n_cand", C.c_uint32), ("i_pad", C.c_uint32), ("n_inst", C.c_void_p),
+                ("tp_idx", C.c_void_p), ("max_batch", C.c_void_p), ("occ", C.c_void_p),
+                ("q_ticks", C.c_void_p)]
+
+
+class Params(C.Structure):
+    _fields_ = [("s_bar", C.c_float), ("pen_kappa", C.c_float), ("tbt_mode", C.c_uint32),
+                ("window", C.c_uint32)]
+
+
+class AssignOut(C.Structure):
+    _fields_ = [("chosen", C.c_void_p), ("slack", C.c_void_p), ("ttft", C.c_void_p),
+                ("tbt", C.c_void_p), ("e2e", C.c_void_p), ("n_satisfied", C.c_void_p)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libmaaso.so from the package directory; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2509_06362_amd.build); "
+                "there is no fallback path")
+        lib = C.CDLL(str(LIB_PATH))
+        lib.maaso_strerror.restype = C.c_char_p
+        lib.maaso_strerror.argtypes = [C.c_int]
+        lib.maaso_profile_tables_load.argtypes = [C.POINTER(ProfileDesc), C.c_int,
+                                                  C.POINTER(C.c_void_p)]
+        lib.maaso_ctx_destroy.argtypes = [C.c_void_p]
+        lib.maaso_ctx_destroy.restype = None
+        lib.maaso_ctx_device_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint32)]
+        lib.maaso_ctx_set_launch_shape.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32]
+        lib.maaso_ctx_set_wait_limit.argtypes = [C.c_void_p, C.c_uint32]
+        lib.maaso_ctx_kernel_timing.argtypes = [C.c_void_p, C.c_int]
+        lib.maaso_ctx_kernel_elapsed.argtypes = [C.c_void_p, C.POINTER(C.c_float),
+                                                 C.POINTER(C.c_uint32)]
+        lib.maaso_score_assign.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
+                                           C.POINTER(Params), C.POINTER(AssignOut), C.c_void_p]
+        lib.maaso_placement_sweep.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
+                                              C.POINTER(Params), C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return load_library().maaso_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise MaasoError(status, where)
+
+
+def _host(a: np.ndarray, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _dptr(t, dtype=None) -> Optional[int]:
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device buffers must be contiguous GPU tensors"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+class Context:
+    """Owns a maaso_ctx*."""
+
+    def __init__(self, handle: int, device: int, n_slo: int):
+        self.handle, self.device, self.n_slo = handle, device, n_slo
+
+    def close(self) -> None:
+        if self.handle:
+            load_library().maaso_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+def maaso_profile_tables_load(n_tp, b_cap, prefill_a, prefill_p, tbt, d_ttft, d_tbt,
+                              tp_degree=None, device: int = 0) -> Context:
+    """Host numpy tables -> context on `device`."""
+    lib = load_library()
+    keep = [_host(prefill_a, np.float32), _host(prefill_p, np.float32), _host(tbt, np.float32),
+            _host(d_ttft, np.float32), _host(d_tbt, np.float32)]
+    deg = None if tp_degree is None else _host(tp_degree, np.uint32)
+    desc = ProfileDesc(int(n_tp), int(b_cap), None if deg is None else deg.ctypes.data,
+                       keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
+                       int(keep[3].shape[0]), keep[3].ctypes.data, keep[4].ctypes.data)
+    out = C.c_void_p()
+    _check(lib.maaso_profile_tables_load(C.byref(desc), int(device), C.byref(out)),
+           "maaso_profile_tables_load")
+    return Context(out.value, int(device), int(keep[3].shape[0]))
+
+
+def maaso_ctx_device_status(ctx: Context) -> int:
+    """Synchronises; returns and clears the MAASO_DEV_* bits.  Raises on a wait timeout."""
+    bits = C.c_uint32(0)
+    rc = load_library().maaso_ctx_device_status(ctx.handle, C.byref(bits))
+    if rc == -6:
+        raise MaasoError(rc, "maaso_ctx_device_status")
+    if rc not in (0, -1):
+        raise MaasoError(rc, "maaso_ctx_device_status")
+    return int(bits.value)
+
+
+def maaso_ctx_set_launch_shape(ctx: Context, sweep_requests_per_lane=0, sweep_chunk=0,
+                               window_blocks=0) -> None:
+    _check(load_library().maaso_ctx_set_launch_shape(ctx.handle, sweep_requests_per_lane,
+                                                     sweep_chunk, window_blocks),
+           "maaso_ctx_set_launch_shape")
+
+
+def maaso_ctx_set_wait_limit(ctx: Context, polls: int) -> None:
+    _check(load_library().maaso_ctx_set_wait_limit(ctx.handle, polls), "maaso_ctx_set_wait_limit")
+
+
+def maaso_ctx_kernel_timing(ctx: Context, enable: bool) -> None:
+    _check(load_library().maaso_ctx_kernel_timing(ctx.handle, int(bool(enable))),
+           "maaso_ctx_kernel_timing")
+
+
+def maaso_ctx_kernel_elapsed(ctx: Context):
+    """(sum of dominant-kernel durations in ms, number of launches) since the last call."""
+    ms, n = C.c_float(0), C.c_uint32(0)
+    _check(load_library().maaso_ctx_kernel_elapsed(ctx.handle, C.byref(ms), C.byref(n)),
+           "maaso_ctx_kernel_elapsed")
+    return float(ms.value), int(n.value)
+
+
+def _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks) -> Requests:
+    import torch
+    return Requests(int(n_req), _dptr(prompt_len, torch.int32), _dptr(out_len, torch.int32),
+                    _dptr(slo_class, torch.uint8), _dptr(arrival_ticks, torch.int32))
+
+
+def _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks) -> Placements:
+    import torch
+    return Placements(int(n_cand), int(i_pad), _dptr(n_inst, torch.int32), _dptr(tp_idx, torch.uint8),
+                      _dptr(max_batch, torch.int16), _dptr(occ, torch.int32),
+                      _dptr(q_ticks, torch.int64))
+
+
+def maaso_score_assign(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
+                       n_req, prompt_len, out_len, slo_class, arrival_ticks=None,
+                       s_bar, pen_kappa=0.0, tbt_mode=0, window=0,
+                       chosen=None, slack=None, ttft=None, tbt=None, e2e=None, n_satisfied=None,
+                       stream=None) -> None:
+    """All array arguments are GPU torch tensors holding the C types' bit patterns
+    (uint32 as int32, uint16 as int16, uint64 as int64)."""
+    import torch
+    pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
+    rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window))
+    out = AssignOut(_dptr(chosen, torch.int32), _dptr(slack, torch.float32),
+                    _dptr(ttft, torch.float32), _dptr(tbt, torch.float32),
+                    _dptr(e2e, torch.float32), _dptr(n_satisfied, torch.int64))
+    _check(load_library().maaso_score_assign(ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm),
+                                             C.byref(out), _stream_handle(stream)),
+           "maaso_score_assign")
+
+
+def maaso_placement_sweep(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
+                          n_req, prompt_len, out_len, slo_class, s_bar, pen_kappa=0.0, tbt_mode=0,
+                          window=0, sat_count, sat_ratio=None, best_cand=None, stream=None) -> None:
+    import torch
+    pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
+    rq = _requests(n_req, prompt_len, out_len, slo_class, None)
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window))
+    _check(load_library().maaso_placement_sweep(
+        ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm), _dptr(sat_count, torch.int32),
+        _dptr(sat_ratio, torch.float32), _dptr(best_cand, torch.int32), _stream_handle(stream)),
+        "maaso_placement_sweep")
+
+
+# ------------------------------------------------------------------------------------------------
+# plumbing for tests and the benchmark: a workload's arrays as GPU tensors
+# ------------------------------------------------------------------------------------------------
+
+class DeviceWorkload:
+    """Uploads the numpy arrays of a `workloads.Workload` once and keeps the tensors resident."""
+
+    def __init__(self, w, device: int = 0):
+        import torch
+        dev = torch.device("cuda", device)
+        self.w = w
+        self.device = device
+
+        def up(a, view):
+            a = np.ascontiguousarray(a)
+            return torch.from_numpy(a.view(view)).to(dev)
+
+        self.prompt_len = up(w.prompt_len, np.int32)
+        self.out_len = up(w.out_len, np.int32)
+        self.slo_class = up(w.slo_class, np.uint8)
+        self.arrival_ticks = None if w.arrival_ticks is None else up(w.arrival_ticks, np.int32)
+        self.n_inst = up(w.n_inst, np.int32)
+        self.tp_idx = up(w.tp_idx, np.uint8)
+        self.max_batch = up(w.max_batch, np.int16)
+        self.occ = up(w.occ, np.int32)
+        self.q_ticks = up(w.q_ticks, np.int64)
+        self.ctx = maaso_profile_tables_load(w.n_tp, w.b_cap, w.prefill_a, w.prefill_p, w.tbt,
+                                             w.d_ttft, w.d_tbt, w.tp_degree, device)
+
+    def request_args(self):
+        return dict(n_req=self.w.n_req, prompt_len=self.prompt_len, out_len=self.out_len,
+                    slo_class=self.slo_class)
+
+    def param_args(self):
+        return dict(s_bar=float(self.w.s_bar), pen_kappa=float(self.w.pen_kappa),
+                    tbt_mode=int(self.w.tbt_mode))
+
+    def sweep(self, stream=None, out=None):
+        """maaso_placement_sweep over all candidates; returns (sat_count, sat_ratio, best_cand)."""
+        import torch
+        dev = self.prompt_len.device
+        C_ = self.w.n_cand
+        if out is None:
+            out = (torch.empty(C_, dtype=torch.int32, device=dev),
+                   torch.empty(C_, dtype=torch.float32, device=dev),
+                   torch.empty(1, dtype=torch.int32, device=dev))
+        maaso_placement_sweep(
+            self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
+            max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, **self.request_args(),
+            **self.param_args(), sat_count=out[0], sat_ratio=out[1], best_cand=out[2], stream=stream)
+        return out
+
+    def assign(self, cand: int = 0, window=None, latencies: bool = True, stream=None, out=None,
+               tbt_mode=None):
+        """maaso_score_assign on candidate `cand` (state tensors are cloned, so the workload's own
+        copies stay as uploaded).  Returns a dict of tensors, plus the state after the call."""
+        import torch
+        dev = self.prompt_len.device
+        R = self.w.n_req
+        window = self.w.window if window is None else window
+        if out is None:
+            out = dict(chosen=torch.empty(R, dtype=torch.int32, device=dev),
+                       slack=torch.empty(R, dtype=torch.float32, device=dev),
+                       n_satisfied=torch.empty(1, dtype=torch.int64, device=dev))
+            if latencies:
+                for k in ("ttft", "tbt", "e2e"):
+                    out[k] = torch.empty(R, dtype=torch.float32, device=dev)
+        occ, q = self.occ[cand:cand + 1], self.q_ticks[cand:cand + 1]
+        if window:  # only the windowed form writes the state
+            occ, q = occ.clone(), q.clone()
+        prm = self.param_args()
+        if tbt_mode is not None:
+            prm["tbt_mode"] = tbt_mode
+        maaso_score_assign(
+            self.ctx, n_cand=1, i_pad=self.w.i_pad, n_inst=self.n_inst[cand:cand + 1],
+            tp_idx=self.tp_idx[cand:cand + 1], max_batch=self.max_batch[cand:cand + 1], occ=occ,
+            q_ticks=q, **self.request_args(), arrival_ticks=self.arrival_ticks, **prm,
+            window=window, stream=stream,
+            **{k: out.get(k) for k in ("chosen", "slack", "ttft", "tbt", "e2e", "n_satisfied")})
+        res = dict(out)
+        res["occ"], res["q_ticks"] = occ, q
+        return res
+
+    def close(self):
+        self.ctx.close()

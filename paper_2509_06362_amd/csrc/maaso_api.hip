@@ -1,0 +1,488 @@
+// Host side of the C ABI declared in include/maaso.h: argument validation, the context, launch
+// shapes.  Every step of the scoring path runs in the kernels of sweep_kernels.hpp and
+// assign_kernels.hpp; nothing here computes on the CPU beyond table validation and the reciprocals
+// of the class deadlines.
+#include "../../include/maaso.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "assign_kernels.hpp"
+#include "sweep_kernels.hpp"
+#include "window_kernels.hpp"
+
+using namespace maaso;
+
+static_assert(MAASO_MAX_SLO == kMaxSlo, "header and kernels disagree on the class limit");
+
+constexpr uint32_t kMaxTimed = 256;
+
+struct maaso_ctx {
+  int device;
+  uint32_t n_tp, b_cap, cells, n_slo;
+  float d_ttft[kMaxSlo], d_tbt[kMaxSlo], i_ttft[kMaxSlo], i_tbt[kMaxSlo];
+  float* tab;           // device: three tables back to back
+  uint32_t* status;     // device status word
+  uint32_t* cls_count;  // device [kMaxSlo]
+  void* ws;             // device workspace, grow-only
+  size_t ws_bytes;
+  uint32_t sweep_q;      // 0 = automatic
+  uint32_t sweep_chunk;  // 0 = automatic
+  uint32_t window_blocks;  // 0 = automatic
+  uint32_t spin_limit;     // polls of the inter-window barrier before a block gives up
+  int n_cu;
+  size_t lds_per_block;
+  // optional timing of the dominant kernel of each call (HIP events on the call's stream)
+  bool timing;
+  uint32_t n_timed;
+  hipEvent_t ev_start[kMaxTimed], ev_stop[kMaxTimed];
+};
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) { ok = false; (void)hipGetLastError(); return; }
+    if (prev != dev && hipSetDevice(dev) != hipSuccess) { ok = false; (void)hipGetLastError(); }
+  }
+  ~DeviceGuard() {
+    int cur = -1;
+    if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+  }
+};
+
+inline bool hip_ok(hipError_t e) {
+  if (e == hipSuccess) return true;
+  (void)hipGetLastError();
+  return false;
+}
+
+// Event pair around the dominant kernel of a call, when timing is on and slots are left.
+struct TimedRegion {
+  maaso_ctx* ctx;
+  hipStream_t s;
+  bool on;
+  TimedRegion(maaso_ctx* c, hipStream_t st) : ctx(c), s(st), on(c->timing && c->n_timed < kMaxTimed) {
+    if (on) on = hipEventRecord(ctx->ev_start[ctx->n_timed], s) == hipSuccess;
+  }
+  ~TimedRegion() {
+    if (on && hipEventRecord(ctx->ev_stop[ctx->n_timed], s) == hipSuccess) ctx->n_timed += 1;
+  }
+};
+
+int ensure_workspace(maaso_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->ws_bytes) return MAASO_OK;
+  if (ctx->ws) {
+    if (!hip_ok(hipDeviceSynchronize())) return MAASO_E_HIP;
+    (void)hipFree(ctx->ws);
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+  }
+  const size_t want = (bytes + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
+  if (!hip_ok(hipMalloc(&ctx->ws, want))) { ctx->ws = nullptr; return MAASO_E_NOMEM; }
+  ctx->ws_bytes = want;
+  return MAASO_OK;
+}
+
+int check_common(const maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                 const maaso_params* prm) {
+  if (!ctx || !pl || !rq || !prm) return MAASO_E_INVALID_ARG;
+  if (pl->n_cand == 0 || !pl->n_inst || !pl->tp_idx || !pl->max_batch || !pl->occ || !pl->q_ticks)
+    return MAASO_E_INVALID_ARG;
+  if (pl->i_pad == 0 || pl->i_pad > MAASO_MAX_INSTANCES) return MAASO_E_SHAPE;
+  if (rq->n_req != 0 && (!rq->prompt_len || !rq->out_len || !rq->slo_class))
+    return MAASO_E_INVALID_ARG;
+  if (rq->n_req > MAASO_MAX_REQUESTS) return MAASO_E_SHAPE;
+  if (!(prm->s_bar > 0.0f) || !std::isfinite(prm->s_bar)) return MAASO_E_INVALID_ARG;
+  if (!(prm->pen_kappa >= 0.0f) || !std::isfinite(prm->pen_kappa)) return MAASO_E_INVALID_ARG;
+  if (prm->tbt_mode > 1u) return MAASO_E_INVALID_ARG;
+  return MAASO_OK;
+}
+
+ModelParams model_params(const maaso_ctx* ctx, const maaso_params* prm) {
+  ModelParams mp;
+  mp.s_bar = prm->s_bar;
+  mp.pen_kappa = prm->pen_kappa;
+  mp.tbt_mode = prm->tbt_mode;
+  mp.n_tp = ctx->n_tp;
+  mp.b_cap = ctx->b_cap;
+  return mp;
+}
+
+template <int Q>
+int launch_sweep(const SweepArgs& a, uint32_t blocks, size_t lds, hipStream_t s) {
+  hipLaunchKernelGGL(sweep_kernel<Q>, dim3(blocks), dim3(kSweepThreads), lds, s, a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placements* pl,
+                      const maaso_requests* rq, const maaso_params* prm,
+                      const maaso_assign_out* out) {
+  a.tab = ctx->tab;
+  a.cells = ctx->cells;
+  a.mp = model_params(ctx, prm);
+  a.n_slo = ctx->n_slo;
+  std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
+  std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
+  std::memcpy(a.i_ttft, ctx->i_ttft, sizeof(a.i_ttft));
+  std::memcpy(a.i_tbt, ctx->i_tbt, sizeof(a.i_tbt));
+  a.i_pad = pl->i_pad;
+  a.n_inst = pl->n_inst;
+  a.tp_idx = pl->tp_idx;
+  a.max_batch = pl->max_batch;
+  a.occ = pl->occ;
+  a.q_ticks = reinterpret_cast<uint64_t*>(pl->q_ticks);
+  a.n_req = rq->n_req;
+  a.prompt_len = rq->prompt_len;
+  a.out_len = rq->out_len;
+  a.slo_class = rq->slo_class;
+  a.arrival_ticks = rq->arrival_ticks;
+  a.chosen = out->chosen;
+  a.slack = out->slack;
+  a.ttft = out->ttft;
+  a.tbt = out->tbt;
+  a.e2e = out->e2e;
+  a.n_satisfied = reinterpret_cast<unsigned long long*>(out->n_satisfied);
+  a.status = ctx->status;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* maaso_strerror(int status) {
+  switch (status) {
+    case MAASO_OK: return "ok";
+    case MAASO_E_INVALID_ARG: return "invalid argument";
+    case MAASO_E_SHAPE: return "size beyond the library's limits";
+    case MAASO_E_TABLE: return "profile table or deadline entry not finite and positive";
+    case MAASO_E_HIP: return "HIP runtime error";
+    case MAASO_E_NOMEM: return "out of memory";
+    case MAASO_E_TIMEOUT: return "inter-window wait timed out on the device";
+    default: return "unknown status";
+  }
+}
+
+int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx** out_ctx) {
+  if (out_ctx) *out_ctx = nullptr;
+  if (!d || !out_ctx || !d->prefill_a || !d->prefill_p || !d->tbt || !d->d_ttft || !d->d_tbt)
+    return MAASO_E_INVALID_ARG;
+  if (d->n_tp == 0 || d->b_cap == 0 || d->n_slo == 0) return MAASO_E_INVALID_ARG;
+  if (d->n_slo > MAASO_MAX_SLO || d->b_cap > 65535u) return MAASO_E_SHAPE;
+  const uint64_t cells64 = (uint64_t)d->n_tp * ((uint64_t)d->b_cap + 1u);
+  if (cells64 > MAASO_MAX_TABLE_CELLS) return MAASO_E_SHAPE;
+  const uint32_t cells = (uint32_t)cells64;
+  for (uint32_t t = 0; t < d->n_tp; ++t)
+    for (uint32_t b = 1; b <= d->b_cap; ++b) {
+      const size_t i = (size_t)t * (d->b_cap + 1u) + b;
+      const float v[3] = {d->prefill_a[i], d->prefill_p[i], d->tbt[i]};
+      for (float x : v)
+        if (!(x > 0.0f) || !std::isfinite(x)) return MAASO_E_TABLE;
+    }
+  for (uint32_t k = 0; k < d->n_slo; ++k) {
+    const float v[2] = {d->d_ttft[k], d->d_tbt[k]};
+    for (float x : v)
+      if (!(x >= 0x1p-20f) || !(x <= 0x1p20f)) return MAASO_E_TABLE;
+  }
+
+  int n_dev = 0;
+  if (!hip_ok(hipGetDeviceCount(&n_dev)) || device < 0 || device >= n_dev) return MAASO_E_HIP;
+  DeviceGuard guard(device);
+  if (!guard.ok) return MAASO_E_HIP;
+
+  maaso_ctx* ctx = new (std::nothrow) maaso_ctx();
+  if (!ctx) return MAASO_E_NOMEM;
+  std::memset(ctx, 0, sizeof(*ctx));
+  ctx->device = device;
+  ctx->n_tp = d->n_tp;
+  ctx->b_cap = d->b_cap;
+  ctx->cells = cells;
+  ctx->n_slo = d->n_slo;
+  ctx->spin_limit = 1u << 22;
+  for (uint32_t k = 0; k < kMaxSlo; ++k) {
+    const bool live = k < d->n_slo;
+    ctx->d_ttft[k] = live ? d->d_ttft[k] : 1.0f;
+    ctx->d_tbt[k] = live ? d->d_tbt[k] : 1.0f;
+    // reciprocal of a deadline: evaluated in double, rounded once to binary32
+    ctx->i_ttft[k] = (float)(1.0 / (double)ctx->d_ttft[k]);
+    ctx->i_tbt[k] = (float)(1.0 / (double)ctx->d_tbt[k]);
+  }
+  hipDeviceProp_t prop;
+  if (!hip_ok(hipGetDeviceProperties(&prop, device))) { delete ctx; return MAASO_E_HIP; }
+  ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  ctx->lds_per_block = prop.sharedMemPerBlock;
+
+  float* host = static_cast<float*>(std::malloc((size_t)3 * cells * sizeof(float)));
+  if (!host) { delete ctx; return MAASO_E_NOMEM; }
+  std::memcpy(host, d->prefill_a, (size_t)cells * 4);
+  std::memcpy(host + cells, d->prefill_p, (size_t)cells * 4);
+  std::memcpy(host + 2 * (size_t)cells, d->tbt, (size_t)cells * 4);
+  int rc = MAASO_OK;
+  if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->tab), (size_t)3 * cells * 4))) rc = MAASO_E_NOMEM;
+  if (rc == MAASO_OK && !hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->status), 256))) rc = MAASO_E_NOMEM;
+  if (rc == MAASO_OK) {
+    ctx->cls_count = ctx->status + 16;  // same small allocation: [0] status, [16..31] class counts
+    if (!hip_ok(hipMemcpy(ctx->tab, host, (size_t)3 * cells * 4, hipMemcpyHostToDevice)) ||
+        !hip_ok(hipMemset(ctx->status, 0, 256)))
+      rc = MAASO_E_HIP;
+  }
+  std::free(host);
+  if (rc != MAASO_OK) {
+    if (ctx->tab) (void)hipFree(ctx->tab);
+    if (ctx->status) (void)hipFree(ctx->status);
+    delete ctx;
+    return rc;
+  }
+  *out_ctx = ctx;
+  return MAASO_OK;
+}
+
+void maaso_ctx_destroy(maaso_ctx* ctx) {
+  if (!ctx) return;
+  DeviceGuard guard(ctx->device);
+  (void)hipDeviceSynchronize();
+  for (uint32_t i = 0; i < kMaxTimed; ++i) {
+    if (ctx->ev_start[i]) (void)hipEventDestroy(ctx->ev_start[i]);
+    if (ctx->ev_stop[i]) (void)hipEventDestroy(ctx->ev_stop[i]);
+  }
+  if (ctx->ws) (void)hipFree(ctx->ws);
+  if (ctx->tab) (void)hipFree(ctx->tab);
+  if (ctx->status) (void)hipFree(ctx->status);
+  (void)hipGetLastError();
+  delete ctx;
+}
+
+int maaso_ctx_device_status(maaso_ctx* ctx, uint32_t* bits) {
+  if (bits) *bits = 0;
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  uint32_t v = 0;
+  if (!hip_ok(hipDeviceSynchronize())) return MAASO_E_HIP;
+  if (!hip_ok(hipMemcpy(&v, ctx->status, 4, hipMemcpyDeviceToHost))) return MAASO_E_HIP;
+  if (v != 0 && !hip_ok(hipMemset(ctx->status, 0, 4))) return MAASO_E_HIP;
+  if (bits) *bits = v;
+  if (v & MAASO_DEV_WAIT_TIMEOUT) return MAASO_E_TIMEOUT;
+  return v ? MAASO_E_INVALID_ARG : MAASO_OK;
+}
+
+int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane,
+                               uint32_t sweep_chunk, uint32_t window_blocks) {
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  const uint32_t q = sweep_requests_per_lane;
+  if (q != 0 && q != 2 && q != 4 && q != 8 && q != 16) return MAASO_E_INVALID_ARG;
+  ctx->sweep_q = q;
+  ctx->sweep_chunk = sweep_chunk;
+  ctx->window_blocks = window_blocks;
+  return MAASO_OK;
+}
+
+int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                          const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
+                          uint32_t* best_cand, void* hip_stream) {
+  int rc = check_common(ctx, pl, rq, prm);
+  if (rc != MAASO_OK) return rc;
+  if (!sat_count || prm->window != 0u) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  const uint32_t C = pl->n_cand, I = pl->i_pad, K = ctx->n_slo, R = rq->n_req;
+
+  // launch shape: Q requests per lane, G candidates staged together, `chunk` candidates per block
+  uint32_t Q = ctx->sweep_q;
+  if (Q == 0) Q = R >= (1u << 15) ? 8u : (R >= (1u << 13) ? 4u : 2u);
+  // LDS: tables + two buffers of G candidates x 4 class slots x I records of 16 B + list lengths;
+  // with G * I <= 256 and the table limit this stays under 64 KiB.
+  const size_t tab_bytes = ((size_t)3 * ctx->cells * 4 + 15) & ~size_t(15);
+  uint32_t G = kSweepThreads / I;
+  if (G == 0) G = 1;
+  const size_t lds = tab_bytes + (size_t)2 * G * kSweepWaves * I * 16 + (size_t)3 * G * kSweepWaves * 4;
+  if (lds > 64u * 1024u) return MAASO_E_SHAPE;
+
+  const uint32_t tile = 64u * Q;
+  const uint64_t max_tiles = ((uint64_t)R + tile - 1) / tile + K;
+  const uint32_t n_req_blocks = (uint32_t)((max_tiles + 3) / 4);
+  uint32_t chunk = ctx->sweep_chunk;
+  if (chunk == 0) {
+    // aim at several blocks per compute unit, but keep at least 32 candidates per block so that the
+    // table and request loads are amortised
+    const uint64_t target_blocks = (uint64_t)ctx->n_cu * 16u;
+    uint64_t want_chunks = target_blocks / n_req_blocks;
+    if (want_chunks < 1) want_chunks = 1;
+    chunk = (uint32_t)(((uint64_t)C + want_chunks - 1) / want_chunks);
+    if (chunk < 32u) chunk = 32u;
+  }
+  chunk = ((chunk + G - 1) / G) * G;
+  const uint32_t n_chunks = (C + chunk - 1) / chunk;
+  const uint64_t blocks64 = (uint64_t)8 * ((n_chunks + 7) / 8) * n_req_blocks;
+  if (blocks64 > 0x7fffffffull) return MAASO_E_SHAPE;
+
+  rc = ensure_workspace(ctx, (size_t)K * (R ? R : 1u) * sizeof(float));
+  if (rc != MAASO_OK) return rc;
+  float* lbuf = static_cast<float*>(ctx->ws);
+
+  const uint32_t n_init = C > kMaxSlo ? C : kMaxSlo;
+  hipLaunchKernelGGL(sweep_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, sat_count, C,
+                     ctx->cls_count, (uint32_t)kMaxSlo);
+  if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+  if (R != 0) {
+    hipLaunchKernelGGL(bucket_requests_kernel, dim3((R + 1023) / 1024), dim3(256), 0, s,
+                       rq->prompt_len, rq->slo_class, R, K, lbuf, ctx->cls_count, ctx->status);
+    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+
+    SweepArgs a;
+    a.tab = ctx->tab;
+    a.cells = ctx->cells;
+    a.mp = model_params(ctx, prm);
+    a.n_slo = K;
+    std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
+    std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
+    a.n_cand = C;
+    a.i_pad = I;
+    a.n_inst = pl->n_inst;
+    a.tp_idx = pl->tp_idx;
+    a.max_batch = pl->max_batch;
+    a.occ = pl->occ;
+    a.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
+    a.lbuf = lbuf;
+    a.cls_count = ctx->cls_count;
+    a.n_req = R;
+    a.group = G;
+    a.chunk = chunk;
+    a.n_req_blocks = n_req_blocks;
+    a.n_chunks = n_chunks;
+    a.sat_count = sat_count;
+    a.status = ctx->status;
+    const uint32_t blocks = (uint32_t)blocks64;
+    {
+      TimedRegion timed(ctx, s);
+      switch (Q) {
+        case 2: rc = launch_sweep<2>(a, blocks, lds, s); break;
+        case 4: rc = launch_sweep<4>(a, blocks, lds, s); break;
+        case 8: rc = launch_sweep<8>(a, blocks, lds, s); break;
+        default: rc = launch_sweep<16>(a, blocks, lds, s); break;
+      }
+    }
+    if (rc != MAASO_OK) return rc;
+  }
+  hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
+                     best_cand);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                       const maaso_params* prm, const maaso_assign_out* out, void* hip_stream) {
+  int rc = check_common(ctx, pl, rq, prm);
+  if (rc != MAASO_OK) return rc;
+  if (!out || pl->n_cand != 1u || (!out->chosen && !out->n_satisfied)) return MAASO_E_INVALID_ARG;
+  const uint32_t R = rq->n_req;
+  if (prm->window != 0u && R != 0 && !rq->arrival_ticks) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  AssignArgs a;
+  fill_assign_args(a, ctx, pl, rq, prm, out);
+  const bool lat = out->ttft || out->tbt || out->e2e;
+  if (R == 0 || prm->window == 0u) {
+    hipLaunchKernelGGL(assign_init_kernel, dim3(1), dim3(64), 0, s, a.n_satisfied);
+    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+    if (R == 0) return MAASO_OK;
+    uint32_t blocks = (R + kAssignThreads - 1) / kAssignThreads;
+    const uint32_t cap = (uint32_t)ctx->n_cu * 8u;
+    if (blocks > cap) blocks = cap;
+    TimedRegion timed(ctx, s);
+    if (lat)
+      hipLaunchKernelGGL(assign_static_kernel<true>, dim3(blocks), dim3(kAssignThreads), 0, s, a);
+    else
+      hipLaunchKernelGGL(assign_static_kernel<false>, dim3(blocks), dim3(kAssignThreads), 0, s, a);
+    return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+  }
+
+  // Windowed: one persistent kernel; all blocks must be resident at once (one per compute unit at
+  // most).  Each request is spread over LPR lanes so that a window fills the blocks.
+  rc = ensure_workspace(ctx, sizeof(WindowWs));
+  if (rc != MAASO_OK) return rc;
+  WindowWs* ws = static_cast<WindowWs*>(ctx->ws);
+  const uint32_t per_window = prm->window < R ? prm->window : R;
+  uint32_t nb = ctx->window_blocks ? ctx->window_blocks : 64u;
+  if (nb > (uint32_t)ctx->n_cu) nb = (uint32_t)ctx->n_cu;
+  if (nb == 0) nb = 1;
+  uint32_t lpr = 1;
+  while (lpr < 64u && lpr * 2u <= pl->i_pad &&
+         (uint64_t)per_window * (lpr * 2u) <= (uint64_t)nb * kAssignThreads)
+    lpr *= 2u;
+  const uint64_t need = ((uint64_t)per_window * lpr + kAssignThreads - 1) / kAssignThreads;
+  if (need < nb) nb = (uint32_t)(need ? need : 1);
+  hipLaunchKernelGGL(window_init_kernel, dim3(1), dim3(256), 0, s, ws, a.n_satisfied);
+  if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+  const uint32_t spin = ctx->spin_limit;
+  TimedRegion timed(ctx, s);
+#define MAASO_LAUNCH_WINDOW(LPR)                                                                  \
+  do {                                                                                            \
+    if (lat)                                                                                      \
+      hipLaunchKernelGGL((assign_window_kernel<LPR, true>), dim3(nb), dim3(kAssignThreads), 0, s, \
+                         a, prm->window, ws, spin);                                               \
+    else                                                                                          \
+      hipLaunchKernelGGL((assign_window_kernel<LPR, false>), dim3(nb), dim3(kAssignThreads), 0, s, \
+                         a, prm->window, ws, spin);                                               \
+  } while (0)
+  switch (lpr) {
+    case 1: MAASO_LAUNCH_WINDOW(1); break;
+    case 2: MAASO_LAUNCH_WINDOW(2); break;
+    case 4: MAASO_LAUNCH_WINDOW(4); break;
+    case 8: MAASO_LAUNCH_WINDOW(8); break;
+    case 16: MAASO_LAUNCH_WINDOW(16); break;
+    case 32: MAASO_LAUNCH_WINDOW(32); break;
+    default: MAASO_LAUNCH_WINDOW(64); break;
+  }
+#undef MAASO_LAUNCH_WINDOW
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+int maaso_ctx_kernel_timing(maaso_ctx* ctx, int enable) {
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  if (enable && !ctx->ev_start[0]) {
+    for (uint32_t i = 0; i < kMaxTimed; ++i)
+      if (!hip_ok(hipEventCreate(&ctx->ev_start[i])) || !hip_ok(hipEventCreate(&ctx->ev_stop[i])))
+        return MAASO_E_HIP;
+  }
+  ctx->timing = enable != 0;
+  ctx->n_timed = 0;
+  return MAASO_OK;
+}
+
+int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches) {
+  if (!ctx || !total_ms || !launches) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  float sum = 0.0f;
+  for (uint32_t i = 0; i < ctx->n_timed; ++i) {
+    float ms = 0.0f;
+    if (!hip_ok(hipEventSynchronize(ctx->ev_stop[i])) ||
+        !hip_ok(hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i])))
+      return MAASO_E_HIP;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = ctx->n_timed;
+  ctx->n_timed = 0;
+  return MAASO_OK;
+}
+
+int maaso_ctx_set_wait_limit(maaso_ctx* ctx, uint32_t polls) {
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  ctx->spin_limit = polls;
+  return MAASO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,234 @@
+// Distributor over an online request stream: requests are taken in windows; all requests of a window
+// are scored in parallel against the instance state at the window's start, then the state advances
+// (the simulator's clock-advance step, Sec. V-A "Simulator Implementation"; admission and blocking
+// as in Sec. IV-F).  The window loop is sequential, so it lives inside ONE persistent kernel: no
+// host round trip and no launch per window.
+//
+// Layout.  The work of a window is small (window x instances triples), so it is spread thin: each
+// request is scored by LPR neighbouring lanes, each lane walking every LPR-th instance, followed by
+// a cross-lane arg-max with lowest-index tie-break (DPP row operations inside a 16-lane row,
+// ds_bpermute across rows).  Admitted load is summed with integer atomics - first in LDS per block,
+// then once per block and instance into a small ring of global accumulators - so the sums do not
+// depend on the order of arrival.  A device-wide barrier (monotone counter, bounded spin) separates
+// the windows; after it every block reads the same sums and advances its private copy of the state
+// with the same integer / binary32 operations, so all copies stay identical.
+#pragma once
+
+#include "assign_kernels.hpp"
+
+#pragma clang fp contract(off)
+
+namespace maaso {
+
+constexpr int kRing = 4;
+
+// Global scratch of the windowed kernel (zeroed by window_init_kernel before each call).
+struct WindowWs {
+  unsigned long long bar;                        // arrivals at the inter-window barrier, monotone
+  uint32_t abort_flag;                           // set when a wait gave up; every block then leaves
+  uint32_t pad;
+  uint32_t ring_n[kRing][256];                   // admitted requests per instance, window w -> w % kRing
+  unsigned long long ring_t[kRing][256];         // admitted prefill ticks per instance
+};
+
+__global__ void window_init_kernel(WindowWs* ws, unsigned long long* n_satisfied) {
+  uint32_t* p = reinterpret_cast<uint32_t*>(ws);
+  for (uint32_t i = threadIdx.x; i < sizeof(WindowWs) / 4u; i += blockDim.x) p[i] = 0u;
+  if (threadIdx.x == 0 && n_satisfied) *n_satisfied = 0ull;
+}
+
+// (slack, index) of the better of two candidates: larger slack, lower index among equals.
+__device__ __forceinline__ void take_better(float& s, int32_t& i, float os, int32_t oi) {
+  const bool take = (os > s) || (os == s && oi < i);
+  s = take ? os : s;
+  i = take ? oi : i;
+}
+
+template <int kCtrl>
+__device__ __forceinline__ void dpp_step(float& s, int32_t& i) {
+  const float os = __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), kCtrl, 0xf, 0xf, false));
+  const int32_t oi = __builtin_amdgcn_update_dpp(0, i, kCtrl, 0xf, 0xf, false);
+  take_better(s, i, os, oi);
+}
+
+// All-reduce of (slack, index) over groups of LPR consecutive lanes; every lane ends with the winner.
+template <int LPR>
+__device__ __forceinline__ void argmax_lanes(float& s, int32_t& i) {
+  if (LPR >= 2) dpp_step<0xB1>(s, i);   // quad_perm [1,0,3,2]: lane ^ 1
+  if (LPR >= 4) dpp_step<0x4E>(s, i);   // quad_perm [2,3,0,1]: lane ^ 2
+  if (LPR >= 8) dpp_step<0x141>(s, i);  // row_half_mirror: pairs the two quads of 8 lanes
+  if (LPR >= 16) dpp_step<0x140>(s, i); // row_mirror: pairs the two halves of a 16-lane row
+  if (LPR >= 32) take_better(s, i, __shfl_xor(s, 16), __shfl_xor(i, 16));
+  if (LPR >= 64) take_better(s, i, __shfl_xor(s, 32), __shfl_xor(i, 32));
+}
+
+// Device-wide barrier on a monotone counter.  Returns false if the wait gave up or another block
+// did; the caller must then leave the kernel.  Must be reached by all threads of the block.
+__device__ __forceinline__ bool grid_barrier(WindowWs* ws, unsigned long long target,
+                                             uint32_t spin_limit, uint32_t* status, int* lds_flag) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    atomicAdd(&ws->bar, 1ull);
+    bool ok = true;
+    uint32_t spins = 0;
+    while (__hip_atomic_load(&ws->bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (__hip_atomic_load(&ws->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u ||
+          spins >= spin_limit) {
+        ok = false;
+        __hip_atomic_store(&ws->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        raise_status(status, 4u);
+        break;
+      }
+      ++spins;
+      __builtin_amdgcn_s_sleep(4);
+    }
+    __threadfence();
+    *lds_flag = ok ? 1 : 0;
+  }
+  __syncthreads();
+  return *lds_flag != 0;
+}
+
+template <int LPR, bool kLat>
+__global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const AssignArgs a,
+                                                                       uint32_t window,
+                                                                       WindowWs* ws,
+                                                                       uint32_t spin_limit) {
+  __shared__ float4 recs[256];
+  __shared__ ClassRow cls[kMaxSlo];
+  __shared__ uint32_t n_blk[256];
+  __shared__ unsigned long long t_blk[256];
+  __shared__ uint32_t wave_sat[kAssignThreads / 64];
+  __shared__ int bar_ok;
+
+  const uint32_t tid = threadIdx.x;
+  const uint32_t n = min(a.n_inst[0], a.i_pad);
+  // thread j owns instance j: configuration and live state stay in its registers
+  uint32_t tp = 0, B = 1;
+  int32_t occ = 0;
+  uint64_t q = 0;
+  if (tid < n) { tp = a.tp_idx[tid]; B = a.max_batch[tid]; occ = a.occ[tid]; q = a.q_ticks[tid]; }
+  if (tid < a.n_slo) cls[tid] = ClassRow{a.d_ttft[tid], a.d_tbt[tid], a.i_ttft[tid], a.i_tbt[tid]};
+
+  constexpr uint32_t kReqPerBlock = kAssignThreads / LPR;
+  const uint32_t sl = tid % LPR;   // which slice of the instances this lane walks
+  const uint32_t rq_in_blk = tid / LPR;
+  const uint64_t R = a.n_req;
+  const uint64_t n_windows = (R + window - 1) / window;
+  uint32_t sat = 0;
+  bool alive = true;
+
+  for (uint64_t w = 0; w < n_windows; ++w) {
+    const uint64_t s0 = w * window;
+    const uint64_t e0 = (s0 + window < R) ? s0 + window : R;
+    float svc = 1.0f;
+    if (tid < n) {
+      Staged st;
+      if (stage_instance(a.tab, a.cells, a.mp, tp, B, occ, q, st)) {
+        recs[tid] = make_float4(st.a, st.p, st.tbt, st.wait);
+        svc = st.svc;
+      } else {
+        raise_status(a.status, 2u);
+        recs[tid] = make_float4(1.0f, 1.0f, 1.0f, INFINITY);
+      }
+      n_blk[tid] = 0u;
+      t_blk[tid] = 0ull;
+    }
+    if (blockIdx.x == 0) {  // recycle the accumulators that window w+2 will use
+      __hip_atomic_store(&ws->ring_n[(w + 2) % kRing][tid], 0u, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&ws->ring_t[(w + 2) % kRing][tid], 0ull, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+
+    for (uint64_t base = s0 + (uint64_t)blockIdx.x * kReqPerBlock; base < e0;
+         base += (uint64_t)gridDim.x * kReqPerBlock) {
+      const uint64_t r = base + rq_in_blk;
+      const bool live = r < e0;
+      float best = -INFINITY;
+      int32_t idx = -1;
+      float L = 0.0f, S = 0.0f;
+      Deadlines d{};
+      bool class_ok = false;
+      if (live) {
+        L = (float)a.prompt_len[r];
+        S = (float)a.out_len[r];
+        const uint32_t k = a.slo_class[r];
+        class_ok = k < a.n_slo;
+        if (class_ok) {
+          const ClassRow c = cls[k];
+          d.Dt = c.Dt; d.Db = c.Db; d.iDt = c.iDt; d.iDb = c.iDb;
+          d.De = fmaf(S, c.Db, c.Dt);
+          d.iDe = 1.0f / d.De;
+          for (uint32_t j = sl; j < n; j += LPR) {
+            const float4 rc = recs[j];
+            const Margins m = score_triple(rc.x, rc.y, rc.z, rc.w, L, S, d);
+            if (m.slack > best) { best = m.slack; idx = (int32_t)j; }
+          }
+        } else if (sl == 0) {
+          raise_status(a.status, 1u);
+        }
+      }
+      argmax_lanes<LPR>(best, idx);
+      if (live && sl == 0) {
+        float o_ttft = __builtin_nanf(""), o_tbt = o_ttft, o_e2e = o_ttft;
+        if (idx >= 0) {
+          const float4 rc = recs[idx];
+          const Margins m = score_triple(rc.x, rc.y, rc.z, rc.w, L, S, d);
+          o_ttft = m.ttft; o_tbt = rc.z; o_e2e = m.e2e;
+          if (best >= 0.0f) {  // admitted: it loads the instance; a blocked request does not
+            ++sat;
+            atomicAdd(&n_blk[idx], 1u);
+            atomicAdd(&t_blk[idx], (unsigned long long)__float2ll_rn(m.pre * 1048576.0f));
+          }
+        }
+        if (a.chosen) a.chosen[r] = idx;
+        if (a.slack) a.slack[r] = best;
+        if (kLat) {
+          if (a.ttft) a.ttft[r] = o_ttft;
+          if (a.tbt) a.tbt[r] = o_tbt;
+          if (a.e2e) a.e2e[r] = o_e2e;
+        }
+      }
+    }
+    __syncthreads();
+    if (tid < n && n_blk[tid] != 0u) {
+      atomicAdd(&ws->ring_n[w % kRing][tid], n_blk[tid]);
+      atomicAdd(&ws->ring_t[w % kRing][tid], t_blk[tid]);
+    }
+
+    if (!grid_barrier(ws, (w + 1) * (unsigned long long)gridDim.x, spin_limit, a.status, &bar_ok)) {
+      alive = false;
+      break;
+    }
+
+    if (tid < n) {
+      occ += (int32_t)__hip_atomic_load(&ws->ring_n[w % kRing][tid], __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);
+      q += __hip_atomic_load(&ws->ring_t[w % kRing][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (e0 < R) {  // time passes until the next window opens
+        const uint32_t delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
+        q -= (q < (uint64_t)delta) ? q : (uint64_t)delta;
+        const int32_t run = min(occ, (int32_t)B);
+        const float x = ((float)run * ((float)delta * 0x1p-20f)) / svc;
+        const int32_t done = min(occ, (int32_t)floorf(fminf(x, 2147483520.0f)));
+        occ -= done;
+      }
+    }
+  }
+
+  if (alive && blockIdx.x == 0 && tid < n) { a.occ[tid] = occ; a.q_ticks[tid] = q; }
+  for (int dlt = 32; dlt >= 1; dlt >>= 1) sat += __shfl_xor(sat, dlt);
+  if ((tid & 63u) == 0u) wave_sat[tid >> 6] = sat;
+  __syncthreads();
+  if (tid == 0 && a.n_satisfied) {
+    uint32_t t = 0;
+    for (int wv = 0; wv < kAssignThreads / 64; ++wv) t += wave_sat[wv];
+    if (t) atomicAdd(a.n_satisfied, (unsigned long long)t);
+  }
+}
+
+}  // namespace maaso

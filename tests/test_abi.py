@@ -1,0 +1,107 @@
+"""CPU checks of the C-ABI library: it loads, exports what the header declares, and its host-side
+validation answers without a GPU.  No compute entry point is launched here."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+from paper_2509_06362_amd import binding, workloads as W
+
+ROOT = Path(__file__).resolve().parent.parent
+HEADER = ROOT / "include" / "maaso.h"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not binding.LIB_PATH.exists():
+        from paper_2509_06362_amd import build
+        build.build_library()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    return sorted(set(re.findall(r"\b(maaso_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"maaso_profile_tables_load", "maaso_score_assign", "maaso_placement_sweep"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in maaso.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_struct_layouts_match_the_header():
+    # sizes follow from the C declaration order on LP64
+    assert C.sizeof(binding.ProfileDesc) == 64
+    assert C.sizeof(binding.Requests) == 40
+    assert C.sizeof(binding.Placements) == 48
+    assert C.sizeof(binding.Params) == 16
+    assert C.sizeof(binding.AssignOut) == 48
+
+
+def test_strerror(lib):
+    assert binding.strerror(0) == "ok"
+    for s in range(-6, 0):
+        assert binding.strerror(s) not in ("ok", "unknown status")
+    assert binding.strerror(-99) == "unknown status"
+
+
+def _load(w, **over):
+    kw = dict(n_tp=w.n_tp, b_cap=w.b_cap, prefill_a=w.prefill_a, prefill_p=w.prefill_p, tbt=w.tbt,
+              d_ttft=w.d_ttft, d_tbt=w.d_tbt, tp_degree=w.tp_degree, device=0)
+    kw.update(over)
+    return binding.maaso_profile_tables_load(**kw)
+
+
+def test_load_validates_on_the_host(lib):
+    w = W.config0(n_req=8)
+    out = C.c_void_p(123)
+    assert lib.maaso_profile_tables_load(None, 0, C.byref(out)) == -1 and out.value is None
+    bad = w.tbt.copy(); bad[1, 3] = -1.0
+    with pytest.raises(binding.MaasoError) as e:
+        _load(w, tbt=bad)
+    assert e.value.status == -3
+    bad = w.prefill_p.copy(); bad[0, 1] = np.inf
+    with pytest.raises(binding.MaasoError) as e:
+        _load(w, prefill_p=bad)
+    assert e.value.status == -3
+    with pytest.raises(binding.MaasoError) as e:
+        _load(w, d_ttft=np.array([0.5, 0.0, 1.0], np.float32))
+    assert e.value.status == -3
+    with pytest.raises(binding.MaasoError) as e:
+        _load(w, d_ttft=np.full(17, 1.0, np.float32), d_tbt=np.full(17, 0.1, np.float32))
+    assert e.value.status == -2
+    big = np.ones((4, 2000), np.float32)
+    with pytest.raises(binding.MaasoError) as e:
+        _load(w, b_cap=1999, prefill_a=big, prefill_p=big, tbt=big)
+    assert e.value.status == -2
+
+
+def test_null_context_is_rejected(lib):
+    assert lib.maaso_score_assign(None, None, None, None, None, None) == -1
+    assert lib.maaso_placement_sweep(None, None, None, None, None, None, None, None) == -1
+    assert lib.maaso_ctx_device_status(None, None) == -1
+    assert lib.maaso_ctx_set_launch_shape(None, 0, 0, 0) == -1
+    assert lib.maaso_ctx_set_wait_limit(None, 1) == -1
+    assert lib.maaso_ctx_kernel_timing(None, 1) == -1
+    assert lib.maaso_ctx_kernel_elapsed(None, None, None) == -1
+    lib.maaso_ctx_destroy(None)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", tmp_path / "libmaaso.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load_library()
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = ROOT / "paper_2509_06362_amd"
+    for f in list(pkg.rglob("*.py")) + list(pkg.rglob("*.hip")) + list(pkg.rglob("*.hpp")):
+        text = f.read_text()
+        assert "import oracle" not in text and "from oracle" not in text, f
+        assert "maaso_oracle" not in text, f

@@ -1,0 +1,331 @@
+"""Parity of the HIP path (through the C-ABI) with the CPU oracle, element by element.
+
+Bar: integer outputs (chosen instance, satisfied counts, best candidate, final occupancy and queue
+ticks) bit-exact; binary32 slack and latencies within 1e-5 relative - in practice they are asserted
+bit-identical, because both sides perform the same sequence of IEEE operations.  A differing chosen
+instance would be tolerated only where the oracle's slacks of the two instances differ by less than
+1e-5 relative (check_assign reports how many such requests there are; none are expected).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_2509_06362_amd import binding, workloads as W  # noqa: E402
+
+REL = 1e-5
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' on CPU-only machines)")
+    binding.load_library()
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def check_sweep(w, shapes=((0, 0),), sampled=None, threshold=False):
+    """GPU sweep vs the triple oracle (all candidates, or `sampled` ones) and optionally vs the
+    threshold-count route on all candidates."""
+    dw = binding.DeviceWorkload(w)
+    try:
+        ref = None
+        if sampled is None:
+            ref = oracle.placement_sweep(w)
+        thr = oracle.threshold_sweep(w) if threshold else None
+        for q, chunk in shapes:
+            binding.maaso_ctx_set_launch_shape(dw.ctx, q, chunk, 0)
+            print(f"sweep {w.name} C={w.n_cand} I={w.i_pad} R={w.n_req} q={q} chunk={chunk}", flush=True)
+            cnt, ratio, best = dw.sweep()
+            torch.cuda.synchronize()
+            cnt, ratio, best = u32(cnt), ratio.cpu().numpy(), int(u32(best)[0])
+            if ref is not None:
+                assert np.array_equal(cnt, ref["sat_count"])
+                assert np.array_equal(ratio, ref["sat_ratio"])
+                assert best == ref["best_cand"]
+            if thr is not None:
+                assert np.array_equal(cnt, thr)
+                assert best == int(np.argmax(thr))
+                if w.n_req:
+                    assert np.array_equal(ratio, (thr.astype(np.float32) / np.float32(w.n_req)))
+            if sampled is not None:
+                for c in sampled:
+                    one = oracle.placement_sweep(w, c, c + 1)
+                    assert cnt[c] == one["sat_count"][c], f"candidate {c}"
+                    assert ratio[c] == one["sat_ratio"][c]
+            assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        return cnt
+    finally:
+        dw.close()
+
+
+def check_assign(w, cand=0, window=None, window_blocks=0, latencies=True, tbt_mode=None, ref=None):
+    dw = binding.DeviceWorkload(w)
+    try:
+        binding.maaso_ctx_set_launch_shape(dw.ctx, 0, 0, window_blocks)
+        print(f"assign {w.name} I={w.i_pad} R={w.n_req} window={window} blocks={window_blocks}", flush=True)
+        got = dw.assign(cand=cand, window=window, latencies=latencies, tbt_mode=tbt_mode)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        if ref is None:
+            ref = oracle.score_assign(w, cand=cand, window=window, tbt_mode=tbt_mode)
+        chosen = got["chosen"].cpu().numpy()
+        slack = got["slack"].cpu().numpy()
+        diff = np.nonzero(chosen != ref["chosen"])[0]
+        if diff.size:  # tolerated only for near-ties; with identical arithmetic there are none
+            a, b = slack[diff], ref["slack"][diff]
+            assert (np.abs(a - b) <= REL * np.maximum(1.0, np.abs(b))).all(), diff[:10]
+            pytest.fail(f"{diff.size} requests chose another instance within tolerance - "
+                        "the two sides are expected to agree exactly")
+        assert np.array_equal(slack, ref["slack"])
+        fin = np.isfinite(ref["slack"])
+        assert np.allclose(slack[fin], ref["slack"][fin], rtol=REL, atol=0)
+        if latencies:
+            for k in ("ttft", "tbt", "e2e"):
+                assert np.array_equal(got[k].cpu().numpy(), ref[k], equal_nan=True), k
+        assert int(got["n_satisfied"].item()) == ref["n_satisfied"]
+        assert np.array_equal(got["occ"].cpu().numpy()[0], ref["occ"])
+        assert np.array_equal(got["q_ticks"].cpu().numpy()[0].view(np.uint64), ref["q_ticks"])
+        near = int((np.abs(ref["slack"][fin]) < REL).sum())
+        print(f"  ok; requests within {REL} of a deadline: {near}", flush=True)
+        return got
+    finally:
+        dw.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# placer sweep
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed,n_cand,i_pad,n_req,n_slo", [
+    (1, 37, 16, 3000, 3),       # ragged n_inst incl. empty candidates, ragged request tail
+    (2, 200, 32, 5000, 3),
+    (3, 9, 1, 700, 1),          # one slot, one class
+    (4, 70, 48, 2500, 5),       # i_pad that does not divide the block
+    (5, 24, 128, 1500, 8),
+    (6, 10, 256, 900, 16),      # the limits: 256 slots, 16 classes
+    (7, 130, 7, 64, 2),         # fewer requests than one wavefront tile
+])
+def test_sweep_small_irregular(seed, n_cand, i_pad, n_req, n_slo):
+    w = W.random_small(seed, n_cand, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
+    cnt = check_sweep(w, shapes=((0, 0), (2, 8), (4, 33), (8, 64), (16, 1000)), threshold=True)
+    assert len(np.unique(cnt)) > 1
+
+
+def test_sweep_edge_cases():
+    w = W.random_small(11, 5, 8, 300)
+    check_sweep(W.replace(w, n_inst=np.zeros(5, np.uint32)))                 # nothing can be served
+    check_sweep(w.with_requests(0, 0))                                       # no requests
+    check_sweep(w.with_requests(0, 1))                                       # one request
+    check_sweep(w.with_candidates(2, 3))                                     # one candidate
+    one_class = W.replace(w, slo_class=np.full(300, 2, np.uint8))            # two classes unused
+    check_sweep(one_class, threshold=True)
+    worst = W.replace(w, tbt_mode=1)
+    check_sweep(worst, threshold=True)
+
+
+def test_sweep_is_deterministic_and_leaves_inputs_alone():
+    w = W.stressed(W.config1(n_cand=300, n_req=6000), seed=5)
+    dw = binding.DeviceWorkload(w)
+    a = [t.clone() for t in dw.sweep()]
+    b = dw.sweep()
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    assert np.array_equal(dw.occ.cpu().numpy(), w.occ)
+    assert np.array_equal(dw.q_ticks.cpu().numpy().view(np.uint64), w.q_ticks)
+    dw.close()
+
+
+@pytest.mark.parametrize("make", [
+    lambda: W.config0(),
+    lambda: W.config1(n_cand=512, n_req=8192),
+    lambda: W.config3(n_cand=512, n_req=4000),
+    lambda: W.config4(n_cand=48, n_req=6000),
+])
+def test_sweep_config_shapes_reduced(make):
+    w = make()
+    check_sweep(w, threshold=True)
+    cnt = check_sweep(W.stressed(w, seed=7), threshold=True)
+    assert w.n_cand == 1 or len(np.unique(cnt)) > 1
+
+
+@pytest.mark.parametrize("cfg,n_sample", [(1, 24), (3, 24), (4, 3)])
+def test_sweep_full_size(cfg, n_sample):
+    """Full configuration sizes in the default launch shape: all candidates against the threshold-
+    count route, sampled candidates against the triple oracle; plain and stressed variants."""
+    w = W.CONFIGS[cfg]()
+    rng = np.random.default_rng(cfg)
+    for v in (w, W.stressed(w, seed=cfg)):
+        sampled = sorted(rng.choice(v.n_cand, size=n_sample, replace=False).tolist())
+        cnt = check_sweep(v, sampled=sampled, threshold=True)
+        assert cnt.max() <= v.n_req
+    assert len(np.unique(cnt)) > 10
+
+
+# ------------------------------------------------------------------------------------------------
+# distributor, static
+# ------------------------------------------------------------------------------------------------
+
+def test_assign_config0_full():
+    w = W.config0()
+    check_assign(w)
+    check_assign(W.stressed(w, seed=2))
+    check_assign(w, tbt_mode=1)
+
+
+@pytest.mark.parametrize("seed,i_pad,n_req,n_slo", [(21, 12, 5000, 3), (22, 1, 300, 1),
+                                                    (23, 256, 1200, 16), (24, 64, 70000, 8),
+                                                    (25, 33, 257, 2)])
+def test_assign_static_irregular(seed, i_pad, n_req, n_slo):
+    w = W.random_small(seed, 3, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
+    w = W.replace(w, n_inst=np.array([i_pad, max(1, i_pad // 2), 0], np.uint32))
+    for cand in range(3):
+        check_assign(w, cand=cand, window=0)
+    check_assign(w, cand=0, window=0, latencies=False)
+
+
+def test_assign_empty_and_identical_instances():
+    w = W.random_small(31, 1, 6, 400)
+    w = W.replace(w, n_inst=np.array([6], np.uint32))
+    check_assign(w.with_requests(0, 0), window=0)
+    for arr in (w.tp_idx, w.max_batch, w.occ, w.q_ticks):
+        arr[0, 1:] = arr[0, 0]
+    got = check_assign(w, window=0)
+    assert (got["chosen"].cpu().numpy() == 0).all()            # lowest index among equal slacks
+
+
+def test_assign_streaming_shape_sampled():
+    """The bandwidth-bound shape (4 instances, long stream) at 2^22 requests."""
+    w = W.streaming_shape(n_req=1 << 22)
+    check_assign(w, window=0)
+
+
+# ------------------------------------------------------------------------------------------------
+# distributor, windowed
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n_req,window,blocks", [
+    (8192, 512, 0), (8192, 512, 1), (8192, 512, 8), (8192, 512, 256),
+    (5000, 384, 0),        # ragged last window
+    (300, 1, 4),           # one request per window
+    (3000, 4096, 0),       # a single window larger than the stream
+    (6000, 3000, 16),      # exactly two windows
+])
+def test_assign_windowed_config2_reduced(n_req, window, blocks):
+    w = W.config2(n_req=n_req, window=window)
+    got = check_assign(w, window=window, window_blocks=blocks)
+    assert (got["occ"].cpu().numpy() >= 0).all()
+
+
+@pytest.mark.parametrize("seed,i_pad,n_inst,window,blocks", [
+    (41, 8, 5, 64, 2), (42, 100, 77, 200, 32), (43, 256, 256, 128, 64), (44, 3, 3, 1000, 0),
+    (45, 16, 0, 50, 4),
+])
+def test_assign_windowed_irregular(seed, i_pad, n_inst, window, blocks):
+    w = W.random_small(seed, 1, i_pad, 4000, n_slo=4, pen_kappa=0.25)
+    w = W.replace(w, n_inst=np.array([n_inst], np.uint32))
+    check_assign(w, window=window, window_blocks=blocks)
+
+
+def test_windowed_with_one_window_matches_static_outputs():
+    w = W.config2(n_req=4096, window=4096)
+    a = check_assign(w, window=0)
+    b = check_assign(w, window=4096)
+    assert torch.equal(a["chosen"], b["chosen"]) and torch.equal(a["slack"], b["slack"])
+
+
+def test_assign_windowed_config2_full():
+    """The online-distributor configuration at full size (2^22 requests, 1024 windows of 4096)."""
+    w = W.config2()
+    ref = oracle.score_assign(w, latencies=False)
+    for k in ("ttft", "tbt", "e2e"):
+        ref.pop(k)
+    check_assign(w, window=w.window, latencies=False, ref=ref)
+
+
+# ------------------------------------------------------------------------------------------------
+# argument and precondition handling
+# ------------------------------------------------------------------------------------------------
+
+def test_host_side_argument_errors():
+    w = W.random_small(51, 2, 8, 100)
+    dw = binding.DeviceWorkload(w)
+    dev = dw.prompt_len.device
+    cnt = torch.empty(2, dtype=torch.int32, device=dev)
+    base = dict(n_cand=2, i_pad=8, n_inst=dw.n_inst, tp_idx=dw.tp_idx, max_batch=dw.max_batch,
+                occ=dw.occ, q_ticks=dw.q_ticks, **dw.request_args(), **dw.param_args())
+
+    def status(fn, **kw):
+        with pytest.raises(binding.MaasoError) as e:
+            fn(dw.ctx, **{**base, **kw})
+        return e.value.status
+
+    sweep, assign = binding.maaso_placement_sweep, binding.maaso_score_assign
+    assert status(sweep, sat_count=None) == -1
+    assert status(sweep, sat_count=cnt, window=4) == -1
+    assert status(sweep, sat_count=cnt, i_pad=257) == -2
+    assert status(sweep, sat_count=cnt, i_pad=0) == -2
+    assert status(sweep, sat_count=cnt, s_bar=0.0) == -1
+    assert status(sweep, sat_count=cnt, pen_kappa=-1.0) == -1
+    assert status(sweep, sat_count=cnt, tbt_mode=2) == -1
+    assert status(sweep, sat_count=cnt, n_inst=None) == -1
+    assert status(sweep, sat_count=cnt, prompt_len=None) == -1
+    n_sat = torch.empty(1, dtype=torch.int64, device=dev)
+    assert status(assign, n_satisfied=n_sat) == -1                      # n_cand must be 1
+    assert status(assign, n_cand=1) == -1                               # no output at all
+    assert status(assign, n_cand=1, n_satisfied=n_sat, window=16) == -1  # windowed without arrivals
+    dw.close()
+
+
+def test_out_of_range_elements_are_flagged_not_followed():
+    w = W.random_small(52, 4, 8, 500)
+    w = W.replace(w, n_inst=np.full(4, 8, np.uint32))
+    bad_cls = w.slo_class.copy(); bad_cls[[3, 77, 400]] = 9
+    bad_tp = w.tp_idx.copy(); bad_tp[1, 2] = 200
+    bad_b = w.max_batch.copy(); bad_b[2, 0] = 0; bad_b[2, 5] = 60000
+    wb = W.replace(w, slo_class=bad_cls, tp_idx=bad_tp, max_batch=bad_b)
+    dw = binding.DeviceWorkload(wb)
+    cnt, _, _ = dw.sweep()
+    torch.cuda.synchronize()
+    assert binding.maaso_ctx_device_status(dw.ctx) == 3
+    assert binding.maaso_ctx_device_status(dw.ctx) == 0                    # cleared by the read
+    # the flagged elements count as absent: same result as removing them
+    keep = np.ones(500, bool); keep[[3, 77, 400]] = False
+    ref_w = W.replace(w, prompt_len=w.prompt_len[keep].copy(), out_len=w.out_len[keep].copy(),
+                      slo_class=w.slo_class[keep].copy(), arrival_ticks=None)
+    ref = oracle.placement_sweep(ref_w)["sat_count"]
+    got = u32(cnt)
+    assert got[0] == ref[0] and got[3] == ref[3]
+    got_a = dw.assign(cand=1, window=0)
+    torch.cuda.synchronize()
+    assert binding.maaso_ctx_device_status(dw.ctx) == 3
+    ch = got_a["chosen"].cpu().numpy()
+    assert (ch[[3, 77, 400]] == -1).all() and (ch != 2).all()
+    dw.close()
+
+
+def test_inter_window_wait_gives_up_cleanly():
+    """A spin limit of zero makes the first block to reach a window boundary give up: the kernel
+    must end by itself and the status must say so."""
+    w = W.config2(n_req=8192, window=256)
+    dw = binding.DeviceWorkload(w)
+    binding.maaso_ctx_set_launch_shape(dw.ctx, 0, 0, 64)
+    binding.maaso_ctx_set_wait_limit(dw.ctx, 0)
+    dw.assign(window=256)
+    with pytest.raises(binding.MaasoError) as e:
+        binding.maaso_ctx_device_status(dw.ctx)
+    assert e.value.status == -6
+    binding.maaso_ctx_set_wait_limit(dw.ctx, 1 << 22)
+    got = dw.assign(window=256)                      # the context is usable again
+    torch.cuda.synchronize()
+    assert binding.maaso_ctx_device_status(dw.ctx) == 0
+    ref = oracle.score_assign(w, window=256)
+    assert np.array_equal(got["chosen"].cpu().numpy(), ref["chosen"])
+    dw.close()
