@@ -114,8 +114,12 @@ def check_assign(w, cand=0, window=None, window_blocks=0, latencies=True, tbt_mo
 ])
 def test_sweep_small_irregular(seed, n_cand, i_pad, n_req, n_slo):
     w = W.random_small(seed, n_cand, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
-    cnt = check_sweep(w, shapes=((0, 0), (2, 8), (4, 33), (8, 64), (16, 1000)), threshold=True)
-    assert len(np.unique(cnt)) > 1
+    spread = 0
+    for v in (w, W.stressed(w, seed=seed, deadline_scale=0.25),
+              W.stressed(w, seed=seed, deadline_scale=0.03)):
+        cnt = check_sweep(v, shapes=((0, 0), (2, 8), (4, 33), (8, 64), (16, 1000)), threshold=True)
+        spread = max(spread, len(np.unique(cnt)))
+    assert spread > 1, "no variant discriminates between candidates"
 
 
 def test_sweep_edge_cases():
