@@ -100,7 +100,8 @@ def main() -> int:
     ap.add_argument("--cpu-triples", type=float, default=1.0e9,
                     help="size of the oracle's timed sample, in triples")
     ap.add_argument("--sweep-q", type=int, default=0)
-    ap.add_argument("--sweep-chunk", type=int, default=0)
+    ap.add_argument("--sweep-group", type=int, default=0)
+    ap.add_argument("--sweep-bq", type=int, default=0)
     ap.add_argument("--window-blocks", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -119,7 +120,8 @@ def main() -> int:
     w = make_workload(args.workload)
     kind = "sweep" if w.n_cand > 1 else "assign"
     dw = binding.DeviceWorkload(w)
-    binding.maaso_ctx_set_launch_shape(dw.ctx, args.sweep_q, args.sweep_chunk, args.window_blocks)
+    binding.maaso_ctx_set_launch_shape(dw.ctx, args.sweep_q, args.sweep_group, args.sweep_bq,
+                                       args.window_blocks)
     dev = dw.prompt_len.device
     stream = torch.cuda.current_stream()
 

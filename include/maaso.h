@@ -94,11 +94,13 @@ const char* maaso_strerror(int status);
 
 /* Performance knobs; they never change a result.  0 selects the library's own choice.
  *   sweep_requests_per_lane: requests a lane of the sweep kernel keeps in registers (0, 2, 4, 8, 16);
- *   sweep_chunk: candidates one block of the sweep kernel walks;
+ *     a block of the sweep owns 256 times as many requests of one SLO class;
+ *   sweep_group: candidates per work item of the sweep kernel (clamped to what fits its LDS lists);
+ *   sweep_blocks_per_queue: persistent blocks serving each (request tile, XCD) work queue;
  *   window_blocks: blocks of the windowed distributor's persistent kernel (at most one per compute
  *   unit is used).  Errors: INVALID_ARG. */
-int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane, uint32_t sweep_chunk,
-                               uint32_t window_blocks);
+int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane, uint32_t sweep_group,
+                               uint32_t sweep_blocks_per_queue, uint32_t window_blocks);
 
 /* Number of polls after which a block of the windowed distributor stops waiting for the other
  * blocks at a window boundary, raises MAASO_DEV_WAIT_TIMEOUT and leaves the kernel (all other blocks

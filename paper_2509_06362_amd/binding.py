@@ -78,7 +78,8 @@ def load_library() -> C.CDLL:
         lib.maaso_ctx_destroy.argtypes = [C.c_void_p]
         lib.maaso_ctx_destroy.restype = None
         lib.maaso_ctx_device_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint32)]
-        lib.maaso_ctx_set_launch_shape.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32]
+        lib.maaso_ctx_set_launch_shape.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
+                                                   C.c_uint32]
         lib.maaso_ctx_set_wait_limit.argtypes = [C.c_void_p, C.c_uint32]
         lib.maaso_ctx_kernel_timing.argtypes = [C.c_void_p, C.c_int]
         lib.maaso_ctx_kernel_elapsed.argtypes = [C.c_void_p, C.POINTER(C.c_float),
@@ -172,10 +173,11 @@ def maaso_ctx_device_status(ctx: Context) -> int:
     return int(bits.value)
 
 
-def maaso_ctx_set_launch_shape(ctx: Context, sweep_requests_per_lane=0, sweep_chunk=0,
-                               window_blocks=0) -> None:
+def maaso_ctx_set_launch_shape(ctx: Context, sweep_requests_per_lane=0, sweep_group=0,
+                               sweep_blocks_per_queue=0, window_blocks=0) -> None:
     _check(load_library().maaso_ctx_set_launch_shape(ctx.handle, sweep_requests_per_lane,
-                                                     sweep_chunk, window_blocks),
+                                                     sweep_group, sweep_blocks_per_queue,
+                                                     window_blocks),
            "maaso_ctx_set_launch_shape")
 
 

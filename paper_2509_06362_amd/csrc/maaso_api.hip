@@ -31,7 +31,9 @@ struct maaso_ctx {
   void* ws;             // device workspace, grow-only
   size_t ws_bytes;
   uint32_t sweep_q;      // 0 = automatic
-  uint32_t sweep_chunk;  // 0 = automatic
+  uint32_t sweep_group;  // 0 = automatic
+  uint32_t sweep_blocks_per_queue;  // 0 = automatic
+  bool counters_dirty;   // class counters may be non-zero (a call failed between its launches)
   uint32_t window_blocks;  // 0 = automatic
   uint32_t spin_limit;     // polls of the inter-window barrier before a block gives up
   int n_cu;
@@ -116,8 +118,8 @@ ModelParams model_params(const maaso_ctx* ctx, const maaso_params* prm) {
 }
 
 template <int Q>
-int launch_sweep(const SweepArgs& a, uint32_t blocks, size_t lds, hipStream_t s) {
-  hipLaunchKernelGGL(sweep_kernel<Q>, dim3(blocks), dim3(kSweepThreads), lds, s, a);
+int launch_sweep(const SweepArgs& a, uint32_t blocks, hipStream_t s) {
+  hipLaunchKernelGGL(sweep_kernel<Q>, dim3(blocks), dim3(kSweepThreads), 0, s, a);
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
 
@@ -273,12 +275,14 @@ int maaso_ctx_device_status(maaso_ctx* ctx, uint32_t* bits) {
 }
 
 int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane,
-                               uint32_t sweep_chunk, uint32_t window_blocks) {
+                               uint32_t sweep_group, uint32_t sweep_blocks_per_queue,
+                               uint32_t window_blocks) {
   if (!ctx) return MAASO_E_INVALID_ARG;
   const uint32_t q = sweep_requests_per_lane;
   if (q != 0 && q != 2 && q != 4 && q != 8 && q != 16) return MAASO_E_INVALID_ARG;
   ctx->sweep_q = q;
-  ctx->sweep_chunk = sweep_chunk;
+  ctx->sweep_group = sweep_group;
+  ctx->sweep_blocks_per_queue = sweep_blocks_per_queue;
   ctx->window_blocks = window_blocks;
   return MAASO_OK;
 }
@@ -295,86 +299,108 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
 
   const uint32_t C = pl->n_cand, I = pl->i_pad, K = ctx->n_slo, R = rq->n_req;
 
-  // launch shape: Q requests per lane, G candidates staged together, `chunk` candidates per block
+  // Launch shape.  Q requests per lane (a block owns 256*Q requests of one class); G candidates per
+  // work item; bq persistent blocks per (request tile, XCD) queue.
   uint32_t Q = ctx->sweep_q;
-  if (Q == 0) Q = R >= (1u << 15) ? 8u : (R >= (1u << 13) ? 4u : 2u);
-  // LDS: tables + two buffers of G candidates x 4 class slots x I records of 16 B + list lengths;
-  // with G * I <= 256 and the table limit this stays under 64 KiB.
-  const size_t tab_bytes = ((size_t)3 * ctx->cells * 4 + 15) & ~size_t(15);
-  uint32_t G = kSweepThreads / I;
-  if (G == 0) G = 1;
-  const size_t lds = tab_bytes + (size_t)2 * G * kSweepWaves * I * 16 + (size_t)3 * G * kSweepWaves * 4;
-  if (lds > 64u * 1024u) return MAASO_E_SHAPE;
-
-  const uint32_t tile = 64u * Q;
-  const uint64_t max_tiles = ((uint64_t)R + tile - 1) / tile + K;
-  const uint32_t n_req_blocks = (uint32_t)((max_tiles + 3) / 4);
-  uint32_t chunk = ctx->sweep_chunk;
-  if (chunk == 0) {
-    // aim at several blocks per compute unit, but keep at least 32 candidates per block so that the
-    // table and request loads are amortised
-    const uint64_t target_blocks = (uint64_t)ctx->n_cu * 16u;
-    uint64_t want_chunks = target_blocks / n_req_blocks;
-    if (want_chunks < 1) want_chunks = 1;
-    chunk = (uint32_t)(((uint64_t)C + want_chunks - 1) / want_chunks);
-    if (chunk < 32u) chunk = 32u;
+  if (Q == 0) Q = R >= (1u << 14) ? 8u : (R >= (1u << 12) ? 4u : 2u);
+  uint32_t G = (uint32_t)kGroupSlots / I;
+  if (G > (uint32_t)kMaxGroup) G = kMaxGroup;
+  if (ctx->sweep_group != 0 && ctx->sweep_group < G) G = ctx->sweep_group;
+  const uint32_t n_items = (C + G - 1) / G;
+  const uint32_t tile = (uint32_t)kSweepThreads * Q;
+  const uint32_t nrb_max = (uint32_t)(((uint64_t)R + tile - 1) / tile) + K;  // >= tiles that exist
+  uint32_t bq = ctx->sweep_blocks_per_queue;
+  if (bq == 0) {
+    bq = ((uint32_t)ctx->n_cu * 8u + 4u * nrb_max) / (8u * nrb_max);  // about 8 blocks per compute unit
+    if (bq == 0) bq = 1;
   }
-  chunk = ((chunk + G - 1) / G) * G;
-  const uint32_t n_chunks = (C + chunk - 1) / chunk;
-  const uint64_t blocks64 = (uint64_t)8 * ((n_chunks + 7) / 8) * n_req_blocks;
+  const uint32_t per_queue = (n_items + 7u) / 8u;
+  if (bq > per_queue) bq = per_queue ? per_queue : 1u;
+  const uint64_t blocks64 = (uint64_t)8 * nrb_max * bq;
   if (blocks64 > 0x7fffffffull) return MAASO_E_SHAPE;
 
-  rc = ensure_workspace(ctx, (size_t)K * (R ? R : 1u) * sizeof(float));
+  // workspace: class-bucketed prompt lengths | staged records | queue heads
+  auto up256 = [](size_t x) { return (x + 255) & ~size_t(255); };
+  const size_t lbuf_bytes = up256((size_t)K * (R ? R : 1u) * sizeof(float));
+  const size_t recs_bytes = up256((size_t)C * I * sizeof(float4));
+  const size_t queue_bytes = up256((size_t)nrb_max * 8u * sizeof(uint32_t));
+  rc = ensure_workspace(ctx, lbuf_bytes + recs_bytes + queue_bytes);
   if (rc != MAASO_OK) return rc;
-  float* lbuf = static_cast<float*>(ctx->ws);
+  unsigned char* wsb = static_cast<unsigned char*>(ctx->ws);
+  float* lbuf = reinterpret_cast<float*>(wsb);
+  float4* recs = reinterpret_cast<float4*>(wsb + lbuf_bytes);
+  uint32_t* queues = reinterpret_cast<uint32_t*>(wsb + lbuf_bytes + recs_bytes);
 
-  const uint32_t n_init = C > kMaxSlo ? C : kMaxSlo;
-  hipLaunchKernelGGL(sweep_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, sat_count, C,
-                     ctx->cls_count, (uint32_t)kMaxSlo);
-  if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-  if (R != 0) {
-    hipLaunchKernelGGL(bucket_requests_kernel, dim3((R + 1023) / 1024), dim3(256), 0, s,
-                       rq->prompt_len, rq->slo_class, R, K, lbuf, ctx->cls_count, ctx->status);
+  if (ctx->counters_dirty) {  // an earlier call failed between its launches
+    if (!hip_ok(hipMemsetAsync(ctx->cls_count, 0, kMaxSlo * sizeof(uint32_t), s))) return MAASO_E_HIP;
+    ctx->counters_dirty = false;
+  }
+  ctx->counters_dirty = true;
+  {
+    PrepArgs p;
+    p.prompt_len = rq->prompt_len;
+    p.slo_class = rq->slo_class;
+    p.n_req = R;
+    p.n_slo = K;
+    p.lbuf = lbuf;
+    p.cls_count = ctx->cls_count;
+    p.n_bucket_blocks = (uint32_t)(((uint64_t)R + kBucketPerBlock - 1) / kBucketPerBlock);
+    p.tab = ctx->tab;
+    p.cells = ctx->cells;
+    p.mp = model_params(ctx, prm);
+    p.n_cand = C;
+    p.i_pad = I;
+    p.n_inst = pl->n_inst;
+    p.tp_idx = pl->tp_idx;
+    p.max_batch = pl->max_batch;
+    p.occ = pl->occ;
+    p.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
+    p.recs = recs;
+    p.sat_count = sat_count;
+    p.queues = queues;
+    p.n_queues = nrb_max * 8u;
+    p.status = ctx->status;
+    const uint64_t n_stage = ((uint64_t)C * I + kStageSlotsPerBlock - 1) / kStageSlotsPerBlock;
+    const uint64_t n_prep = (uint64_t)p.n_bucket_blocks + n_stage;
+    if (n_prep > 0x7fffffffull) return MAASO_E_SHAPE;
+    size_t lds = (size_t)3 * ctx->cells * sizeof(float);
+    if (lds < 2 * kMaxSlo * sizeof(uint32_t)) lds = 2 * kMaxSlo * sizeof(uint32_t);
+    hipLaunchKernelGGL(sweep_prep_kernel, dim3((uint32_t)n_prep), dim3(256), lds, s, p);
     if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-
+  }
+  if (R != 0) {
     SweepArgs a;
-    a.tab = ctx->tab;
-    a.cells = ctx->cells;
-    a.mp = model_params(ctx, prm);
     a.n_slo = K;
     std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
     std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
     a.n_cand = C;
     a.i_pad = I;
-    a.n_inst = pl->n_inst;
-    a.tp_idx = pl->tp_idx;
-    a.max_batch = pl->max_batch;
-    a.occ = pl->occ;
-    a.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
+    a.recs = recs;
     a.lbuf = lbuf;
     a.cls_count = ctx->cls_count;
     a.n_req = R;
     a.group = G;
-    a.chunk = chunk;
-    a.n_req_blocks = n_req_blocks;
-    a.n_chunks = n_chunks;
+    a.n_items = n_items;
+    a.nrb_max = nrb_max;
+    a.queues = queues;
     a.sat_count = sat_count;
-    a.status = ctx->status;
     const uint32_t blocks = (uint32_t)blocks64;
     {
       TimedRegion timed(ctx, s);
       switch (Q) {
-        case 2: rc = launch_sweep<2>(a, blocks, lds, s); break;
-        case 4: rc = launch_sweep<4>(a, blocks, lds, s); break;
-        case 8: rc = launch_sweep<8>(a, blocks, lds, s); break;
-        default: rc = launch_sweep<16>(a, blocks, lds, s); break;
+        case 2: rc = launch_sweep<2>(a, blocks, s); break;
+        case 4: rc = launch_sweep<4>(a, blocks, s); break;
+        case 8: rc = launch_sweep<8>(a, blocks, s); break;
+        default: rc = launch_sweep<16>(a, blocks, s); break;
       }
     }
     if (rc != MAASO_OK) return rc;
   }
   hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
-                     best_cand);
-  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+                     best_cand, ctx->cls_count);
+  if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+  ctx->counters_dirty = false;
+  return MAASO_OK;
 }
 
 int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,

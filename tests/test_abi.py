@@ -85,7 +85,7 @@ def test_null_context_is_rejected(lib):
     assert lib.maaso_score_assign(None, None, None, None, None, None) == -1
     assert lib.maaso_placement_sweep(None, None, None, None, None, None, None, None) == -1
     assert lib.maaso_ctx_device_status(None, None) == -1
-    assert lib.maaso_ctx_set_launch_shape(None, 0, 0, 0) == -1
+    assert lib.maaso_ctx_set_launch_shape(None, 0, 0, 0, 0) == -1
     assert lib.maaso_ctx_set_wait_limit(None, 1) == -1
     assert lib.maaso_ctx_kernel_timing(None, 1) == -1
     assert lib.maaso_ctx_kernel_elapsed(None, None, None) == -1

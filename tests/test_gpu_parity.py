@@ -30,7 +30,7 @@ def u32(t):
     return t.cpu().numpy().view(np.uint32)
 
 
-def check_sweep(w, shapes=((0, 0),), sampled=None, threshold=False):
+def check_sweep(w, shapes=((0, 0, 0),), sampled=None, threshold=False):
     """GPU sweep vs the triple oracle (all candidates, or `sampled` ones) and optionally vs the
     threshold-count route on all candidates."""
     dw = binding.DeviceWorkload(w)
@@ -39,9 +39,10 @@ def check_sweep(w, shapes=((0, 0),), sampled=None, threshold=False):
         if sampled is None:
             ref = oracle.placement_sweep(w)
         thr = oracle.threshold_sweep(w) if threshold else None
-        for q, chunk in shapes:
-            binding.maaso_ctx_set_launch_shape(dw.ctx, q, chunk, 0)
-            print(f"sweep {w.name} C={w.n_cand} I={w.i_pad} R={w.n_req} q={q} chunk={chunk}", flush=True)
+        for q, group, bq in shapes:
+            binding.maaso_ctx_set_launch_shape(dw.ctx, q, group, bq, 0)
+            print(f"sweep {w.name} C={w.n_cand} I={w.i_pad} R={w.n_req} q={q} group={group} bq={bq}",
+                  flush=True)
             cnt, ratio, best = dw.sweep()
             torch.cuda.synchronize()
             cnt, ratio, best = u32(cnt), ratio.cpu().numpy(), int(u32(best)[0])
@@ -68,7 +69,7 @@ def check_sweep(w, shapes=((0, 0),), sampled=None, threshold=False):
 def check_assign(w, cand=0, window=None, window_blocks=0, latencies=True, tbt_mode=None, ref=None):
     dw = binding.DeviceWorkload(w)
     try:
-        binding.maaso_ctx_set_launch_shape(dw.ctx, 0, 0, window_blocks)
+        binding.maaso_ctx_set_launch_shape(dw.ctx, 0, 0, 0, window_blocks)
         print(f"assign {w.name} I={w.i_pad} R={w.n_req} window={window} blocks={window_blocks}", flush=True)
         got = dw.assign(cand=cand, window=window, latencies=latencies, tbt_mode=tbt_mode)
         torch.cuda.synchronize()
@@ -117,7 +118,7 @@ def test_sweep_small_irregular(seed, n_cand, i_pad, n_req, n_slo):
     spread = 0
     for v in (w, W.stressed(w, seed=seed, deadline_scale=0.25),
               W.stressed(w, seed=seed, deadline_scale=0.03)):
-        cnt = check_sweep(v, shapes=((0, 0), (2, 8), (4, 33), (8, 64), (16, 1000)), threshold=True)
+        cnt = check_sweep(v, shapes=((0, 0, 0), (2, 1, 1), (4, 3, 2), (8, 64, 5), (16, 7, 100)), threshold=True)
         spread = max(spread, len(np.unique(cnt)))
     assert spread > 1, "no variant discriminates between candidates"
 
@@ -320,7 +321,7 @@ def test_inter_window_wait_gives_up_cleanly():
     must end by itself and the status must say so."""
     w = W.config2(n_req=8192, window=256)
     dw = binding.DeviceWorkload(w)
-    binding.maaso_ctx_set_launch_shape(dw.ctx, 0, 0, 64)
+    binding.maaso_ctx_set_launch_shape(dw.ctx, 0, 0, 0, 64)
     binding.maaso_ctx_set_wait_limit(dw.ctx, 0)
     dw.assign(window=256)
     with pytest.raises(binding.MaasoError) as e:
