@@ -25,19 +25,20 @@ ROOT = Path(__file__).resolve().parent
 if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
-# MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 single-issue fp32 lane
-# operations per second.  (The published 157.3 TFLOP/s counts a packed dual fused multiply-add,
-# 4 flop per lane per issue; packed fp32 instructions are compiled out of this library.)
-VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# MI355X fp32 vector peak: 157.3 TFLOP/s published = 256 compute units x 4 SIMDs x 32 lanes per clock
+# x 2.4 GHz x 2 flop per fused multiply-add, i.e. 78.6e12 VALU lane operations per second.  A
+# min, add or compare occupies a lane slot exactly as an fma does, so the kernels are priced in lane
+# operations; the flop figure (an fma counts two, everything else one) is given beside it.
+VALU_PEAK_TLANEOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 
-# Algorithmic work of the sweep per (request, instance) triple: prefill fma, wait add, min.
-SWEEP_LANEOPS_PER_TRIPLE = 3
-SWEEP_FLOP_PER_TRIPLE = 4  # the fma counts two
-# Algorithmic work of the distributor per triple: 2 fma, 1 add, 3 sub, 3 mul, 2 min, compare,
-# 2 selects (slack and index).
-ASSIGN_LANEOPS_PER_TRIPLE = 14
+# Sweep, per (request, instance) pair that reaches the latency loop: prefill fma, queue-wait add, min.
+SWEEP_LANEOPS_PER_PAIR = 3
+SWEEP_FLOP_PER_PAIR = 4
+# Distributor, per triple: 2 fma, 1 add, 2 sub, 2 mul, 2 min, 1 compare, 2 selects (the between-token
+# margin comes from a per-(class, instance) table).
+ASSIGN_LANEOPS_PER_TRIPLE = 12
 # Algorithmic HBM bytes of the distributor per request: prompt_len 4 + out_len 4 + class 1 in,
 # chosen 4 + slack 4 out.
 ASSIGN_BYTES_PER_REQUEST = 17
@@ -92,8 +93,8 @@ def cpu_baseline(w, kind: str, budget_triples: float):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="cfg1",
                     choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -178,23 +179,26 @@ def main() -> int:
     binding.maaso_ctx_kernel_timing(dw.ctx, False)
     k_avg_s = k_ms / max(k_n, 1) * 1e-3
     if kind == "sweep":
-        laneops = SWEEP_LANEOPS_PER_TRIPLE * triples_sweep
+        pairs = binding.maaso_ctx_sweep_evaluated(dw.ctx)  # pairs that reached the latency loop
+        ops = SWEEP_LANEOPS_PER_PAIR * pairs
         roofline = {
             "kernel": "sweep_kernel", "bound": "alu",
-            "achieved": laneops / k_avg_s / 1e12, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
-            "frac": laneops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS, "traffic": None,
+            "achieved": ops / k_avg_s / 1e12, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
+            "frac": ops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS, "traffic": None,
             "kernel_ms": k_avg_s * 1e3, "launches_timed": k_n,
-            "laneops_per_triple": SWEEP_LANEOPS_PER_TRIPLE,
-            "tflops": SWEEP_FLOP_PER_TRIPLE * triples_sweep / k_avg_s / 1e12,
-            "frac_of_fp32_vector_peak": SWEEP_FLOP_PER_TRIPLE * triples_sweep / k_avg_s / 1e12
+            "laneops_per_pair": SWEEP_LANEOPS_PER_PAIR,
+            "pairs_evaluated": pairs, "valid_triples": triples_sweep,
+            "settled_per_class_instance": triples_sweep - pairs,
+            "tflops": SWEEP_FLOP_PER_PAIR * pairs / k_avg_s / 1e12,
+            "frac_of_fp32_vector_peak": SWEEP_FLOP_PER_PAIR * pairs / k_avg_s / 1e12
             / FP32_VECTOR_PEAK_TFLOPS,
             "kernel_triples_per_s": triples_sweep / k_avg_s,
         }
     else:
         nbytes = ASSIGN_BYTES_PER_REQUEST * w.n_req
-        laneops = ASSIGN_LANEOPS_PER_TRIPLE * triples_assign
+        ops = ASSIGN_LANEOPS_PER_TRIPLE * triples_assign
         hbm_frac = nbytes / k_avg_s / 1e9 / HBM_PEAK_GBS
-        alu_frac = laneops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS
+        alu_frac = ops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS
         name = "assign_window_kernel" if w.window else "assign_static_kernel"
         roofline = {
             "kernel": name, "bound": "hbm", "achieved": nbytes / k_avg_s / 1e9,

@@ -117,6 +117,12 @@ int maaso_ctx_set_wait_limit(maaso_ctx* ctx, uint32_t polls);
 int maaso_ctx_kernel_timing(maaso_ctx* ctx, int enable);
 int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches);
 
+/* Synchronises the device and returns how many (request, instance) pairs the context's most recent
+ * maaso_placement_sweep evaluated in its latency loop, i.e. the valid triples minus those whose
+ * instance already fails the between-token deadline of the request's class (they are settled per
+ * (class, instance) and never reach the loop).  0 if no sweep has run.  Errors: INVALID_ARG, HIP. */
+int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs);
+
 /* Requests as structure-of-arrays streams (Sec. IV-C: a request r decodes S_r tokens before its
  * deadline; Sec. V-A: arrivals over time).  DEVICE pointers, read only. */
 typedef struct {

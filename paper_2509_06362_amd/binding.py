@@ -22,7 +22,8 @@ MAASO_MAX_TABLE_CELLS = 2048
 EXPORTS = (
     "maaso_profile_tables_load", "maaso_ctx_destroy", "maaso_ctx_device_status", "maaso_strerror",
     "maaso_ctx_set_launch_shape", "maaso_ctx_set_wait_limit", "maaso_ctx_kernel_timing",
-    "maaso_ctx_kernel_elapsed", "maaso_score_assign", "maaso_placement_sweep",
+    "maaso_ctx_kernel_elapsed", "maaso_ctx_sweep_evaluated", "maaso_score_assign",
+    "maaso_placement_sweep",
 )
 
 
@@ -84,6 +85,7 @@ def load_library() -> C.CDLL:
         lib.maaso_ctx_kernel_timing.argtypes = [C.c_void_p, C.c_int]
         lib.maaso_ctx_kernel_elapsed.argtypes = [C.c_void_p, C.POINTER(C.c_float),
                                                  C.POINTER(C.c_uint32)]
+        lib.maaso_ctx_sweep_evaluated.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         lib.maaso_score_assign.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                            C.POINTER(Params), C.POINTER(AssignOut), C.c_void_p]
         lib.maaso_placement_sweep.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
@@ -196,6 +198,14 @@ def maaso_ctx_kernel_elapsed(ctx: Context):
     _check(load_library().maaso_ctx_kernel_elapsed(ctx.handle, C.byref(ms), C.byref(n)),
            "maaso_ctx_kernel_elapsed")
     return float(ms.value), int(n.value)
+
+
+def maaso_ctx_sweep_evaluated(ctx: Context) -> int:
+    """(request, instance) pairs the last sweep evaluated in its latency loop (synchronises)."""
+    v = C.c_uint64(0)
+    _check(load_library().maaso_ctx_sweep_evaluated(ctx.handle, C.byref(v)),
+           "maaso_ctx_sweep_evaluated")
+    return int(v.value)
 
 
 def _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks) -> Requests:

@@ -51,29 +51,9 @@ struct ClassRow {
   float Dt, Db, iDt, iDb;
 };
 
-// Scores one request against n staged instances held in LDS; j ascending and a strict '>' give the
-// lowest index among equal slacks.
-template <bool kLat>
-__device__ __forceinline__ void best_instance(const float4* __restrict__ recs, uint32_t n, float L,
-                                              float S, const Deadlines& d, float& best, int32_t& idx,
-                                              float& b_ttft, float& b_tbt, float& b_e2e) {
-  best = -INFINITY;
-  idx = -1;
-  b_ttft = b_tbt = b_e2e = __builtin_nanf("");
-  for (uint32_t j = 0; j < n; ++j) {
-    const float4 r = recs[j];  // a, p, tbt, wait
-    const Margins m = score_triple(r.x, r.y, r.z, r.w, L, S, d);
-    if (m.slack > best) {
-      best = m.slack;
-      idx = (int32_t)j;
-      if (kLat) { b_ttft = m.ttft; b_tbt = r.z; b_e2e = m.e2e; }
-    }
-  }
-}
-
-// Stage the placement's instances into LDS records {a, p, tbt, wait}; invalid slots are compacted
-// out would change indices, so an instance outside the tables keeps its slot with a record that can
-// never win (wait = +inf gives slack = -inf, which a strict '>' against -inf never takes).
+// Stage the placement's instances into LDS records {a, p, tbt, wait}.  An instance outside the
+// tables keeps its slot (dropping it would shift the indices) with a record that can never win:
+// wait = +inf gives slack = -inf, which a strict '>' against -inf never takes.
 __device__ __forceinline__ void stage_placement(const AssignArgs& a, uint32_t n, float4* recs,
                                                 float* svc) {
   for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) {
@@ -89,49 +69,131 @@ __device__ __forceinline__ void stage_placement(const AssignArgs& a, uint32_t n,
   }
 }
 
-template <bool kLat>
-__global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const AssignArgs a) {
-  __shared__ float4 recs[256];
-  __shared__ ClassRow cls[kMaxSlo];
-  __shared__ uint32_t wave_sat[kAssignThreads / 64];
-  const uint32_t n = min(a.n_inst[0], a.i_pad);
-  stage_placement(a, n, recs, nullptr);
+constexpr int kS2Stride = 257;  // odd: the per-class rows of the margin table fall on different banks
+
+// V consecutive requests starting at r0 (V = 4: 16-byte loads and stores; V = 1: any alignment).
+// The instance loop is outermost so that one broadcast LDS read of a record serves all V requests;
+// j ascending and a strict '>' give the lowest index among equal slacks.  The between-token margin
+// (D_tbt - tbt_j) / D_tbt depends on (class, instance) only and is read from an LDS table.
+template <bool kLat, int V>
+__device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_t r0, uint32_t n,
+                                                    const float4* __restrict__ recs,
+                                                    const ClassRow* __restrict__ cls,
+                                                    const float* __restrict__ s2tab) {
+  float L[V], S[V], best[V], De[V], iDe[V], Dt[V], iDt[V];
+  float b_ttft[V], b_tbt[V], b_e2e[V];
+  uint32_t k[V];
+  int32_t idx[V];
+  if (V == 4) {
+    const uint4 pl = *reinterpret_cast<const uint4*>(a.prompt_len + r0);
+    const uint4 ol = *reinterpret_cast<const uint4*>(a.out_len + r0);
+    const uint32_t kk = *reinterpret_cast<const uint32_t*>(a.slo_class + r0);
+    const uint32_t p4[4] = {pl.x, pl.y, pl.z, pl.w}, o4[4] = {ol.x, ol.y, ol.z, ol.w};
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      L[v] = (float)p4[v]; S[v] = (float)o4[v]; k[v] = (kk >> (8 * v)) & 0xffu;
+    }
+  } else {
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      L[v] = (float)a.prompt_len[r0 + v]; S[v] = (float)a.out_len[r0 + v]; k[v] = a.slo_class[r0 + v];
+    }
+  }
+  bool ok[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    ok[v] = k[v] < a.n_slo;
+    if (!ok[v]) { raise_status(a.status, 1u); k[v] = 0u; }
+    const ClassRow c = cls[k[v]];
+    Dt[v] = c.Dt; iDt[v] = c.iDt;
+    De[v] = fmaf(S[v], c.Db, c.Dt);
+    iDe[v] = 1.0f / De[v];
+    best[v] = -INFINITY;
+    idx[v] = -1;
+    b_ttft[v] = b_tbt[v] = b_e2e[v] = __builtin_nanf("");
+  }
+  for (uint32_t j = 0; j < n; ++j) {
+    const float4 r = recs[j];  // a, p, tbt, wait
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      const float pre = fmaf(r.y, L[v], r.x);
+      const float ttft = r.w + pre;
+      const float e2e = fmaf(S[v], r.z, ttft);
+      const float s1 = (Dt[v] - ttft) * iDt[v];
+      const float s2 = s2tab[k[v] * kS2Stride + j];
+      const float s3 = (De[v] - e2e) * iDe[v];
+      const float slack = fminf(fminf(s1, s2), s3);
+      if (slack > best[v]) {
+        best[v] = slack;
+        idx[v] = (int32_t)j;
+        if (kLat) { b_ttft[v] = ttft; b_tbt[v] = r.z; b_e2e[v] = e2e; }
+      }
+    }
+  }
+  uint32_t sat = 0;
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    if (!ok[v]) { best[v] = -INFINITY; idx[v] = -1; b_ttft[v] = b_tbt[v] = b_e2e[v] = __builtin_nanf(""); }
+    sat += (best[v] >= 0.0f) ? 1u : 0u;
+  }
+  if (V == 4) {
+    if (a.chosen) *reinterpret_cast<int4*>(a.chosen + r0) = make_int4(idx[0], idx[1], idx[2], idx[3]);
+    if (a.slack) *reinterpret_cast<float4*>(a.slack + r0) = make_float4(best[0], best[1], best[2], best[3]);
+    if (kLat) {
+      if (a.ttft) *reinterpret_cast<float4*>(a.ttft + r0) = make_float4(b_ttft[0], b_ttft[1], b_ttft[2], b_ttft[3]);
+      if (a.tbt) *reinterpret_cast<float4*>(a.tbt + r0) = make_float4(b_tbt[0], b_tbt[1], b_tbt[2], b_tbt[3]);
+      if (a.e2e) *reinterpret_cast<float4*>(a.e2e + r0) = make_float4(b_e2e[0], b_e2e[1], b_e2e[2], b_e2e[3]);
+    }
+  } else {
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      if (a.chosen) a.chosen[r0 + v] = idx[v];
+      if (a.slack) a.slack[r0 + v] = best[v];
+      if (kLat) {
+        if (a.ttft) a.ttft[r0 + v] = b_ttft[v];
+        if (a.tbt) a.tbt[r0 + v] = b_tbt[v];
+        if (a.e2e) a.e2e[r0 + v] = b_e2e[v];
+      }
+    }
+  }
+  return sat;
+}
+
+// Per-block set-up shared by the static and the windowed kernel: class rows and the table of
+// between-token margins s2[k][j] = (D_tbt[k] - tbt_j) * (1 / D_tbt[k]).
+__device__ __forceinline__ void fill_class_tables(const AssignArgs& a, uint32_t n, const float4* recs,
+                                                  ClassRow* cls, float* s2tab) {
   if (threadIdx.x < a.n_slo) {
     const uint32_t k = threadIdx.x;
     cls[k] = ClassRow{a.d_ttft[k], a.d_tbt[k], a.i_ttft[k], a.i_tbt[k]};
   }
+  for (uint32_t i = threadIdx.x; i < a.n_slo * n; i += blockDim.x) {
+    const uint32_t k = i / n, j = i - k * n;
+    s2tab[k * kS2Stride + j] = (a.d_tbt[k] - recs[j].z) * a.i_tbt[k];
+  }
+}
+
+// V = 4 needs 16-byte aligned request and output arrays (slo_class 4-byte aligned); the host checks.
+template <bool kLat, int V>
+__global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const AssignArgs a) {
+  __shared__ float4 recs[256];
+  __shared__ ClassRow cls[kMaxSlo];
+  __shared__ float s2tab[kMaxSlo * kS2Stride];
+  __shared__ uint32_t wave_sat[kAssignThreads / 64];
+  const uint32_t n = min(a.n_inst[0], a.i_pad);
+  stage_placement(a, n, recs, nullptr);
+  __syncthreads();
+  fill_class_tables(a, n, recs, cls, s2tab);
   __syncthreads();
 
   uint32_t sat = 0;
-  for (uint64_t base = (uint64_t)blockIdx.x * kAssignThreads; base < a.n_req;
-       base += (uint64_t)gridDim.x * kAssignThreads) {
-    const uint64_t r = base + threadIdx.x;
-    if (r < a.n_req) {
-      const float L = (float)a.prompt_len[r];
-      const float S = (float)a.out_len[r];
-      const uint32_t k = a.slo_class[r];
-      float best = -INFINITY, b_ttft, b_tbt, b_e2e;
-      int32_t idx = -1;
-      b_ttft = b_tbt = b_e2e = __builtin_nanf("");
-      if (k < a.n_slo) {
-        const ClassRow c = cls[k];
-        Deadlines d;
-        d.Dt = c.Dt; d.Db = c.Db; d.iDt = c.iDt; d.iDb = c.iDb;
-        d.De = fmaf(S, c.Db, c.Dt);
-        d.iDe = 1.0f / d.De;
-        best_instance<kLat>(recs, n, L, S, d, best, idx, b_ttft, b_tbt, b_e2e);
-      } else {
-        raise_status(a.status, 1u);
-      }
-      if (a.chosen) a.chosen[r] = idx;
-      if (a.slack) a.slack[r] = best;
-      if (kLat) {
-        if (a.ttft) a.ttft[r] = b_ttft;
-        if (a.tbt) a.tbt[r] = b_tbt;
-        if (a.e2e) a.e2e[r] = b_e2e;
-      }
-      sat += (best >= 0.0f) ? 1u : 0u;
-    }
+  const uint64_t n_vec = (uint64_t)a.n_req / V;  // groups of V requests
+  for (uint64_t g = (uint64_t)blockIdx.x * kAssignThreads + threadIdx.x; g < n_vec;
+       g += (uint64_t)gridDim.x * kAssignThreads)
+    sat += assign_requests<kLat, V>(a, g * V, n, recs, cls, s2tab);
+  if (V > 1 && blockIdx.x == 0) {  // the ragged tail, one request per thread
+    const uint64_t r = n_vec * V + threadIdx.x;
+    if (r < a.n_req) sat += assign_requests<kLat, 1>(a, r, n, recs, cls, s2tab);
   }
   // block-then-atomic reduction of the admitted count
   for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);

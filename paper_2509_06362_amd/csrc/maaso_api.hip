@@ -33,6 +33,7 @@ struct maaso_ctx {
   uint32_t sweep_q;      // 0 = automatic
   uint32_t sweep_group;  // 0 = automatic
   uint32_t sweep_blocks_per_queue;  // 0 = automatic
+  unsigned long long* last_evaluated;  // device word written by the last sweep, or null
   bool counters_dirty;   // class counters may be non-zero (a call failed between its launches)
   uint32_t window_blocks;  // 0 = automatic
   uint32_t spin_limit;     // polls of the inter-window barrier before a block gives up
@@ -305,13 +306,17 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   if (Q == 0) Q = R >= (1u << 14) ? 8u : (R >= (1u << 12) ? 4u : 2u);
   uint32_t G = (uint32_t)kGroupSlots / I;
   if (G > (uint32_t)kMaxGroup) G = kMaxGroup;
-  if (ctx->sweep_group != 0 && ctx->sweep_group < G) G = ctx->sweep_group;
+  // measured: items of about 128 instance slots balance best across the persistent blocks
+  uint32_t g_want = ctx->sweep_group ? ctx->sweep_group : (128u / I ? 128u / I : 1u);
+  if (g_want < G) G = g_want;
   const uint32_t n_items = (C + G - 1) / G;
   const uint32_t tile = (uint32_t)kSweepThreads * Q;
   const uint32_t nrb_max = (uint32_t)(((uint64_t)R + tile - 1) / tile) + K;  // >= tiles that exist
   uint32_t bq = ctx->sweep_blocks_per_queue;
   if (bq == 0) {
-    bq = ((uint32_t)ctx->n_cu * 8u + 4u * nrb_max) / (8u * nrb_max);  // about 8 blocks per compute unit
+    // measured: about twice as many blocks as can be resident (8 per compute unit) - the late
+    // starters fill the tail of the dynamic queues
+    bq = ((uint32_t)ctx->n_cu * 18u + 4u * nrb_max) / (8u * nrb_max);
     if (bq == 0) bq = 1;
   }
   const uint32_t per_queue = (n_items + 7u) / 8u;
@@ -323,7 +328,9 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   auto up256 = [](size_t x) { return (x + 255) & ~size_t(255); };
   const size_t lbuf_bytes = up256((size_t)K * (R ? R : 1u) * sizeof(float));
   const size_t recs_bytes = up256((size_t)C * I * sizeof(float4));
-  const size_t queue_bytes = up256((size_t)nrb_max * 8u * sizeof(uint32_t));
+  // queue heads, then one 8-byte evaluated-pairs word per sweep block
+  const size_t queue_words = (size_t)nrb_max * 8u + 2u * (size_t)blocks64;
+  const size_t queue_bytes = up256(queue_words * sizeof(uint32_t));
   rc = ensure_workspace(ctx, lbuf_bytes + recs_bytes + queue_bytes);
   if (rc != MAASO_OK) return rc;
   unsigned char* wsb = static_cast<unsigned char*>(ctx->ws);
@@ -358,7 +365,7 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
     p.recs = recs;
     p.sat_count = sat_count;
     p.queues = queues;
-    p.n_queues = nrb_max * 8u;
+    p.n_queues = (uint32_t)queue_words;
     p.status = ctx->status;
     const uint64_t n_stage = ((uint64_t)C * I + kStageSlotsPerBlock - 1) / kStageSlotsPerBlock;
     const uint64_t n_prep = (uint64_t)p.n_bucket_blocks + n_stage;
@@ -384,6 +391,7 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
     a.nrb_max = nrb_max;
     a.queues = queues;
     a.sat_count = sat_count;
+    a.evaluated = reinterpret_cast<unsigned long long*>(queues + (size_t)nrb_max * 8u);
     const uint32_t blocks = (uint32_t)blocks64;
     {
       TimedRegion timed(ctx, s);
@@ -396,8 +404,13 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
     }
     if (rc != MAASO_OK) return rc;
   }
+  // evaluated-pairs total lands in the context's small device block, next to the class counters
+  unsigned long long* eval_total = reinterpret_cast<unsigned long long*>(ctx->status + 32);
   hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
-                     best_cand, ctx->cls_count);
+                     best_cand, ctx->cls_count,
+                     reinterpret_cast<const unsigned long long*>(queues + (size_t)nrb_max * 8u),
+                     R != 0 ? (uint32_t)blocks64 : 0u, eval_total);
+  ctx->last_evaluated = eval_total;
   if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
   ctx->counters_dirty = false;
   return MAASO_OK;
@@ -421,14 +434,27 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
     hipLaunchKernelGGL(assign_init_kernel, dim3(1), dim3(64), 0, s, a.n_satisfied);
     if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
     if (R == 0) return MAASO_OK;
-    uint32_t blocks = (R + kAssignThreads - 1) / kAssignThreads;
+    // 16-byte accesses, four requests per thread, when every array allows it
+    auto al = [](const void* p, uintptr_t m) { return (reinterpret_cast<uintptr_t>(p) & m) == 0; };
+    const bool vec = al(rq->prompt_len, 15) && al(rq->out_len, 15) && al(rq->slo_class, 3) &&
+                     al(out->chosen, 15) && al(out->slack, 15) && al(out->ttft, 15) &&
+                     al(out->tbt, 15) && al(out->e2e, 15);
+    const uint32_t per_block = kAssignThreads * (vec ? 4u : 1u);
+    uint32_t blocks = (uint32_t)(((uint64_t)R + per_block - 1) / per_block);
     const uint32_t cap = (uint32_t)ctx->n_cu * 8u;
     if (blocks > cap) blocks = cap;
     TimedRegion timed(ctx, s);
-    if (lat)
-      hipLaunchKernelGGL(assign_static_kernel<true>, dim3(blocks), dim3(kAssignThreads), 0, s, a);
-    else
-      hipLaunchKernelGGL(assign_static_kernel<false>, dim3(blocks), dim3(kAssignThreads), 0, s, a);
+    if (vec) {
+      if (lat)
+        hipLaunchKernelGGL((assign_static_kernel<true, 4>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
+      else
+        hipLaunchKernelGGL((assign_static_kernel<false, 4>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
+    } else {
+      if (lat)
+        hipLaunchKernelGGL((assign_static_kernel<true, 1>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
+      else
+        hipLaunchKernelGGL((assign_static_kernel<false, 1>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
+    }
     return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
   }
 
@@ -502,6 +528,19 @@ int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches
   *total_ms = sum;
   *launches = ctx->n_timed;
   ctx->n_timed = 0;
+  return MAASO_OK;
+}
+
+int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs) {
+  if (!ctx || !pairs) return MAASO_E_INVALID_ARG;
+  *pairs = 0;
+  if (!ctx->last_evaluated) return MAASO_OK;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  unsigned long long v = 0;
+  if (!hip_ok(hipDeviceSynchronize())) return MAASO_E_HIP;
+  if (!hip_ok(hipMemcpy(&v, ctx->last_evaluated, sizeof(v), hipMemcpyDeviceToHost))) return MAASO_E_HIP;
+  *pairs = v;
   return MAASO_OK;
 }
 

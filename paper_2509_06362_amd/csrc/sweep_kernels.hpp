@@ -82,7 +82,7 @@ struct PrepArgs {
   // per-call accumulators to clear
   uint32_t* sat_count;  // [n_cand]
   uint32_t* queues;     // [n_queues]
-  uint32_t n_queues;
+  uint32_t n_queues;  // words to clear: queue heads and evaluated-pair words
   uint32_t* status;
 };
 
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void sweep_prep_kernel(const PrepArgs a) {
   float* tab = reinterpret_cast<float*>(smem);
   for (uint32_t i = tid; i < 3u * a.cells; i += 256u) tab[i] = a.tab[i];
   const uint32_t sb = blockIdx.x - a.n_bucket_blocks;
-  if (sb == 0u)
+  if (sb == 0u)  // queue heads, then the per-block words that count evaluated pairs
     for (uint32_t i = tid; i < a.n_queues; i += 256u) a.queues[i] = 0u;
   __syncthreads();
   const uint64_t n_slots = (uint64_t)a.n_cand * a.i_pad;
@@ -169,11 +169,13 @@ struct SweepArgs {
   uint32_t nrb_max;  // request-tile slots of the grid (>= tiles that exist)
   uint32_t* queues;  // [nrb_max][8] next position of each (request tile, XCD) queue
   uint32_t* sat_count;
+  unsigned long long* evaluated;  // [gridDim.x] per block: (request, instance) pairs that reached
+                                  // the latency loop (zero on entry; summed by the finalize kernel)
 };
 
 template <int Q>
 __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a) {
-  __shared__ float4 lists[2][kGroupSlots + 1];  // +1: the look-ahead read past the last record
+  __shared__ float4 lists[2][kGroupSlots];
   __shared__ uint32_t lens[3][kMaxGroup];
   __shared__ uint32_t blk_cnt[2][kSweepWaves][kMaxGroup];
   __shared__ uint32_t items[2];
@@ -258,6 +260,11 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
   }
   __syncthreads();
 
+  uint32_t wave_reqs = 0;  // valid requests held by this wavefront
+#pragma unroll
+  for (int q = 0; q < Q; ++q) wave_reqs += (uint32_t)__popcll(vmask[q]);
+  unsigned long long evaluated = 0ull;
+
   uint32_t prev_c0 = 0, prev_n = 0;
   for (uint32_t it = 0;; ++it) {
     uint32_t after_next = 0xffffffffu;
@@ -279,25 +286,31 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
       const float4* gl = lists[it & 1u];
       const uint32_t* glen = lens[it % 3u];
       uint32_t n_ahead = glen[0];
+      uint32_t n_sum = 0;  // records this wavefront walks in this group
       for (uint32_t g = 0; g < g_cands; ++g) {
         const uint32_t n = __builtin_amdgcn_readfirstlane(n_ahead);
         n_ahead = glen[min(g + 1u, G - 1u)];
+        n_sum += n;
         const float4* lst = gl + g * I;
-        float m[Q];
-#pragma unroll
-        for (int q = 0; q < Q; ++q) m[q] = INFINITY;
-        float4 r = lst[0];
-        for (uint32_t i = 0; i < n; ++i) {
-          const float4 rn = lst[i + 1u];  // look-ahead; the record after the last one is never used
-#pragma unroll
-          for (int q = 0; q < Q; ++q) m[q] = min_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y));
-          r = rn;
-        }
         uint32_t cnt = 0;
+        if (n != 0u) {
+          float m[Q];  // smallest first-token latency so far; the first record initialises it
+          {
+            const float4 r = lst[0];
 #pragma unroll
-        for (int q = 0; q < Q; ++q) cnt += (uint32_t)__popcll(__ballot(m[q] <= Dt) & vmask[q]);
+            for (int q = 0; q < Q; ++q) m[q] = r.z + fmaf(r.x, L[q], r.y);
+          }
+          for (uint32_t i = 1; i < n; ++i) {
+            const float4 r = lst[i];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) m[q] = min_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y));
+          }
+#pragma unroll
+          for (int q = 0; q < Q; ++q) cnt += (uint32_t)__popcll(__ballot(m[q] <= Dt) & vmask[q]);
+        }
         acc = (lane == g) ? cnt : acc;
       }
+      evaluated += (unsigned long long)n_sum * wave_reqs;
     }
     blk_cnt[it & 1u][wave][lane] = acc;
 
@@ -318,6 +331,11 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
       break;
     }
   }
+  // one word per block, no atomics: thousands of same-address atomics at the kernel's end are slow
+  __shared__ unsigned long long wave_eval[kSweepWaves];
+  if (lane == 0u) wave_eval[wave] = evaluated;
+  __syncthreads();
+  if (tid == 0u) a.evaluated[blockIdx.x] = wave_eval[0] + wave_eval[1] + wave_eval[2] + wave_eval[3];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -327,9 +345,19 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(const uint32_t* __
                                                               uint32_t n_cand, uint32_t n_req,
                                                               float* __restrict__ sat_ratio,
                                                               uint32_t* __restrict__ best_cand,
-                                                              uint32_t* __restrict__ cls_count) {
+                                                              uint32_t* __restrict__ cls_count,
+                                                              const unsigned long long* __restrict__ eval_parts,
+                                                              uint32_t n_parts,
+                                                              unsigned long long* __restrict__ eval_total) {
   __shared__ unsigned long long best[16];
+  __shared__ unsigned long long esum[16];
   if (threadIdx.x < kMaxSlo) cls_count[threadIdx.x] = 0u;
+  {
+    unsigned long long e = 0ull;
+    for (uint32_t i = threadIdx.x; i < n_parts; i += blockDim.x) e += eval_parts[i];
+    for (int d = 32; d >= 1; d >>= 1) e += __shfl_xor(e, d);
+    if ((threadIdx.x & 63u) == 0u) esum[threadIdx.x >> 6] = e;
+  }
   const float fr = (float)n_req;
   unsigned long long key = 0ull;  // (count << 32) | ~index: max key = max count, then min index
   for (uint32_t c = threadIdx.x; c < n_cand; c += blockDim.x) {
@@ -347,6 +375,11 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(const uint32_t* __
   if (threadIdx.x == 0 && best_cand) {
     for (uint32_t w = 1; w < (blockDim.x >> 6); ++w) key = best[w] > key ? best[w] : key;
     *best_cand = ~(uint32_t)(key & 0xffffffffull);
+  }
+  if (threadIdx.x == 0) {
+    unsigned long long e = 0ull;
+    for (uint32_t w = 0; w < (blockDim.x >> 6); ++w) e += esum[w];
+    *eval_total = e;
   }
 }
 

@@ -212,6 +212,47 @@ def test_assign_streaming_shape_sampled():
     check_assign(w, window=0)
 
 
+def test_assign_static_unaligned_arrays_take_the_scalar_path():
+    """Request and output arrays offset by one element are only 4-byte aligned."""
+    w = W.stressed(W.random_small(26, 1, 20, 3001, n_slo=3), seed=3)
+    w = W.replace(w, n_inst=np.array([20], np.uint32))
+    dw = binding.DeviceWorkload(w)
+    dev = dw.prompt_len.device
+    R = w.n_req - 1
+    chosen = torch.empty(R + 1, dtype=torch.int32, device=dev)
+    slack = torch.empty(R + 1, dtype=torch.float32, device=dev)
+    n_sat = torch.empty(1, dtype=torch.int64, device=dev)
+    binding.maaso_score_assign(
+        dw.ctx, n_cand=1, i_pad=w.i_pad, n_inst=dw.n_inst, tp_idx=dw.tp_idx, max_batch=dw.max_batch,
+        occ=dw.occ, q_ticks=dw.q_ticks, n_req=R, prompt_len=dw.prompt_len[1:], out_len=dw.out_len[1:],
+        slo_class=dw.slo_class[1:], **dw.param_args(), chosen=chosen[1:], slack=slack[1:],
+        n_satisfied=n_sat)
+    torch.cuda.synchronize()
+    ref = oracle.score_assign(w.with_requests(1, R + 1), window=0)
+    assert np.array_equal(chosen[1:].cpu().numpy(), ref["chosen"])
+    assert np.array_equal(slack[1:].cpu().numpy(), ref["slack"])
+    assert int(n_sat.item()) == ref["n_satisfied"]
+    dw.close()
+
+
+def test_sweep_reports_the_pairs_it_evaluated():
+    """Pairs that reach the latency loop = sum over (candidate, class) of the instances whose
+    between-token latency meets the class deadline, times the requests of that class."""
+    w = W.stressed(W.config4(n_cand=40, n_req=5000), seed=2)
+    dw = binding.DeviceWorkload(w)
+    dw.sweep()
+    got = binding.maaso_ctx_sweep_evaluated(dw.ctx)
+    per_class = np.bincount(w.slo_class, minlength=w.n_slo).astype(np.int64)
+    want = 0
+    for c in range(w.n_cand):
+        tbt = oracle.stage(w, c)["tbt"]
+        for k in range(w.n_slo):
+            want += int((tbt <= w.d_tbt[k]).sum()) * int(per_class[k])
+    assert got == want
+    assert 0 < got < w.valid_triples()
+    dw.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # distributor, windowed
 # ------------------------------------------------------------------------------------------------
