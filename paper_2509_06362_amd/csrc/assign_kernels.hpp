@@ -75,12 +75,18 @@ constexpr int kS2Stride = 257;  // odd: the per-class rows of the margin table f
 // The instance loop is outermost so that one broadcast LDS read of a record serves all V requests;
 // j ascending and a strict '>' give the lowest index among equal slacks.  The between-token margin
 // (D_tbt - tbt_j) / D_tbt depends on (class, instance) only and is read from an LDS table.
-template <bool kLat, int V>
+//
+// NREG = 0: records and between-token margins are read from LDS (any number of instances).
+// NREG > 0: the placement has at most NREG instances and the caller holds their records in
+// registers (`rreg`); the margin is recomputed from the class row, so the loop touches no LDS - the
+// form used when there are so few instances that the request stream from HBM is the bound.
+template <bool kLat, int V, int NREG>
 __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_t r0, uint32_t n,
                                                     const float4* __restrict__ recs,
                                                     const ClassRow* __restrict__ cls,
-                                                    const float* __restrict__ s2tab) {
-  float L[V], S[V], best[V], De[V], iDe[V], Dt[V], iDt[V];
+                                                    const float* __restrict__ s2tab,
+                                                    const float4* rreg) {
+  float L[V], S[V], best[V], De[V], iDe[V], Dt[V], iDt[V], Db[V], iDb[V];
   float b_ttft[V], b_tbt[V], b_e2e[V];
   uint32_t k[V];
   int32_t idx[V];
@@ -105,22 +111,21 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
     ok[v] = k[v] < a.n_slo;
     if (!ok[v]) { raise_status(a.status, 1u); k[v] = 0u; }
     const ClassRow c = cls[k[v]];
-    Dt[v] = c.Dt; iDt[v] = c.iDt;
+    Dt[v] = c.Dt; iDt[v] = c.iDt; Db[v] = c.Db; iDb[v] = c.iDb;
     De[v] = fmaf(S[v], c.Db, c.Dt);
     iDe[v] = 1.0f / De[v];
     best[v] = -INFINITY;
     idx[v] = -1;
     b_ttft[v] = b_tbt[v] = b_e2e[v] = __builtin_nanf("");
   }
-  for (uint32_t j = 0; j < n; ++j) {
-    const float4 r = recs[j];  // a, p, tbt, wait
+  auto score = [&](const float4 r, uint32_t j) {  // r = {a, p, tbt, wait}
 #pragma unroll
     for (int v = 0; v < V; ++v) {
       const float pre = fmaf(r.y, L[v], r.x);
       const float ttft = r.w + pre;
       const float e2e = fmaf(S[v], r.z, ttft);
       const float s1 = (Dt[v] - ttft) * iDt[v];
-      const float s2 = s2tab[k[v] * kS2Stride + j];
+      const float s2 = NREG ? (Db[v] - r.z) * iDb[v] : s2tab[k[v] * kS2Stride + j];
       const float s3 = (De[v] - e2e) * iDe[v];
       const float slack = fminf(fminf(s1, s2), s3);
       if (slack > best[v]) {
@@ -129,6 +134,13 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
         if (kLat) { b_ttft[v] = ttft; b_tbt[v] = r.z; b_e2e[v] = e2e; }
       }
     }
+  };
+  if (NREG) {
+#pragma unroll
+    for (int j = 0; j < (NREG ? NREG : 1); ++j)
+      if ((uint32_t)j < n) score(rreg[j], (uint32_t)j);
+  } else {
+    for (uint32_t j = 0; j < n; ++j) score(recs[j], j);
   }
   uint32_t sat = 0;
 #pragma unroll
@@ -174,26 +186,38 @@ __device__ __forceinline__ void fill_class_tables(const AssignArgs& a, uint32_t 
 }
 
 // V = 4 needs 16-byte aligned request and output arrays (slo_class 4-byte aligned); the host checks.
-template <bool kLat, int V>
+// NREG > 0 requires n_inst <= NREG (the host checks against the i_pad it was given).
+template <bool kLat, int V, int NREG>
 __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const AssignArgs a) {
   __shared__ float4 recs[256];
   __shared__ ClassRow cls[kMaxSlo];
-  __shared__ float s2tab[kMaxSlo * kS2Stride];
+  __shared__ float s2tab[NREG ? 1 : kMaxSlo * kS2Stride];
   __shared__ uint32_t wave_sat[kAssignThreads / 64];
-  const uint32_t n = min(a.n_inst[0], a.i_pad);
+  const uint32_t n = min(min(a.n_inst[0], a.i_pad), NREG ? (uint32_t)NREG : 256u);
   stage_placement(a, n, recs, nullptr);
   __syncthreads();
-  fill_class_tables(a, n, recs, cls, s2tab);
+  if (NREG) {
+    if (threadIdx.x < a.n_slo) {
+      const uint32_t k = threadIdx.x;
+      cls[k] = ClassRow{a.d_ttft[k], a.d_tbt[k], a.i_ttft[k], a.i_tbt[k]};
+    }
+  } else {
+    fill_class_tables(a, n, recs, cls, s2tab);
+  }
   __syncthreads();
+  float4 rreg[NREG ? NREG : 1];
+#pragma unroll
+  for (int j = 0; j < (NREG ? NREG : 1); ++j)
+    rreg[j] = (NREG && (uint32_t)j < n) ? recs[j] : make_float4(1.0f, 1.0f, 1.0f, INFINITY);
 
   uint32_t sat = 0;
   const uint64_t n_vec = (uint64_t)a.n_req / V;  // groups of V requests
   for (uint64_t g = (uint64_t)blockIdx.x * kAssignThreads + threadIdx.x; g < n_vec;
        g += (uint64_t)gridDim.x * kAssignThreads)
-    sat += assign_requests<kLat, V>(a, g * V, n, recs, cls, s2tab);
+    sat += assign_requests<kLat, V, NREG>(a, g * V, n, recs, cls, s2tab, rreg);
   if (V > 1 && blockIdx.x == 0) {  // the ragged tail, one request per thread
     const uint64_t r = n_vec * V + threadIdx.x;
-    if (r < a.n_req) sat += assign_requests<kLat, 1>(a, r, n, recs, cls, s2tab);
+    if (r < a.n_req) sat += assign_requests<kLat, 1, NREG>(a, r, n, recs, cls, s2tab, rreg);
   }
   // block-then-atomic reduction of the admitted count
   for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);

@@ -443,18 +443,19 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
     uint32_t blocks = (uint32_t)(((uint64_t)R + per_block - 1) / per_block);
     const uint32_t cap = (uint32_t)ctx->n_cu * 8u;
     if (blocks > cap) blocks = cap;
+    // few instance slots: records live in registers and the loop needs no LDS (HBM-bound shape)
+    const bool few = pl->i_pad <= 8u;
     TimedRegion timed(ctx, s);
+#define MAASO_LAUNCH_STATIC(LAT, V, NREG)                                                       \
+  hipLaunchKernelGGL((assign_static_kernel<LAT, V, NREG>), dim3(blocks), dim3(kAssignThreads), 0, s, a)
     if (vec) {
-      if (lat)
-        hipLaunchKernelGGL((assign_static_kernel<true, 4>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
-      else
-        hipLaunchKernelGGL((assign_static_kernel<false, 4>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
+      if (few) { if (lat) MAASO_LAUNCH_STATIC(true, 4, 8); else MAASO_LAUNCH_STATIC(false, 4, 8); }
+      else     { if (lat) MAASO_LAUNCH_STATIC(true, 4, 0); else MAASO_LAUNCH_STATIC(false, 4, 0); }
     } else {
-      if (lat)
-        hipLaunchKernelGGL((assign_static_kernel<true, 1>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
-      else
-        hipLaunchKernelGGL((assign_static_kernel<false, 1>), dim3(blocks), dim3(kAssignThreads), 0, s, a);
+      if (few) { if (lat) MAASO_LAUNCH_STATIC(true, 1, 8); else MAASO_LAUNCH_STATIC(false, 1, 8); }
+      else     { if (lat) MAASO_LAUNCH_STATIC(true, 1, 0); else MAASO_LAUNCH_STATIC(false, 1, 0); }
     }
+#undef MAASO_LAUNCH_STATIC
     return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
   }
 

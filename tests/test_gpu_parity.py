@@ -187,7 +187,8 @@ def test_assign_config0_full():
 
 @pytest.mark.parametrize("seed,i_pad,n_req,n_slo", [(21, 12, 5000, 3), (22, 1, 300, 1),
                                                     (23, 256, 1200, 16), (24, 64, 70000, 8),
-                                                    (25, 33, 257, 2)])
+                                                    (25, 33, 257, 2), (27, 8, 4003, 3),
+                                                    (28, 5, 999, 4), (29, 9, 1000, 3)])
 def test_assign_static_irregular(seed, i_pad, n_req, n_slo):
     w = W.random_small(seed, 3, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
     w = W.replace(w, n_inst=np.array([i_pad, max(1, i_pad // 2), 0], np.uint32))
