@@ -465,26 +465,29 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
   if (rc != MAASO_OK) return rc;
   WindowWs* ws = static_cast<WindowWs*>(ctx->ws);
   const uint32_t per_window = prm->window < R ? prm->window : R;
-  uint32_t nb = ctx->window_blocks ? ctx->window_blocks : 64u;
+  // Few blocks keep the inter-window barrier short (about 1 us up to 16 blocks, 3.5 us at 64);
+  // lanes per request are then chosen so that a window is scored in one pass.
+  uint32_t nb = ctx->window_blocks ? ctx->window_blocks : 16u;
   if (nb > (uint32_t)ctx->n_cu) nb = (uint32_t)ctx->n_cu;
   if (nb == 0) nb = 1;
   uint32_t lpr = 1;
   while (lpr < 64u && lpr * 2u <= pl->i_pad &&
-         (uint64_t)per_window * (lpr * 2u) <= (uint64_t)nb * kAssignThreads)
+         (uint64_t)per_window * (lpr * 2u) <= (uint64_t)nb * kWindowThreads)
     lpr *= 2u;
-  const uint64_t need = ((uint64_t)per_window * lpr + kAssignThreads - 1) / kAssignThreads;
+  const uint64_t need = ((uint64_t)per_window * lpr + kWindowThreads - 1) / kWindowThreads;
   if (need < nb) nb = (uint32_t)(need ? need : 1);
   hipLaunchKernelGGL(window_init_kernel, dim3(1), dim3(256), 0, s, ws, a.n_satisfied);
   if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
   const uint32_t spin = ctx->spin_limit;
+  const size_t wlds = (size_t)3 * ctx->cells * sizeof(float);  // profile tables in LDS
   TimedRegion timed(ctx, s);
 #define MAASO_LAUNCH_WINDOW(LPR)                                                                  \
   do {                                                                                            \
     if (lat)                                                                                      \
-      hipLaunchKernelGGL((assign_window_kernel<LPR, true>), dim3(nb), dim3(kAssignThreads), 0, s, \
+      hipLaunchKernelGGL((assign_window_kernel<LPR, true>), dim3(nb), dim3(kWindowThreads), wlds, s, \
                          a, prm->window, ws, spin);                                               \
     else                                                                                          \
-      hipLaunchKernelGGL((assign_window_kernel<LPR, false>), dim3(nb), dim3(kAssignThreads), 0, s, \
+      hipLaunchKernelGGL((assign_window_kernel<LPR, false>), dim3(nb), dim3(kWindowThreads), wlds, s, \
                          a, prm->window, ws, spin);                                               \
   } while (0)
   switch (lpr) {

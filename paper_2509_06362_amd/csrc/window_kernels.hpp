@@ -21,6 +21,7 @@
 namespace maaso {
 
 constexpr int kRing = 4;
+constexpr int kWindowThreads = 1024;  // 16 wavefronts: four per SIMD hide the LDS latency of the instance loop
 
 // Global scratch of the windowed kernel (zeroed by window_init_kernel before each call).
 struct WindowWs {
@@ -92,15 +93,17 @@ __device__ __forceinline__ bool grid_barrier(WindowWs* ws, unsigned long long ta
 }
 
 template <int LPR, bool kLat>
-__global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const AssignArgs a,
+__global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const AssignArgs a,
                                                                        uint32_t window,
                                                                        WindowWs* ws,
                                                                        uint32_t spin_limit) {
+  extern __shared__ __align__(16) unsigned char smem[];  // profile tables, read at every window's stage
+  float* tab = reinterpret_cast<float*>(smem);
   __shared__ float4 recs[256];
   __shared__ ClassRow cls[kMaxSlo];
   __shared__ uint32_t n_blk[256];
   __shared__ unsigned long long t_blk[256];
-  __shared__ uint32_t wave_sat[kAssignThreads / 64];
+  __shared__ uint32_t wave_sat[kWindowThreads / 64];
   __shared__ int bar_ok;
 
   const uint32_t tid = threadIdx.x;
@@ -111,8 +114,10 @@ __global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const Ass
   uint64_t q = 0;
   if (tid < n) { tp = a.tp_idx[tid]; B = a.max_batch[tid]; occ = a.occ[tid]; q = a.q_ticks[tid]; }
   if (tid < a.n_slo) cls[tid] = ClassRow{a.d_ttft[tid], a.d_tbt[tid], a.i_ttft[tid], a.i_tbt[tid]};
+  for (uint32_t i = tid; i < 3u * a.cells; i += kWindowThreads) tab[i] = a.tab[i];
+  __syncthreads();
 
-  constexpr uint32_t kReqPerBlock = kAssignThreads / LPR;
+  constexpr uint32_t kReqPerBlock = kWindowThreads / LPR;
   const uint32_t sl = tid % LPR;   // which slice of the instances this lane walks
   const uint32_t rq_in_blk = tid / LPR;
   const uint64_t R = a.n_req;
@@ -120,13 +125,27 @@ __global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const Ass
   uint32_t sat = 0;
   bool alive = true;
 
+  // The request a lane scores first in a window is fetched one window ahead, so that its load
+  // latency overlaps the inter-window barrier instead of following it.
+  uint32_t pf_pl = 0, pf_ol = 0, pf_k = 0;
+  auto prefetch = [&](uint64_t wn) {
+    if (wn >= n_windows) return;
+    const uint64_t s = wn * window;
+    const uint64_t e = (s + window < R) ? s + window : R;
+    const uint64_t r = s + (uint64_t)blockIdx.x * kReqPerBlock + rq_in_blk;
+    if (r < e) { pf_pl = a.prompt_len[r]; pf_ol = a.out_len[r]; pf_k = a.slo_class[r]; }
+  };
+  prefetch(0);
+
   for (uint64_t w = 0; w < n_windows; ++w) {
     const uint64_t s0 = w * window;
     const uint64_t e0 = (s0 + window < R) ? s0 + window : R;
+    uint32_t delta = 0;  // arrival time that passes until the next window opens
+    if (tid < n && e0 < R) delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
     float svc = 1.0f;
     if (tid < n) {
       Staged st;
-      if (stage_instance(a.tab, a.cells, a.mp, tp, B, occ, q, st)) {
+      if (stage_instance(tab, a.cells, a.mp, tp, B, occ, q, st)) {
         recs[tid] = make_float4(st.a, st.p, st.tbt, st.wait);
         svc = st.svc;
       } else {
@@ -136,7 +155,7 @@ __global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const Ass
       n_blk[tid] = 0u;
       t_blk[tid] = 0ull;
     }
-    if (blockIdx.x == 0) {  // recycle the accumulators that window w+2 will use
+    if (blockIdx.x == 0 && tid < 256u) {  // recycle the accumulators that window w+2 will use
       __hip_atomic_store(&ws->ring_n[(w + 2) % kRing][tid], 0u, __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(&ws->ring_t[(w + 2) % kRing][tid], 0ull, __ATOMIC_RELAXED,
@@ -144,26 +163,39 @@ __global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const Ass
     }
     __syncthreads();
 
-    for (uint64_t base = s0 + (uint64_t)blockIdx.x * kReqPerBlock; base < e0;
-         base += (uint64_t)gridDim.x * kReqPerBlock) {
+    const uint64_t base0 = s0 + (uint64_t)blockIdx.x * kReqPerBlock;
+    for (uint64_t base = base0; base < e0; base += (uint64_t)gridDim.x * kReqPerBlock) {
       const uint64_t r = base + rq_in_blk;
       const bool live = r < e0;
+      const bool first = base == base0;
       float best = -INFINITY;
       int32_t idx = -1;
       float L = 0.0f, S = 0.0f;
       Deadlines d{};
       bool class_ok = false;
       if (live) {
-        L = (float)a.prompt_len[r];
-        S = (float)a.out_len[r];
-        const uint32_t k = a.slo_class[r];
+        L = (float)(first ? pf_pl : a.prompt_len[r]);
+        S = (float)(first ? pf_ol : a.out_len[r]);
+        const uint32_t k = first ? pf_k : (uint32_t)a.slo_class[r];
         class_ok = k < a.n_slo;
         if (class_ok) {
           const ClassRow c = cls[k];
           d.Dt = c.Dt; d.Db = c.Db; d.iDt = c.iDt; d.iDb = c.iDb;
           d.De = fmaf(S, c.Db, c.Dt);
           d.iDe = 1.0f / d.De;
-          for (uint32_t j = sl; j < n; j += LPR) {
+          uint32_t j = sl;
+          for (; j + 3u * LPR < n; j += 4u * LPR) {  // four records per trip: one LDS wait for four reads
+            const float4 r0 = recs[j], r1 = recs[j + LPR], r2 = recs[j + 2u * LPR], r3 = recs[j + 3u * LPR];
+            const float s0 = score_triple(r0.x, r0.y, r0.z, r0.w, L, S, d).slack;
+            const float s1 = score_triple(r1.x, r1.y, r1.z, r1.w, L, S, d).slack;
+            const float s2 = score_triple(r2.x, r2.y, r2.z, r2.w, L, S, d).slack;
+            const float s3 = score_triple(r3.x, r3.y, r3.z, r3.w, L, S, d).slack;
+            if (s0 > best) { best = s0; idx = (int32_t)j; }
+            if (s1 > best) { best = s1; idx = (int32_t)(j + LPR); }
+            if (s2 > best) { best = s2; idx = (int32_t)(j + 2u * LPR); }
+            if (s3 > best) { best = s3; idx = (int32_t)(j + 3u * LPR); }
+          }
+          for (; j < n; j += LPR) {
             const float4 rc = recs[j];
             const Margins m = score_triple(rc.x, rc.y, rc.z, rc.w, L, S, d);
             if (m.slack > best) { best = m.slack; idx = (int32_t)j; }
@@ -194,6 +226,7 @@ __global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const Ass
         }
       }
     }
+    prefetch(w + 1);
     __syncthreads();
     if (tid < n && n_blk[tid] != 0u) {
       atomicAdd(&ws->ring_n[w % kRing][tid], n_blk[tid]);
@@ -210,7 +243,6 @@ __global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const Ass
                                         __HIP_MEMORY_SCOPE_AGENT);
       q += __hip_atomic_load(&ws->ring_t[w % kRing][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (e0 < R) {  // time passes until the next window opens
-        const uint32_t delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
         q -= (q < (uint64_t)delta) ? q : (uint64_t)delta;
         const int32_t run = min(occ, (int32_t)B);
         const float x = ((float)run * ((float)delta * 0x1p-20f)) / svc;
@@ -226,7 +258,7 @@ __global__ __launch_bounds__(kAssignThreads) void assign_window_kernel(const Ass
   __syncthreads();
   if (tid == 0 && a.n_satisfied) {
     uint32_t t = 0;
-    for (int wv = 0; wv < kAssignThreads / 64; ++wv) t += wave_sat[wv];
+    for (int wv = 0; wv < kWindowThreads / 64; ++wv) t += wave_sat[wv];
     if (t) atomicAdd(a.n_satisfied, (unsigned long long)t);
   }
 }
