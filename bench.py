@@ -104,6 +104,8 @@ def main() -> int:
     ap.add_argument("--sweep-group", type=int, default=0)
     ap.add_argument("--sweep-bq", type=int, default=0)
     ap.add_argument("--window-blocks", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB copy kernel five times (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)",
@@ -206,6 +208,16 @@ def main() -> int:
             "kernel_ms": k_avg_s * 1e3, "launches_timed": k_n, "alu_frac": alu_frac,
             "bytes_per_request": ASSIGN_BYTES_PER_REQUEST,
         }
+
+    if args.copy_calibration:
+        # a plain elementwise copy of known size (1 GiB read + 1 GiB written per launch), so that
+        # FETCH_SIZE / WRITE_SIZE readings of the kernels above can be scaled to bytes
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     status = binding.maaso_ctx_device_status(dw.ctx)
     result = {

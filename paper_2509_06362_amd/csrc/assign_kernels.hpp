@@ -41,6 +41,8 @@ struct AssignArgs {
   float* e2e;
   unsigned long long* n_satisfied;
   uint32_t* status;
+  unsigned long long* sat_acc;  // [1] admitted-count accumulator of the static kernel; zero between calls
+  uint32_t* sat_done;           // [1] blocks that have delivered their count; zero between calls
 };
 
 __global__ void assign_init_kernel(unsigned long long* n_satisfied) {
@@ -219,14 +221,24 @@ __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const Ass
     const uint64_t r = n_vec * V + threadIdx.x;
     if (r < a.n_req) sat += assign_requests<kLat, 1, NREG>(a, r, n, recs, cls, s2tab, rreg);
   }
-  // block-then-atomic reduction of the admitted count
+  // Admitted count: wavefront shuffle, block sum in LDS, one atomic per block into an accumulator
+  // the library owns and keeps at zero between calls.  Every block then takes a ticket; the block
+  // with the last ticket swaps the total out (leaving zero behind) and writes the output, so no
+  // clearing launch is needed.  All shared words are touched by returning atomics only, each issued
+  // after the previous one has returned, so no cache write-back fence is involved (a fence here would
+  // flush the per-request outputs of the whole kernel out of the L2).
   for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);
   if ((threadIdx.x & 63u) == 0u) wave_sat[threadIdx.x >> 6] = sat;
   __syncthreads();
   if (threadIdx.x == 0 && a.n_satisfied) {
-    uint32_t t = 0;
+    unsigned long long t = 0;
     for (int w = 0; w < kAssignThreads / 64; ++w) t += wave_sat[w];
-    if (t) atomicAdd(a.n_satisfied, (unsigned long long)t);
+    const unsigned long long before = atomicAdd(a.sat_acc, t);
+    const uint32_t ticket = atomicAdd(a.sat_done, 1u + (uint32_t)(before & 0ull));
+    if (ticket == gridDim.x - 1u) {
+      *a.n_satisfied = atomicExch(a.sat_acc, 0ull);
+      atomicExch(a.sat_done, 0u);
+    }
   }
 }
 

@@ -20,6 +20,7 @@ using namespace maaso;
 static_assert(MAASO_MAX_SLO == kMaxSlo, "header and kernels disagree on the class limit");
 
 constexpr uint32_t kMaxTimed = 256;
+constexpr size_t kSmallBytes = 256;
 
 struct maaso_ctx {
   int device;
@@ -153,6 +154,8 @@ void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placement
   a.e2e = out->e2e;
   a.n_satisfied = reinterpret_cast<unsigned long long*>(out->n_satisfied);
   a.status = ctx->status;
+  a.sat_done = ctx->status + 34;
+  a.sat_acc = reinterpret_cast<unsigned long long*>(ctx->status + 36);
 }
 
 }  // namespace
@@ -228,11 +231,14 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   std::memcpy(host + 2 * (size_t)cells, d->tbt, (size_t)cells * 4);
   int rc = MAASO_OK;
   if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->tab), (size_t)3 * cells * 4))) rc = MAASO_E_NOMEM;
-  if (rc == MAASO_OK && !hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->status), 256))) rc = MAASO_E_NOMEM;
+  if (rc == MAASO_OK && !hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->status), kSmallBytes))) rc = MAASO_E_NOMEM;
   if (rc == MAASO_OK) {
-    ctx->cls_count = ctx->status + 16;  // same small allocation: [0] status, [16..31] class counts
+    // one small allocation, in 32-bit words: [0] status, [16..31] class counts, [32..33] evaluated
+    // pairs of the last sweep, [34] delivered-blocks counter and [36..37] admitted-count
+    // accumulator of the static distributor
+    ctx->cls_count = ctx->status + 16;
     if (!hip_ok(hipMemcpy(ctx->tab, host, (size_t)3 * cells * 4, hipMemcpyHostToDevice)) ||
-        !hip_ok(hipMemset(ctx->status, 0, 256)))
+        !hip_ok(hipMemset(ctx->status, 0, kSmallBytes)))
       rc = MAASO_E_HIP;
   }
   std::free(host);
@@ -430,10 +436,11 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
   AssignArgs a;
   fill_assign_args(a, ctx, pl, rq, prm, out);
   const bool lat = out->ttft || out->tbt || out->e2e;
-  if (R == 0 || prm->window == 0u) {
+  if (R == 0) {
     hipLaunchKernelGGL(assign_init_kernel, dim3(1), dim3(64), 0, s, a.n_satisfied);
-    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-    if (R == 0) return MAASO_OK;
+    return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+  }
+  if (prm->window == 0u) {
     // 16-byte accesses, four requests per thread, when every array allows it
     auto al = [](const void* p, uintptr_t m) { return (reinterpret_cast<uintptr_t>(p) & m) == 0; };
     const bool vec = al(rq->prompt_len, 15) && al(rq->out_len, 15) && al(rq->slo_class, 3) &&

@@ -44,7 +44,7 @@ constexpr int kSweepWaves = kSweepThreads / kWave;
 constexpr int kSlotsPerThread = 2;                            // instance slots a thread files per group
 constexpr int kGroupSlots = kSweepThreads * kSlotsPerThread;  // 512 records per LDS buffer
 constexpr int kMaxGroup = 64;                                 // candidates per group (one lane each)
-constexpr int kStageSlotsPerBlock = 2048;
+constexpr int kStageSlotsPerBlock = 512;   // two per thread: short blocks, their loads overlap
 constexpr int kBucketPerBlock = 1024;
 
 __device__ __forceinline__ void raise_status(uint32_t* status, uint32_t bit) {
@@ -136,16 +136,35 @@ __global__ __launch_bounds__(256) void sweep_prep_kernel(const PrepArgs a) {
   __syncthreads();
   const uint64_t n_slots = (uint64_t)a.n_cand * a.i_pad;
   const uint64_t base = (uint64_t)sb * kStageSlotsPerBlock;
-  for (uint32_t u = 0; u < (uint32_t)kStageSlotsPerBlock / 256u; ++u) {
-    const uint64_t s = base + u * 256u + tid;
-    if (s >= n_slots) break;
-    const uint32_t c = (uint32_t)(s / a.i_pad);
-    const uint32_t j = (uint32_t)(s - (uint64_t)c * a.i_pad);
-    if (j == 0u) a.sat_count[c] = 0u;
+  constexpr int kPerThread = kStageSlotsPerBlock / 256;
+  // all loads first, so that their latencies overlap
+  uint32_t tp[kPerThread], B[kPerThread], c_of[kPerThread];
+  int32_t occ[kPerThread];
+  uint64_t q[kPerThread];
+  bool live[kPerThread], valid[kPerThread];
+#pragma unroll
+  for (int u = 0; u < kPerThread; ++u) {
+    const uint64_t s = base + (uint64_t)u * 256u + tid;
+    live[u] = s < n_slots;
+    valid[u] = false;
+    tp[u] = 0; B[u] = 1; occ[u] = 0; q[u] = 0; c_of[u] = 0;
+    if (live[u]) {
+      const uint32_t c = (uint32_t)(s / a.i_pad);
+      const uint32_t j = (uint32_t)(s - (uint64_t)c * a.i_pad);
+      c_of[u] = c;
+      if (j == 0u) a.sat_count[c] = 0u;
+      valid[u] = j < a.n_inst[c];
+      tp[u] = a.tp_idx[s]; B[u] = a.max_batch[s]; occ[u] = a.occ[s]; q[u] = a.q_ticks[s];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kPerThread; ++u) {
+    if (!live[u]) continue;
+    const uint64_t s = base + (uint64_t)u * 256u + tid;
     float4 rec = make_float4(0.0f, 0.0f, INFINITY, INFINITY);  // absent: never listed
-    if (j < a.n_inst[c]) {
+    if (valid[u]) {
       Staged st;
-      if (stage_instance(tab, a.cells, a.mp, a.tp_idx[s], a.max_batch[s], a.occ[s], a.q_ticks[s], st))
+      if (stage_instance(tab, a.cells, a.mp, tp[u], B[u], occ[u], q[u], st))
         rec = make_float4(st.p, st.a, st.wait, st.tbt);
       else
         raise_status(a.status, 2u);
