@@ -83,6 +83,10 @@ def make_workload(name: str):
         return W.config2()
     if name == "stream":
         return W.streaming_shape()
+    if name == "cfg4w":  # config 4 scored capacity-aware: windows of 4096 over its bursty arrivals
+        from dataclasses import replace
+        w = W.config4()
+        return replace(w, name=w.name + "_windowed", window=4096)
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -96,7 +100,10 @@ def cpu_baseline(w, kind: str, budget_triples: float):
         n = int(np.searchsorted(np.cumsum(per_cand), budget_triples)) + 1
         n = max(1, min(n, w.n_cand))
         t0 = time.perf_counter()
-        oracle.placement_sweep(w, 0, n)
+        if w.window:
+            oracle.placement_sweep_windowed(w, window=int(w.window), c_begin=0, c_end=n)
+        else:
+            oracle.placement_sweep(w, 0, n)
         dt = time.perf_counter() - t0
         triples = int(per_cand[:n].sum())
         sample = f"candidates [0,{n}) of {w.n_cand} x all {w.n_req} requests, {triples:.3e} triples"
@@ -121,9 +128,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="cfg1",
-                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "stream"])
+                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-triples", type=float, default=1.0e9,
+    ap.add_argument("--cpu-triples", type=float, default=3.0e9,
                     help="size of the oracle's timed sample, in triples")
     ap.add_argument("--sweep-q", type=int, default=0)
     ap.add_argument("--sweep-group", type=int, default=0)
@@ -147,6 +154,7 @@ def main() -> int:
     binding.load_library()
     w = make_workload(args.workload)
     kind = "sweep" if w.n_cand > 1 else "assign"
+    sweep_window = int(w.window) if kind == "sweep" else 0
     dw = binding.DeviceWorkload(w)
     binding.maaso_ctx_set_launch_shape(dw.ctx, args.sweep_q, args.sweep_group, args.sweep_bq,
                                        args.window_blocks)
@@ -164,14 +172,14 @@ def main() -> int:
     if kind == "sweep":
         # the distributor runs on the winning deployment; its index is fixed by a first sweep so
         # that the timed steps need no device-to-host copy
-        dw.sweep(out=sweep_out)
+        dw.sweep(out=sweep_out, window=sweep_window)
         torch.cuda.synchronize()
         best = int(sweep_out[2].item())
         triples_sweep = w.valid_triples()
         triples_assign = w.n_req * int(w.n_inst[best])
 
         def step():
-            dw.sweep(out=sweep_out, stream=stream)
+            dw.sweep(out=sweep_out, stream=stream, window=sweep_window)
             dw.assign(cand=best, window=0, latencies=False, out=assign_out, stream=stream)
     else:
         best = 0
@@ -198,14 +206,24 @@ def main() -> int:
     n_timed = min(args.steps, 100)
     for _ in range(n_timed):
         if kind == "sweep":
-            dw.sweep(out=sweep_out, stream=stream)
+            dw.sweep(out=sweep_out, stream=stream, window=sweep_window)
         else:
             step()
     torch.cuda.synchronize()
     k_ms, k_n = binding.maaso_ctx_kernel_elapsed(dw.ctx)
     binding.maaso_ctx_kernel_timing(dw.ctx, False)
     k_avg_s = k_ms / max(k_n, 1) * 1e-3
-    if kind == "sweep":
+    if kind == "sweep" and sweep_window:
+        ops = ASSIGN_LANEOPS_PER_TRIPLE * triples_sweep
+        roofline = {
+            "kernel": "sweep_window_kernel", "bound": "alu",
+            "achieved": ops / k_avg_s / 1e12, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
+            "frac": ops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS, "traffic": measured_traffic(w.name),
+            "kernel_ms": k_avg_s * 1e3, "launches_timed": k_n,
+            "laneops_per_triple": ASSIGN_LANEOPS_PER_TRIPLE,
+            "kernel_triples_per_s": triples_sweep / k_avg_s,
+        }
+    elif kind == "sweep":
         pairs = binding.maaso_ctx_sweep_evaluated(dw.ctx)  # pairs that reached the latency loop
         ops = SWEEP_LANEOPS_PER_PAIR * pairs
         roofline = {

@@ -188,11 +188,16 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
 
 /* Placer: SLO-satisfaction count and ratio of every candidate deployment against the whole request
  * set, and the best candidate - the evaluation of Phi_S^n(I', R_x) that Alg. 1 performs for each
- * candidate deployment I' (Eq. 3, Eq. 6).  A request counts for candidate c iff some valid instance
- * of c has slack >= 0 (the same triple arithmetic as maaso_score_assign, static state).
+ * candidate deployment I' (Eq. 3, Eq. 6).
+ *   prm->window == 0 (static): a request counts for candidate c iff some valid instance of c has
+ *     slack >= 0 against the state as given (the same triple arithmetic as maaso_score_assign).
+ *   prm->window  > 0 (capacity-aware): every candidate is run through the windowed distributor of
+ *     maaso_score_assign on its own copy of its instance state, so admitted requests load the
+ *     instances and later windows see it (the stand-in for the paper's virtual-slot simulator,
+ *     Sec. V-A); the count is the number of admitted requests.  rq->arrival_ticks is required.
  * Outputs, DEVICE pointers: sat_count [C] (required), sat_ratio [C] = count / R (0 when R == 0; may
  * be NULL), best_cand [1] = lowest index among the largest counts (may be NULL).
- * prm->window must be 0.  The placements are not written.
+ * The placements are not written in either form.
  * Errors: INVALID_ARG, SHAPE, HIP, NOMEM. */
 int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,

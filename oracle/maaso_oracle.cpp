@@ -282,6 +282,45 @@ int oracle_placement_sweep(uint32_t n_tp, uint32_t b_cap, const float* prefill_a
   return 0;
 }
 
+// Placer with capacity-aware scoring: every candidate of [c_begin, c_end) is run through the windowed
+// distributor above, on its own copy of its instance state (the candidates do not interact and the
+// caller's state is not modified).  sat_count[c] is the number of requests admitted over all
+// windows; ratio and best candidate as in the static sweep.  Returns 0, -1 bad arguments.
+int oracle_placement_sweep_windowed(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
+                                    const float* prefill_p, const float* tbt, uint32_t n_slo,
+                                    const float* d_ttft, const float* d_tbt, uint32_t n_cand,
+                                    uint32_t i_pad, const uint32_t* n_inst, const uint8_t* tp_idx,
+                                    const uint16_t* max_batch, const int32_t* occ,
+                                    const uint64_t* q_ticks, uint32_t n_req,
+                                    const uint32_t* prompt_len, const uint32_t* out_len,
+                                    const uint8_t* slo_class, const uint32_t* arrival_ticks,
+                                    float s_bar, float pen_kappa, uint32_t tbt_mode, uint32_t window,
+                                    uint32_t c_begin, uint32_t c_end, uint32_t* sat_count,
+                                    float* sat_ratio, uint32_t* best_cand) {
+  if (c_end > n_cand || window == 0) return -1;
+  std::vector<int32_t> occ_c(i_pad);
+  std::vector<uint64_t> q_c(i_pad);
+  uint32_t best_c = c_begin, best_n = 0;
+  bool have = false;
+  for (uint32_t c = c_begin; c < c_end; ++c) {
+    const size_t base = (size_t)c * i_pad;
+    std::copy(occ + base, occ + base + i_pad, occ_c.begin());
+    std::copy(q_ticks + base, q_ticks + base + i_pad, q_c.begin());
+    uint64_t sat = 0;
+    const int rc = oracle_score_assign(n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt,
+                                       std::min(n_inst[c], i_pad), tp_idx + base, max_batch + base,
+                                       occ_c.data(), q_c.data(), n_req, prompt_len, out_len, slo_class,
+                                       arrival_ticks, s_bar, pen_kappa, tbt_mode, window, nullptr,
+                                       nullptr, nullptr, nullptr, nullptr, &sat);
+    if (rc != 0) return rc;
+    sat_count[c] = (uint32_t)sat;
+    sat_ratio[c] = (n_req == 0) ? 0.0f : (float)sat / (float)n_req;
+    if (!have || (uint32_t)sat > best_n) { best_n = (uint32_t)sat; best_c = c; have = true; }
+  }
+  if (best_cand) *best_cand = best_c;
+  return 0;
+}
+
 // Independent second route to the static sweep's counts.  For a fixed (instance, class) the first-
 // token latency is non-decreasing in prompt length and the end-to-end margin is implied by the other
 // two, so feasibility reduces to "tbt within its deadline and prompt_len <= Lmax"; Lmax is found by

@@ -241,11 +241,12 @@ def maaso_score_assign(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch
 
 
 def maaso_placement_sweep(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
-                          n_req, prompt_len, out_len, slo_class, s_bar, pen_kappa=0.0, tbt_mode=0,
-                          window=0, sat_count, sat_ratio=None, best_cand=None, stream=None) -> None:
+                          n_req, prompt_len, out_len, slo_class, arrival_ticks=None, s_bar,
+                          pen_kappa=0.0, tbt_mode=0, window=0, sat_count, sat_ratio=None,
+                          best_cand=None, stream=None) -> None:
     import torch
     pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
-    rq = _requests(n_req, prompt_len, out_len, slo_class, None)
+    rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
     prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window))
     _check(load_library().maaso_placement_sweep(
         ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm), _dptr(sat_count, torch.int32),
@@ -290,8 +291,9 @@ class DeviceWorkload:
         return dict(s_bar=float(self.w.s_bar), pen_kappa=float(self.w.pen_kappa),
                     tbt_mode=int(self.w.tbt_mode))
 
-    def sweep(self, stream=None, out=None):
-        """maaso_placement_sweep over all candidates; returns (sat_count, sat_ratio, best_cand)."""
+    def sweep(self, stream=None, out=None, window=0):
+        """maaso_placement_sweep over all candidates; returns (sat_count, sat_ratio, best_cand).
+        window > 0 selects the capacity-aware form."""
         import torch
         dev = self.prompt_len.device
         C_ = self.w.n_cand
@@ -302,6 +304,7 @@ class DeviceWorkload:
         maaso_placement_sweep(
             self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
             max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, **self.request_args(),
+            arrival_ticks=self.arrival_ticks if window else None, window=window,
             **self.param_args(), sat_count=out[0], sat_ratio=out[1], best_cand=out[2], stream=stream)
         return out
 

@@ -13,6 +13,7 @@
 
 #include "assign_kernels.hpp"
 #include "sweep_kernels.hpp"
+#include "sweep_window_kernels.hpp"
 #include "window_kernels.hpp"
 
 using namespace maaso;
@@ -299,12 +300,54 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
                           uint32_t* best_cand, void* hip_stream) {
   int rc = check_common(ctx, pl, rq, prm);
   if (rc != MAASO_OK) return rc;
-  if (!sat_count || prm->window != 0u) return MAASO_E_INVALID_ARG;
+  if (!sat_count) return MAASO_E_INVALID_ARG;
+  if (prm->window != 0u && rq->n_req != 0 && !rq->arrival_ticks) return MAASO_E_INVALID_ARG;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
   const uint32_t C = pl->n_cand, I = pl->i_pad, K = ctx->n_slo, R = rq->n_req;
+
+  if (prm->window != 0u && R != 0) {
+    // Capacity-aware form: one block per candidate walks the request windows on its own state copy.
+    SweepWindowArgs a;
+    a.tab = ctx->tab;
+    a.cells = ctx->cells;
+    a.mp = model_params(ctx, prm);
+    a.n_slo = K;
+    std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
+    std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
+    std::memcpy(a.i_ttft, ctx->i_ttft, sizeof(a.i_ttft));
+    std::memcpy(a.i_tbt, ctx->i_tbt, sizeof(a.i_tbt));
+    a.n_cand = C;
+    a.i_pad = I;
+    a.n_inst = pl->n_inst;
+    a.tp_idx = pl->tp_idx;
+    a.max_batch = pl->max_batch;
+    a.occ = pl->occ;
+    a.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
+    a.n_req = R;
+    a.prompt_len = rq->prompt_len;
+    a.out_len = rq->out_len;
+    a.slo_class = rq->slo_class;
+    a.arrival_ticks = rq->arrival_ticks;
+    a.window = prm->window;
+    a.sat_count = sat_count;
+    a.status = ctx->status;
+    {
+      TimedRegion timed(ctx, s);
+      hipLaunchKernelGGL(sweep_window_kernel, dim3(C), dim3(kAssignThreads),
+                         (size_t)3 * ctx->cells * sizeof(float), s, a);
+      if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+    }
+    unsigned long long* eval_total = reinterpret_cast<unsigned long long*>(ctx->status + 32);
+    hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
+                       best_cand, ctx->cls_count, static_cast<const unsigned long long*>(nullptr), 0u,
+                       eval_total);
+    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+    ctx->last_evaluated = nullptr;
+    return MAASO_OK;
+  }
 
   // Launch shape.  Q requests per lane (a block owns 256*Q requests of one class); G candidates per
   // work item; bq persistent blocks per (request tile, XCD) queue.

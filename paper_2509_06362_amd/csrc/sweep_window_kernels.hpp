@@ -1,0 +1,184 @@
+// Placer with capacity-aware scoring: every candidate deployment is run through the windowed
+// distributor on its own copy of its instance state - the stand-in for the paper's virtual-slot
+// simulator (Sec. V-A "Simulator Implementation") inside the evaluation of a candidate (Alg. 1).
+//
+// Candidates do not interact, so one block owns one candidate and walks the windows by itself: no
+// device-wide barrier.  Thread j keeps instance j's live state (occupancy, queued prefill ticks) in
+// registers; per window the block stages its instances into LDS records, fills the per-(class,
+// instance) between-token margins, scores the window's requests (lanes = requests, four in flight
+// per lane, broadcast LDS reads of the records), adds the admitted load with integer LDS atomics
+// (aggregated per wavefront when all its admitted requests chose the same instance, the common case
+// when a window herds onto the instance with the most slack), and advances the state exactly as the
+// distributor does.
+#pragma once
+
+#include "assign_kernels.hpp"
+
+#pragma clang fp contract(off)
+
+namespace maaso {
+
+struct SweepWindowArgs {
+  const float* tab;
+  uint32_t cells;
+  ModelParams mp;
+  uint32_t n_slo;
+  float d_ttft[kMaxSlo], d_tbt[kMaxSlo], i_ttft[kMaxSlo], i_tbt[kMaxSlo];
+  uint32_t n_cand, i_pad;
+  const uint32_t* n_inst;
+  const uint8_t* tp_idx;
+  const uint16_t* max_batch;
+  const int32_t* occ;
+  const uint64_t* q_ticks;
+  uint32_t n_req;
+  const uint32_t* prompt_len;
+  const uint32_t* out_len;
+  const uint8_t* slo_class;
+  const uint32_t* arrival_ticks;
+  uint32_t window;
+  uint32_t* sat_count;
+  uint32_t* status;
+};
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  return v;
+}
+
+__global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const SweepWindowArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* tab = reinterpret_cast<float*>(smem);
+  __shared__ float4 recs[256];
+  __shared__ ClassRow cls[kMaxSlo];
+  __shared__ float s2tab[kMaxSlo * kS2Stride];
+  __shared__ uint32_t n_blk[256];
+  __shared__ unsigned long long t_blk[256];
+  __shared__ uint32_t wave_sat[kAssignThreads / 64];
+
+  const uint32_t tid = threadIdx.x;
+  const uint32_t c = blockIdx.x;
+  const size_t base = (size_t)c * a.i_pad;
+  const uint32_t n = min(a.n_inst[c], a.i_pad);
+  uint32_t tp = 0, B = 1;
+  int32_t occ = 0;
+  uint64_t q = 0;
+  if (tid < n) {
+    tp = a.tp_idx[base + tid]; B = a.max_batch[base + tid];
+    occ = a.occ[base + tid]; q = a.q_ticks[base + tid];
+  }
+  if (tid < a.n_slo) cls[tid] = ClassRow{a.d_ttft[tid], a.d_tbt[tid], a.i_ttft[tid], a.i_tbt[tid]};
+  for (uint32_t i = tid; i < 3u * a.cells; i += kAssignThreads) tab[i] = a.tab[i];
+  __syncthreads();
+
+  const uint64_t R = a.n_req;
+  const uint64_t n_windows = (R + a.window - 1) / a.window;
+  uint32_t sat = 0;
+  constexpr int V = 4;
+
+  for (uint64_t w = 0; w < n_windows; ++w) {
+    const uint64_t s0 = w * a.window;
+    const uint64_t e0 = (s0 + a.window < R) ? s0 + a.window : R;
+    uint32_t delta = 0;
+    if (tid < n && e0 < R) delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
+    float svc = 1.0f;
+    if (tid < n) {
+      Staged st;
+      if (stage_instance(tab, a.cells, a.mp, tp, B, occ, q, st)) {
+        recs[tid] = make_float4(st.a, st.p, st.tbt, st.wait);
+        svc = st.svc;
+      } else {
+        raise_status(a.status, 2u);
+        recs[tid] = make_float4(1.0f, 1.0f, 1.0f, INFINITY);
+      }
+      n_blk[tid] = 0u;
+      t_blk[tid] = 0ull;
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < a.n_slo * n; i += kAssignThreads) {
+      const uint32_t k = i / n, j = i - k * n;
+      s2tab[k * kS2Stride + j] = (a.d_tbt[k] - recs[j].z) * a.i_tbt[k];
+    }
+    __syncthreads();
+
+    for (uint64_t b0 = s0; b0 < e0; b0 += (uint64_t)V * kAssignThreads) {
+      float L[V], S[V], Dt[V], iDt[V], De[V], iDe[V], best[V], bpre[V];
+      uint32_t k[V];
+      int32_t idx[V];
+      bool live[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const uint64_t r = b0 + (uint64_t)v * kAssignThreads + tid;
+        live[v] = r < e0;
+        uint32_t pl = 0, ol = 0;
+        k[v] = 0;
+        if (live[v]) { pl = a.prompt_len[r]; ol = a.out_len[r]; k[v] = a.slo_class[r]; }
+        if (k[v] >= a.n_slo) { raise_status(a.status, 1u); live[v] = false; k[v] = 0; }
+        L[v] = (float)pl; S[v] = (float)ol;
+        const ClassRow cr = cls[k[v]];
+        Dt[v] = cr.Dt; iDt[v] = cr.iDt;
+        De[v] = fmaf(S[v], cr.Db, cr.Dt);
+        iDe[v] = 1.0f / De[v];
+        best[v] = -INFINITY; idx[v] = -1; bpre[v] = 0.0f;
+      }
+      for (uint32_t j = 0; j < n; ++j) {
+        const float4 r = recs[j];  // a, p, tbt, wait
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          const float pre = fmaf(r.y, L[v], r.x);
+          const float ttft = r.w + pre;
+          const float e2e = fmaf(S[v], r.z, ttft);
+          const float s1 = (Dt[v] - ttft) * iDt[v];
+          const float s2 = s2tab[k[v] * kS2Stride + j];
+          const float s3 = (De[v] - e2e) * iDe[v];
+          const float slack = fminf(fminf(s1, s2), s3);
+          if (slack > best[v]) { best[v] = slack; idx[v] = (int32_t)j; bpre[v] = pre; }
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const bool adm = live[v] && best[v] >= 0.0f;  // admitted requests load their instance
+        const uint64_t am = __ballot(adm);
+        if (am == 0ull) continue;
+        sat += adm ? 1u : 0u;
+        const unsigned long long ticks = adm ? (unsigned long long)__float2ll_rn(bpre[v] * 1048576.0f) : 0ull;
+        const int32_t first = __builtin_amdgcn_readlane(idx[v], __builtin_ctzll(am));
+        if (__ballot(adm && idx[v] == first) == am) {  // the whole wavefront chose one instance
+          const unsigned long long tsum = wave_sum_u64(ticks);
+          if ((tid & 63u) == 0u) {
+            atomicAdd(&n_blk[first], (uint32_t)__popcll(am));
+            atomicAdd(&t_blk[first], tsum);
+          }
+        } else if (adm) {
+          atomicAdd(&n_blk[idx[v]], 1u);
+          atomicAdd(&t_blk[idx[v]], ticks);
+        }
+      }
+    }
+    __syncthreads();
+
+    if (tid < n) {
+      occ += (int32_t)n_blk[tid];
+      q += t_blk[tid];
+      if (e0 < R) {  // time passes until the next window opens
+        q -= (q < (uint64_t)delta) ? q : (uint64_t)delta;
+        const int32_t run = min(occ, (int32_t)B);
+        const float x = ((float)run * ((float)delta * 0x1p-20f)) / svc;
+        const int32_t done = min(occ, (int32_t)floorf(fminf(x, 2147483520.0f)));
+        occ -= done;
+      }
+    }
+    // the next stage rewrites recs / n_blk / t_blk: every thread must have finished reading them
+    __syncthreads();
+  }
+
+  for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);
+  if ((tid & 63u) == 0u) wave_sat[tid >> 6] = sat;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t t = 0;
+    for (int wv = 0; wv < kAssignThreads / 64; ++wv) t += wave_sat[wv];
+    a.sat_count[c] = t;
+  }
+}
+
+}  // namespace maaso

@@ -175,6 +175,68 @@ def test_sweep_full_size(cfg, n_sample):
 
 
 # ------------------------------------------------------------------------------------------------
+# placer sweep, capacity-aware (windowed)
+# ------------------------------------------------------------------------------------------------
+
+def check_sweep_windowed(w, window, sampled=None):
+    dw = binding.DeviceWorkload(w)
+    try:
+        print(f"windowed sweep {w.name} C={w.n_cand} I={w.i_pad} R={w.n_req} window={window}", flush=True)
+        cnt, ratio, best = dw.sweep(window=window)
+        torch.cuda.synchronize()
+        cnt, ratio, best = u32(cnt), ratio.cpu().numpy(), int(u32(best)[0])
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        if sampled is None:
+            ref = oracle.placement_sweep_windowed(w, window=window)
+            assert np.array_equal(cnt, ref["sat_count"])
+            assert np.array_equal(ratio, ref["sat_ratio"])
+            assert best == ref["best_cand"]
+        else:
+            for c in sampled:
+                one = oracle.placement_sweep_windowed(w, window=window, c_begin=c, c_end=c + 1)
+                assert cnt[c] == one["sat_count"][c], f"candidate {c}"
+                assert ratio[c] == one["sat_ratio"][c]
+            assert best == int(np.argmax(cnt))
+        assert np.array_equal(dw.occ.cpu().numpy(), w.occ)            # the caller's state is untouched
+        return cnt
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("seed,n_cand,i_pad,n_req,n_slo,window", [
+    (61, 30, 16, 3000, 3, 256), (62, 12, 1, 700, 1, 64), (63, 9, 48, 2500, 5, 1000),
+    (64, 6, 128, 1500, 8, 100), (65, 4, 256, 900, 16, 333), (66, 20, 7, 300, 2, 1),
+    (67, 10, 32, 2000, 3, 5000),
+])
+def test_windowed_sweep_small_irregular(seed, n_cand, i_pad, n_req, n_slo, window):
+    w = W.random_small(seed, n_cand, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
+    spread = 0
+    for v in (w, W.stressed(w, seed=seed, deadline_scale=0.25),
+              W.stressed(w, seed=seed, deadline_scale=0.03)):
+        cnt = check_sweep_windowed(v, window)
+        spread = max(spread, len(np.unique(cnt)))
+    assert spread > 1
+
+
+def test_windowed_sweep_one_window_equals_static_sweep():
+    w = W.stressed(W.config1(n_cand=64, n_req=4096), seed=9)
+    w = W.replace(w, arrival_ticks=W.poisson_arrivals(W.rng_for(9, 3), 2000.0, 4096))
+    a = check_sweep(w)
+    b = check_sweep_windowed(w, 4096)
+    assert np.array_equal(a, b)
+
+
+def test_windowed_sweep_config4_shape():
+    """Config 4 with its bursty arrivals, windows of 4096: reduced in full, full size on a sample."""
+    small = W.config4(n_cand=24, n_req=16384)
+    check_sweep_windowed(small, 4096)
+    check_sweep_windowed(W.stressed(small, seed=4), 1024)
+    full = W.config4()
+    rng = np.random.default_rng(44)
+    check_sweep_windowed(full, 4096, sampled=sorted(rng.choice(full.n_cand, 6, replace=False).tolist()))
+
+
+# ------------------------------------------------------------------------------------------------
 # distributor, static
 # ------------------------------------------------------------------------------------------------
 
@@ -316,7 +378,7 @@ def test_host_side_argument_errors():
 
     sweep, assign = binding.maaso_placement_sweep, binding.maaso_score_assign
     assert status(sweep, sat_count=None) == -1
-    assert status(sweep, sat_count=cnt, window=4) == -1
+    assert status(sweep, sat_count=cnt, window=4) == -1                 # windowed without arrivals
     assert status(sweep, sat_count=cnt, i_pad=257) == -2
     assert status(sweep, sat_count=cnt, i_pad=0) == -2
     assert status(sweep, sat_count=cnt, s_bar=0.0) == -1
