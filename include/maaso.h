@@ -203,6 +203,41 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
                           const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
                           uint32_t* best_cand, void* hip_stream);
 
+/* Weights and thresholds of the composite serving score (Sec. IV-D, Eq. 6): alpha prioritises SLO
+ * satisfaction (the paper uses 4, and 10 in its ablation), beta in [0,1] balances throughput against
+ * latency (0.3), gamma_t > 0 is the throughput that normalises to 1 (tokens/s), gamma_l > 0 the
+ * largest acceptable queuing latency (seconds). */
+typedef struct {
+  float alpha, beta, gamma_t, gamma_l;
+} maaso_score_weights;
+
+/* Per-candidate outputs of maaso_placement_score.  DEVICE pointers, [C] each; sat_count and score
+ * are required, the others may be NULL.  best_cand [1] (may be NULL): lowest index among the largest
+ * scores. */
+typedef struct {
+  uint32_t* sat_count; /* admitted requests                                              */
+  float* phi_s;        /* Phi_S^n = sat_count / R (0 when R == 0)                        */
+  float* phi_t;        /* Phi_T: sum of 1 / tbt_j over the instances that served a request */
+  float* phi_l;        /* Phi_L: mean queue wait of the admitted requests, seconds       */
+  float* score;        /* Phi                                                            */
+  uint32_t* best_cand;
+} maaso_score_out;
+
+/* Placer objective: the composite serving score Phi(I', R_x) of every candidate deployment
+ * (Sec. IV-D, Eq. 6-8; the quantity Alg. 1 compares).  Each candidate is run through the distributor
+ * of maaso_score_assign - against the state as given when prm->window == 0, window by window on a
+ * copy of its state when prm->window > 0 (rq->arrival_ticks required) - and
+ *   Phi = alpha * Phi_S^n + beta * min(Phi_T, gamma_t) / gamma_t + (1 - beta) * max(gamma_l - Phi_L, 0) / gamma_l
+ * with Phi_S^n the admitted fraction (Eq. 3), Phi_T the sum, in index order, of 1 / tbt_j over the
+ * instances that served at least one request (tbt_j as staged for the first window; Eq. 4) and Phi_L
+ * the mean over the admitted requests of their instance's queue wait at admission, taken from the
+ * exact integer sum of the waits in ticks (Eq. 5).  Every float operation is a single binary32
+ * operation in a fixed order, so the result does not depend on scheduling.
+ * The placements are not written.  Errors: INVALID_ARG, SHAPE, HIP. */
+int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                          const maaso_params* prm, const maaso_score_weights* wts,
+                          const maaso_score_out* out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,7 +46,8 @@ def load():
         _lib = C.CDLL(str(LIB))
         _lib.oracle_triple.restype = None
         for name in ("oracle_stage", "oracle_score_assign", "oracle_placement_sweep",
-                     "oracle_placement_sweep_windowed", "oracle_threshold_sweep"):
+                     "oracle_placement_sweep_windowed", "oracle_placement_score",
+                     "oracle_threshold_sweep"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -161,6 +162,31 @@ def placement_sweep_windowed(w, window=None, c_begin: int = 0, c_end=None, tbt_m
     if rc != 0:
         raise ValueError(f"oracle_placement_sweep_windowed rejected its arguments (rc={rc})")
     return dict(sat_count=cnt, sat_ratio=ratio, best_cand=int(best.value))
+
+
+def placement_score(w, alpha, beta, gamma_t, gamma_l, window=0, c_begin: int = 0, c_end=None,
+                    tbt_mode=None):
+    """Composite serving score of candidates [c_begin, c_end) (window 0 = static)."""
+    lib = load()
+    c_end = w.n_cand if c_end is None else c_end
+    if window and w.arrival_ticks is None:
+        raise ValueError("windowed scoring needs arrival_ticks")
+    cnt = np.zeros(w.n_cand, np.uint32)
+    ps, pt, pl, sc = (np.zeros(w.n_cand, np.float32) for _ in range(4))
+    best = C.c_uint32(0)
+    rc = lib.oracle_placement_score(
+        *_profile_args(w), *_slo_args(w), C.c_uint32(w.n_cand), C.c_uint32(w.i_pad),
+        _ptr(w.n_inst, C.c_uint32), _ptr(w.tp_idx, C.c_uint8), _ptr(w.max_batch, C.c_uint16),
+        _ptr(w.occ, C.c_int32), _ptr(w.q_ticks, C.c_uint64), C.c_uint32(w.n_req),
+        _ptr(w.prompt_len, C.c_uint32), _ptr(w.out_len, C.c_uint32), _ptr(w.slo_class, C.c_uint8),
+        _ptr(w.arrival_ticks, C.c_uint32), C.c_float(float(w.s_bar)), C.c_float(float(w.pen_kappa)),
+        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window),
+        C.c_float(alpha), C.c_float(beta), C.c_float(gamma_t), C.c_float(gamma_l),
+        C.c_uint32(c_begin), C.c_uint32(c_end), _ptr(cnt, C.c_uint32), _ptr(ps, C.c_float),
+        _ptr(pt, C.c_float), _ptr(pl, C.c_float), _ptr(sc, C.c_float), C.byref(best))
+    if rc != 0:
+        raise ValueError(f"oracle_placement_score rejected its arguments (rc={rc})")
+    return dict(sat_count=cnt, phi_s=ps, phi_t=pt, phi_l=pl, score=sc, best_cand=int(best.value))
 
 
 def threshold_sweep(w, tbt_mode=None):

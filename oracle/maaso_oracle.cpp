@@ -150,24 +150,34 @@ void oracle_triple(float a, float p, float tbt_j, float wait, uint32_t prompt_le
   out[6] = t.slack;
 }
 
-// Distributor over one placement (the first n_inst slots of the arrays given).
-//   window == 0 : every request scores against the given state; the state is left untouched.
-//   window  > 0 : requests are taken in windows of that many; all requests of a window see the state
-//                 at the window's start; after each window the state is advanced (occ, q_ticks are
-//                 updated in place).
-// Per-request outputs (each may be NULL): chosen instance (-1 if there is none), its slack, and the
-// chosen instance's ttft / tbt / e2e latencies (NaN if there is none).  Returns 0, -1 bad profile.
-int oracle_score_assign(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
-                        const float* prefill_p, const float* tbt, uint32_t n_slo,
-                        const float* d_ttft, const float* d_tbt, uint32_t n_inst,
-                        const uint8_t* tp_idx, const uint16_t* max_batch, int32_t* occ,
-                        uint64_t* q_ticks, uint32_t n_req, const uint32_t* prompt_len,
-                        const uint32_t* out_len, const uint8_t* slo_class,
-                        const uint32_t* arrival_ticks, float s_bar, float pen_kappa,
-                        uint32_t tbt_mode, uint32_t window, int32_t* chosen, float* slack,
-                        float* lat_ttft, float* lat_tbt, float* lat_e2e, uint64_t* n_satisfied) {
+}  // extern "C"
+
+namespace {
+
+// What the serving score needs to know about a run of the distributor, beyond the admitted count.
+struct RunStats {
+  std::vector<uint64_t> admitted_per_inst;  // requests admitted to each instance, all windows
+  std::vector<float> tbt_first;             // per-token latency of each instance in the first window
+  uint64_t wait_ticks = 0;                  // sum over admitted requests of their instance's queue
+                                            // wait at admission, in ticks of 2^-20 s (lrintf)
+};
+
+// The distributor proper; see oracle_score_assign for the contract.  `stats` may be null.
+int distributor(uint32_t n_tp, uint32_t b_cap, const float* prefill_a, const float* prefill_p,
+                const float* tbt, uint32_t n_slo, const float* d_ttft, const float* d_tbt,
+                uint32_t n_inst, const uint8_t* tp_idx, const uint16_t* max_batch, int32_t* occ,
+                uint64_t* q_ticks, uint32_t n_req, const uint32_t* prompt_len,
+                const uint32_t* out_len, const uint8_t* slo_class, const uint32_t* arrival_ticks,
+                float s_bar, float pen_kappa, uint32_t tbt_mode, uint32_t window, int32_t* chosen,
+                float* slack, float* lat_ttft, float* lat_tbt, float* lat_e2e, uint64_t* n_satisfied,
+                RunStats* stats) {
   Profile pf{n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt};
   if (!profile_ok(pf)) return -1;
+  if (stats) {
+    stats->admitted_per_inst.assign(n_inst, 0);
+    stats->tbt_first.assign(n_inst, 0.0f);
+    stats->wait_ticks = 0;
+  }
   std::vector<float> iDt(n_slo), iDb(n_slo);
   for (uint32_t k = 0; k < n_slo; ++k) {
     iDt[k] = recip_deadline(d_ttft[k]);
@@ -186,6 +196,8 @@ int oracle_score_assign(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
                              tbt_mode);
     std::fill(n_new.begin(), n_new.end(), 0u);
     std::fill(t_new.begin(), t_new.end(), (uint64_t)0);
+    if (stats && s == 0)
+      for (uint32_t j = 0; j < n_inst; ++j) stats->tbt_first[j] = st[j].tbt;
     for (uint32_t r = (uint32_t)s; r < e; ++r) {
       const float L = (float)prompt_len[r], S = (float)out_len[r];
       const uint32_t k = slo_class[r];
@@ -202,6 +214,10 @@ int oracle_score_assign(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
       const bool admitted = best >= 0.0f;
       if (admitted) {
         ++sat;
+        if (stats) {
+          stats->admitted_per_inst[idx] += 1;
+          stats->wait_ticks += (uint64_t)lrintf(st[idx].wait * 1048576.0f);
+        }
         if (window != 0) {
           n_new[idx] += 1;
           t_new[idx] += (uint64_t)lrintf(bt.pre * 1048576.0f);
@@ -230,6 +246,32 @@ int oracle_score_assign(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
   }
   if (n_satisfied) *n_satisfied = sat;
   return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Distributor over one placement (the first n_inst slots of the arrays given).
+//   window == 0 : every request scores against the given state; the state is left untouched.
+//   window  > 0 : requests are taken in windows of that many; all requests of a window see the state
+//                 at the window's start; after each window the state is advanced (occ, q_ticks are
+//                 updated in place).
+// Per-request outputs (each may be NULL): chosen instance (-1 if there is none), its slack, and the
+// chosen instance's ttft / tbt / e2e latencies (NaN if there is none).  Returns 0, -1 bad profile.
+int oracle_score_assign(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
+                        const float* prefill_p, const float* tbt, uint32_t n_slo,
+                        const float* d_ttft, const float* d_tbt, uint32_t n_inst,
+                        const uint8_t* tp_idx, const uint16_t* max_batch, int32_t* occ,
+                        uint64_t* q_ticks, uint32_t n_req, const uint32_t* prompt_len,
+                        const uint32_t* out_len, const uint8_t* slo_class,
+                        const uint32_t* arrival_ticks, float s_bar, float pen_kappa,
+                        uint32_t tbt_mode, uint32_t window, int32_t* chosen, float* slack,
+                        float* lat_ttft, float* lat_tbt, float* lat_e2e, uint64_t* n_satisfied) {
+  return distributor(n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt, n_inst, tp_idx,
+                     max_batch, occ, q_ticks, n_req, prompt_len, out_len, slo_class, arrival_ticks,
+                     s_bar, pen_kappa, tbt_mode, window, chosen, slack, lat_ttft, lat_tbt, lat_e2e,
+                     n_satisfied, nullptr);
 }
 
 // Placer: static score of candidates [c_begin, c_end) of a [n_cand][i_pad] placement table against
@@ -316,6 +358,64 @@ int oracle_placement_sweep_windowed(uint32_t n_tp, uint32_t b_cap, const float* 
     sat_count[c] = (uint32_t)sat;
     sat_ratio[c] = (n_req == 0) ? 0.0f : (float)sat / (float)n_req;
     if (!have || (uint32_t)sat > best_n) { best_n = (uint32_t)sat; best_c = c; have = true; }
+  }
+  if (best_cand) *best_cand = best_c;
+  return 0;
+}
+
+// Composite serving score of every candidate of [c_begin, c_end) (Sec. IV-D, Eq. 6-8):
+//   Phi = alpha * Phi_S^n + beta * min(Phi_T, gamma_T) / gamma_T + (1 - beta) * max(gamma_L - Phi_L, 0) / gamma_L
+// observed from a run of the distributor over the candidate (window == 0: one pass against the state
+// as given; window > 0: capacity-aware, on a copy of the state):
+//   Phi_S^n = admitted / R                                             (SLO satisfaction ratio, Eq. 3)
+//   Phi_T   = sum over the instances that served at least one request, in index order, of
+//             1 / tbt_j, tbt_j taken at the first window                (decoding throughput, Eq. 4)
+//   Phi_L   = mean over the admitted requests of their instance's queue wait at admission, from the
+//             exact integer sum of lrintf(wait * 2^20) ticks            (queuing latency, Eq. 5)
+// All float operations are single binary32 operations in the order written below.
+// Outputs are indexed by absolute candidate; best_cand is the lowest candidate of the range with the
+// largest score.  Returns 0, -1 bad arguments.
+int oracle_placement_score(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
+                           const float* prefill_p, const float* tbt, uint32_t n_slo,
+                           const float* d_ttft, const float* d_tbt, uint32_t n_cand, uint32_t i_pad,
+                           const uint32_t* n_inst, const uint8_t* tp_idx, const uint16_t* max_batch,
+                           const int32_t* occ, const uint64_t* q_ticks, uint32_t n_req,
+                           const uint32_t* prompt_len, const uint32_t* out_len,
+                           const uint8_t* slo_class, const uint32_t* arrival_ticks, float s_bar,
+                           float pen_kappa, uint32_t tbt_mode, uint32_t window, float alpha,
+                           float beta, float gamma_t, float gamma_l, uint32_t c_begin, uint32_t c_end,
+                           uint32_t* sat_count, float* phi_s, float* phi_t, float* phi_l,
+                           float* score, uint32_t* best_cand) {
+  if (c_end > n_cand || !(gamma_t > 0.0f) || !(gamma_l > 0.0f)) return -1;
+  std::vector<int32_t> occ_c(i_pad);
+  std::vector<uint64_t> q_c(i_pad);
+  RunStats st;
+  uint32_t best_c = c_begin;
+  float best_s = -INFINITY;
+  // one window over everything never reaches the state update, which is what "static" means
+  const uint32_t win = window ? window : std::max<uint32_t>(n_req, 1u);
+  for (uint32_t c = c_begin; c < c_end; ++c) {
+    const size_t base = (size_t)c * i_pad;
+    const uint32_t ni = std::min(n_inst[c], i_pad);
+    std::copy(occ + base, occ + base + i_pad, occ_c.begin());
+    std::copy(q_ticks + base, q_ticks + base + i_pad, q_c.begin());
+    uint64_t sat = 0;
+    const int rc = distributor(n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt, ni,
+                               tp_idx + base, max_batch + base, occ_c.data(), q_c.data(), n_req,
+                               prompt_len, out_len, slo_class, arrival_ticks, s_bar, pen_kappa,
+                               tbt_mode, win, nullptr, nullptr, nullptr, nullptr, nullptr, &sat, &st);
+    if (rc != 0) return rc;
+    const float ps = (n_req == 0) ? 0.0f : (float)sat / (float)n_req;
+    float pt = 0.0f;
+    for (uint32_t j = 0; j < ni; ++j)
+      if (st.admitted_per_inst[j] != 0) pt = pt + 1.0f / st.tbt_first[j];
+    const float pl = (sat == 0) ? 0.0f : ((float)st.wait_ticks * 0x1p-20f) / (float)sat;
+    const float ptn = fminf(pt, gamma_t) / gamma_t;
+    const float pln = fmaxf(gamma_l - pl, 0.0f) / gamma_l;
+    const float sc = fmaf(alpha, ps, fmaf(beta, ptn, (1.0f - beta) * pln));
+    sat_count[c] = (uint32_t)sat;
+    phi_s[c] = ps; phi_t[c] = pt; phi_l[c] = pl; score[c] = sc;
+    if (sc > best_s) { best_s = sc; best_c = c; }
   }
   if (best_cand) *best_cand = best_c;
   return 0;

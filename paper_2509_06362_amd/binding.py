@@ -23,7 +23,7 @@ EXPORTS = (
     "maaso_profile_tables_load", "maaso_ctx_destroy", "maaso_ctx_device_status", "maaso_strerror",
     "maaso_ctx_set_launch_shape", "maaso_ctx_set_wait_limit", "maaso_ctx_kernel_timing",
     "maaso_ctx_kernel_elapsed", "maaso_ctx_sweep_evaluated", "maaso_score_assign",
-    "maaso_placement_sweep",
+    "maaso_placement_sweep", "maaso_placement_score",
 )
 
 
@@ -60,6 +60,16 @@ class AssignOut(C.Structure):
                 ("tbt", C.c_void_p), ("e2e", C.c_void_p), ("n_satisfied", C.c_void_p)]
 
 
+class ScoreWeights(C.Structure):
+    _fields_ = [("alpha", C.c_float), ("beta", C.c_float), ("gamma_t", C.c_float),
+                ("gamma_l", C.c_float)]
+
+
+class ScoreOut(C.Structure):
+    _fields_ = [("sat_count", C.c_void_p), ("phi_s", C.c_void_p), ("phi_t", C.c_void_p),
+                ("phi_l", C.c_void_p), ("score", C.c_void_p), ("best_cand", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -91,6 +101,9 @@ def load_library() -> C.CDLL:
         lib.maaso_placement_sweep.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                               C.POINTER(Params), C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p]
+        lib.maaso_placement_score.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
+                                              C.POINTER(Params), C.POINTER(ScoreWeights),
+                                              C.POINTER(ScoreOut), C.c_void_p]
         _lib = lib
     return _lib
 
@@ -254,6 +267,24 @@ def maaso_placement_sweep(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_ba
         "maaso_placement_sweep")
 
 
+def maaso_placement_score(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
+                          n_req, prompt_len, out_len, slo_class, arrival_ticks=None, s_bar,
+                          pen_kappa=0.0, tbt_mode=0, window=0, alpha, beta, gamma_t, gamma_l,
+                          sat_count, score, phi_s=None, phi_t=None, phi_l=None, best_cand=None,
+                          stream=None) -> None:
+    import torch
+    pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
+    rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window))
+    wts = ScoreWeights(float(alpha), float(beta), float(gamma_t), float(gamma_l))
+    out = ScoreOut(_dptr(sat_count, torch.int32), _dptr(phi_s, torch.float32),
+                   _dptr(phi_t, torch.float32), _dptr(phi_l, torch.float32),
+                   _dptr(score, torch.float32), _dptr(best_cand, torch.int32))
+    _check(load_library().maaso_placement_score(ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm),
+                                                C.byref(wts), C.byref(out), _stream_handle(stream)),
+           "maaso_placement_score")
+
+
 # ------------------------------------------------------------------------------------------------
 # plumbing for tests and the benchmark: a workload's arrays as GPU tensors
 # ------------------------------------------------------------------------------------------------
@@ -306,6 +337,23 @@ class DeviceWorkload:
             max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, **self.request_args(),
             arrival_ticks=self.arrival_ticks if window else None, window=window,
             **self.param_args(), sat_count=out[0], sat_ratio=out[1], best_cand=out[2], stream=stream)
+        return out
+
+    def score(self, alpha, beta, gamma_t, gamma_l, window=0, stream=None):
+        """maaso_placement_score over all candidates; returns a dict of tensors."""
+        import torch
+        dev = self.prompt_len.device
+        C_ = self.w.n_cand
+        out = dict(sat_count=torch.empty(C_, dtype=torch.int32, device=dev),
+                   best_cand=torch.empty(1, dtype=torch.int32, device=dev))
+        for k in ("phi_s", "phi_t", "phi_l", "score"):
+            out[k] = torch.empty(C_, dtype=torch.float32, device=dev)
+        maaso_placement_score(
+            self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
+            max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, **self.request_args(),
+            arrival_ticks=self.arrival_ticks if window else None, window=window,
+            **self.param_args(), alpha=alpha, beta=beta, gamma_t=gamma_t, gamma_l=gamma_l,
+            stream=stream, **out)
         return out
 
     def assign(self, cand: int = 0, window=None, latencies: bool = True, stream=None, out=None,

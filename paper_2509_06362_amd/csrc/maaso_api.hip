@@ -159,6 +159,37 @@ void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placement
   a.sat_acc = reinterpret_cast<unsigned long long*>(ctx->status + 36);
 }
 
+void fill_sweep_window_args(SweepWindowArgs& a, const maaso_ctx* ctx, const maaso_placements* pl,
+                            const maaso_requests* rq, const maaso_params* prm, uint32_t window,
+                            uint32_t* sat_count) {
+  a.tab = ctx->tab;
+  a.cells = ctx->cells;
+  a.mp = model_params(ctx, prm);
+  a.n_slo = ctx->n_slo;
+  std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
+  std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
+  std::memcpy(a.i_ttft, ctx->i_ttft, sizeof(a.i_ttft));
+  std::memcpy(a.i_tbt, ctx->i_tbt, sizeof(a.i_tbt));
+  a.n_cand = pl->n_cand;
+  a.i_pad = pl->i_pad;
+  a.n_inst = pl->n_inst;
+  a.tp_idx = pl->tp_idx;
+  a.max_batch = pl->max_batch;
+  a.occ = pl->occ;
+  a.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
+  a.n_req = rq->n_req;
+  a.prompt_len = rq->prompt_len;
+  a.out_len = rq->out_len;
+  a.slo_class = rq->slo_class;
+  a.arrival_ticks = rq->arrival_ticks;
+  a.window = window;
+  a.sat_count = sat_count;
+  a.status = ctx->status;
+  a.alpha = a.beta = 0.0f;
+  a.gamma_t = a.gamma_l = 1.0f;
+  a.phi_s = a.phi_t = a.phi_l = a.score = nullptr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -311,32 +342,10 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   if (prm->window != 0u && R != 0) {
     // Capacity-aware form: one block per candidate walks the request windows on its own state copy.
     SweepWindowArgs a;
-    a.tab = ctx->tab;
-    a.cells = ctx->cells;
-    a.mp = model_params(ctx, prm);
-    a.n_slo = K;
-    std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
-    std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
-    std::memcpy(a.i_ttft, ctx->i_ttft, sizeof(a.i_ttft));
-    std::memcpy(a.i_tbt, ctx->i_tbt, sizeof(a.i_tbt));
-    a.n_cand = C;
-    a.i_pad = I;
-    a.n_inst = pl->n_inst;
-    a.tp_idx = pl->tp_idx;
-    a.max_batch = pl->max_batch;
-    a.occ = pl->occ;
-    a.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
-    a.n_req = R;
-    a.prompt_len = rq->prompt_len;
-    a.out_len = rq->out_len;
-    a.slo_class = rq->slo_class;
-    a.arrival_ticks = rq->arrival_ticks;
-    a.window = prm->window;
-    a.sat_count = sat_count;
-    a.status = ctx->status;
+    fill_sweep_window_args(a, ctx, pl, rq, prm, prm->window, sat_count);
     {
       TimedRegion timed(ctx, s);
-      hipLaunchKernelGGL(sweep_window_kernel, dim3(C), dim3(kAssignThreads),
+      hipLaunchKernelGGL(sweep_window_kernel<false>, dim3(C), dim3(kAssignThreads),
                          (size_t)3 * ctx->cells * sizeof(float), s, a);
       if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
     }
@@ -462,6 +471,45 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   ctx->last_evaluated = eval_total;
   if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
   ctx->counters_dirty = false;
+  return MAASO_OK;
+}
+
+int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                          const maaso_params* prm, const maaso_score_weights* wts,
+                          const maaso_score_out* out, void* hip_stream) {
+  int rc = check_common(ctx, pl, rq, prm);
+  if (rc != MAASO_OK) return rc;
+  if (!wts || !out || !out->sat_count || !out->score) return MAASO_E_INVALID_ARG;
+  if (!std::isfinite(wts->alpha) || !std::isfinite(wts->beta) || !(wts->gamma_t > 0.0f) ||
+      !(wts->gamma_l > 0.0f) || !std::isfinite(wts->gamma_t) || !std::isfinite(wts->gamma_l))
+    return MAASO_E_INVALID_ARG;
+  if (prm->window != 0u && rq->n_req != 0 && !rq->arrival_ticks) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  SweepWindowArgs a;
+  // static = one window over everything: the state update is never reached
+  const uint32_t window = prm->window ? prm->window : (rq->n_req ? rq->n_req : 1u);
+  fill_sweep_window_args(a, ctx, pl, rq, prm, window, out->sat_count);
+  a.alpha = wts->alpha;
+  a.beta = wts->beta;
+  a.gamma_t = wts->gamma_t;
+  a.gamma_l = wts->gamma_l;
+  a.phi_s = out->phi_s;
+  a.phi_t = out->phi_t;
+  a.phi_l = out->phi_l;
+  a.score = out->score;
+  {
+    TimedRegion timed(ctx, s);
+    hipLaunchKernelGGL(sweep_window_kernel<true>, dim3(pl->n_cand), dim3(kAssignThreads),
+                       (size_t)3 * ctx->cells * sizeof(float), s, a);
+    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+  }
+  if (out->best_cand) {
+    hipLaunchKernelGGL(score_argmax_kernel, dim3(1), dim3(1024), 0, s, out->score, pl->n_cand,
+                       out->best_cand);
+    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+  }
   return MAASO_OK;
 }
 

@@ -38,6 +38,12 @@ struct SweepWindowArgs {
   uint32_t window;
   uint32_t* sat_count;
   uint32_t* status;
+  // composite serving score (kScore kernels only); every output may be null
+  float alpha, beta, gamma_t, gamma_l;
+  float* phi_s;
+  float* phi_t;
+  float* phi_l;
+  float* score;
 };
 
 __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
@@ -45,6 +51,12 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
   return v;
 }
 
+// kScore: also observe what the composite serving score needs (Sec. IV-D, Eq. 6-8) - which instances
+// served a request, and the exact integer sum of the admitted requests' queue waits - and finish the
+// candidate's score in the block: Phi = alpha * Phi_S^n + beta * min(Phi_T, gamma_T) / gamma_T +
+// (1 - beta) * max(gamma_L - Phi_L, 0) / gamma_L with Phi_T = sum of 1 / tbt_j over the serving
+// instances in index order (tbt_j of the first window) and Phi_L = mean wait of the admitted requests.
+template <bool kScore>
 __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const SweepWindowArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* tab = reinterpret_cast<float*>(smem);
@@ -74,6 +86,10 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   const uint64_t n_windows = (R + a.window - 1) / a.window;
   uint32_t sat = 0;
   constexpr int V = 4;
+  uint32_t served = 0;                // requests admitted to instance tid over all windows
+  unsigned long long wait_sum = 0ull; // their queue waits at admission, in ticks
+  unsigned long long wait_ticks = 0ull;
+  float inv_tbt_first = 0.0f;
 
   for (uint64_t w = 0; w < n_windows; ++w) {
     const uint64_t s0 = w * a.window;
@@ -86,6 +102,10 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
       if (stage_instance(tab, a.cells, a.mp, tp, B, occ, q, st)) {
         recs[tid] = make_float4(st.a, st.p, st.tbt, st.wait);
         svc = st.svc;
+        if (kScore) {
+          wait_ticks = (unsigned long long)__float2ll_rn(st.wait * 1048576.0f);
+          if (w == 0) inv_tbt_first = 1.0f / st.tbt;
+        }
       } else {
         raise_status(a.status, 2u);
         recs[tid] = make_float4(1.0f, 1.0f, 1.0f, INFINITY);
@@ -157,6 +177,10 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
     __syncthreads();
 
     if (tid < n) {
+      if (kScore) {
+        served += n_blk[tid];
+        wait_sum += (unsigned long long)n_blk[tid] * wait_ticks;
+      }
       occ += (int32_t)n_blk[tid];
       q += t_blk[tid];
       if (e0 < R) {  // time passes until the next window opens
@@ -173,11 +197,60 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
 
   for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);
   if ((tid & 63u) == 0u) wave_sat[tid >> 6] = sat;
+  if (kScore) {
+    // reuse the LDS arrays of the window loop (all threads are past its last barrier):
+    // s2tab[j] = 1 / tbt_j of a serving instance, or -1; t_blk[wave] = wait ticks of the wavefront
+    s2tab[tid] = (tid < n && served != 0u) ? inv_tbt_first : -1.0f;
+    wait_sum = wave_sum_u64(wait_sum);
+    if ((tid & 63u) == 0u) t_blk[tid >> 6] = wait_sum;
+  }
   __syncthreads();
   if (tid == 0) {
     uint32_t t = 0;
     for (int wv = 0; wv < kAssignThreads / 64; ++wv) t += wave_sat[wv];
     a.sat_count[c] = t;
+    if (kScore) {
+      unsigned long long ticks = 0ull;
+      for (int wv = 0; wv < kAssignThreads / 64; ++wv) ticks += t_blk[wv];
+      const float ps = (a.n_req == 0u) ? 0.0f : (float)t / (float)a.n_req;
+      float pt = 0.0f;
+      for (uint32_t j = 0; j < n; ++j) {
+        const float inv = s2tab[j];
+        if (inv >= 0.0f) pt = pt + inv;
+      }
+      const float pl = (t == 0u) ? 0.0f : ((float)ticks * 0x1p-20f) / (float)t;
+      const float ptn = fminf(pt, a.gamma_t) / a.gamma_t;
+      const float pln = fmaxf(a.gamma_l - pl, 0.0f) / a.gamma_l;
+      const float sc = fmaf(a.alpha, ps, fmaf(a.beta, ptn, (1.0f - a.beta) * pln));
+      if (a.phi_s) a.phi_s[c] = ps;
+      if (a.phi_t) a.phi_t[c] = pt;
+      if (a.phi_l) a.phi_l[c] = pl;
+      if (a.score) a.score[c] = sc;
+    }
+  }
+}
+
+// Best candidate by score: largest score, lowest index on ties.  One block.
+__global__ __launch_bounds__(1024) void score_argmax_kernel(const float* __restrict__ score,
+                                                            uint32_t n_cand,
+                                                            uint32_t* __restrict__ best_cand) {
+  __shared__ unsigned long long best[16];
+  unsigned long long key = 0ull;  // (order-preserving bits of the score << 32) | ~index
+  for (uint32_t c = threadIdx.x; c < n_cand; c += blockDim.x) {
+    const uint32_t b = __float_as_uint(score[c]);
+    const uint32_t ord = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    const unsigned long long kc = ((unsigned long long)ord << 32) | (unsigned long long)(~c);
+    key = kc > key ? kc : key;
+  }
+  for (int d = 32; d >= 1; d >>= 1) {
+    const unsigned long long o = __shfl_xor(key, d);
+    key = o > key ? o : key;
+  }
+  if ((threadIdx.x & 63u) == 0u) best[threadIdx.x >> 6] = key;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (uint32_t w = 1; w < (blockDim.x >> 6); ++w) key = best[w] > key ? best[w] : key;
+    *best_cand = ~(uint32_t)(key & 0xffffffffull);
   }
 }
 

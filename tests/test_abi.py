@@ -41,6 +41,8 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(binding.Placements) == 48
     assert C.sizeof(binding.Params) == 16
     assert C.sizeof(binding.AssignOut) == 48
+    assert C.sizeof(binding.ScoreWeights) == 16
+    assert C.sizeof(binding.ScoreOut) == 48
 
 
 def test_strerror(lib):
@@ -84,6 +86,7 @@ def test_load_validates_on_the_host(lib):
 def test_null_context_is_rejected(lib):
     assert lib.maaso_score_assign(None, None, None, None, None, None) == -1
     assert lib.maaso_placement_sweep(None, None, None, None, None, None, None, None) == -1
+    assert lib.maaso_placement_score(None, None, None, None, None, None, None) == -1
     assert lib.maaso_ctx_device_status(None, None) == -1
     assert lib.maaso_ctx_set_launch_shape(None, 0, 0, 0, 0) == -1
     assert lib.maaso_ctx_set_wait_limit(None, 1) == -1

@@ -237,6 +237,94 @@ def test_windowed_sweep_config4_shape():
 
 
 # ------------------------------------------------------------------------------------------------
+# composite serving score (Sec. IV-D, Eq. 6-8)
+# ------------------------------------------------------------------------------------------------
+SCORE_WEIGHTS = ((4.0, 0.3, 512.0, 0.5), (10.0, 0.75, 1.0e5, 0.004), (0.0, 1.0, 2000.0, 3.0))
+
+
+def check_score(w, window=0, weights=SCORE_WEIGHTS, sampled=None):
+    """Every output of maaso_placement_score bit-identical to the oracle's: counts, the three
+    indicators, the score and the best candidate."""
+    dw = binding.DeviceWorkload(w)
+    try:
+        seen = set()
+        for alpha, beta, gt, gl in weights:
+            print(f"score {w.name} C={w.n_cand} I={w.i_pad} R={w.n_req} window={window} "
+                  f"alpha={alpha} beta={beta} gamma_t={gt} gamma_l={gl}", flush=True)
+            got = dw.score(alpha, beta, gt, gl, window=window)
+            torch.cuda.synchronize()
+            assert binding.maaso_ctx_device_status(dw.ctx) == 0
+            got = {k: (u32(v) if v.dtype == torch.int32 else v.cpu().numpy()) for k, v in got.items()}
+            if sampled is None:
+                ref = oracle.placement_score(w, alpha, beta, gt, gl, window=window)
+                for k in ("sat_count", "phi_s", "phi_t", "phi_l", "score"):
+                    assert np.array_equal(got[k], ref[k]), k
+                assert int(got["best_cand"][0]) == ref["best_cand"]
+            else:
+                for c in sampled:
+                    one = oracle.placement_score(w, alpha, beta, gt, gl, window=window,
+                                                 c_begin=c, c_end=c + 1)
+                    for k in ("sat_count", "phi_s", "phi_t", "phi_l", "score"):
+                        assert got[k][c] == one[k][c], (k, c)
+                assert int(got["best_cand"][0]) == int(np.argmax(got["score"]))
+            seen.update(got["score"].tolist())
+        assert np.array_equal(dw.occ.cpu().numpy(), w.occ)
+        return seen
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("seed,n_cand,i_pad,n_req,n_slo,window", [
+    (71, 30, 16, 3000, 3, 0), (72, 12, 1, 700, 1, 64), (73, 9, 48, 2500, 5, 1000),
+    (74, 6, 128, 1500, 8, 0), (75, 4, 256, 900, 16, 333), (76, 20, 7, 300, 2, 1),
+    (77, 10, 32, 2000, 3, 5000),
+])
+def test_score_small_irregular(seed, n_cand, i_pad, n_req, n_slo, window):
+    w = W.random_small(seed, n_cand, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
+    seen = set()
+    for v in (w, W.stressed(w, seed=seed, deadline_scale=0.25),
+              W.stressed(w, seed=seed, deadline_scale=0.03)):
+        seen |= check_score(v, window)
+    assert len(seen) > 3
+
+
+def test_score_edge_cases():
+    w = W.random_small(78, 5, 8, 400, n_slo=2)
+    check_score(w.with_requests(0, 0))                                # no requests: every indicator 0
+    check_score(W.replace(w, n_inst=np.zeros_like(w.n_inst)))         # no instances: nothing admitted
+    hopeless = W.replace(w, d_ttft=np.full_like(w.d_ttft, 2.0 ** -20),
+                         d_tbt=np.full_like(w.d_tbt, 2.0 ** -20))
+    check_score(hopeless)                                             # nothing admitted anywhere
+    check_score(hopeless, window=50)
+
+
+def test_score_counts_match_the_sweeps():
+    w = W.stressed(W.config1(n_cand=48, n_req=8192), seed=12)
+    w = W.replace(w, arrival_ticks=W.poisson_arrivals(W.rng_for(12, 3), 1500.0, 8192))
+    dw = binding.DeviceWorkload(w)
+    try:
+        for window in (0, 1024):
+            cnt, _, _ = dw.sweep(window=window)
+            got = dw.score(4.0, 0.3, 512.0, 0.5, window=window)
+            torch.cuda.synchronize()
+            assert torch.equal(cnt, got["sat_count"])
+    finally:
+        dw.close()
+
+
+def test_score_config_shapes():
+    check_score(W.config0(), weights=SCORE_WEIGHTS[:1])
+    small = W.config4(n_cand=24, n_req=16384)
+    check_score(small, window=4096, weights=SCORE_WEIGHTS[:2])
+    check_score(W.stressed(small, seed=4), window=1024, weights=SCORE_WEIGHTS[:2])
+    full = W.config4()
+    rng = np.random.default_rng(45)
+    picks = sorted(rng.choice(full.n_cand, 4, replace=False).tolist())
+    check_score(full, window=4096, weights=SCORE_WEIGHTS[:1], sampled=picks)
+    check_score(full, window=0, weights=SCORE_WEIGHTS[1:2], sampled=picks[:2])
+
+
+# ------------------------------------------------------------------------------------------------
 # distributor, static
 # ------------------------------------------------------------------------------------------------
 
