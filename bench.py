@@ -42,6 +42,9 @@ ASSIGN_LANEOPS_PER_TRIPLE = 12
 # Algorithmic HBM bytes of the distributor per request: prompt_len 4 + out_len 4 + class 1 in,
 # chosen 4 + slack 4 out.
 ASSIGN_BYTES_PER_REQUEST = 17
+# Composite serving score (Sec. IV-D, Eq. 6): alpha and beta as in the paper's evaluation; gamma_T a
+# throughput no deployment of these workloads exceeds (tokens/s), gamma_L the largest acceptable wait (s).
+SCORE_WEIGHTS = (4.0, 0.3, 16384.0, 2.0)
 
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by the
@@ -87,6 +90,10 @@ def make_workload(name: str):
         from dataclasses import replace
         w = W.config4()
         return replace(w, name=w.name + "_windowed", window=4096)
+    if name == "cfg4score":  # the same, every candidate scored with the composite serving score
+        from dataclasses import replace
+        w = W.config4()
+        return replace(w, name=w.name + "_windowed_score", window=4096)
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -100,7 +107,9 @@ def cpu_baseline(w, kind: str, budget_triples: float):
         n = int(np.searchsorted(np.cumsum(per_cand), budget_triples)) + 1
         n = max(1, min(n, w.n_cand))
         t0 = time.perf_counter()
-        if w.window:
+        if w.name.endswith("_score"):
+            oracle.placement_score(w, *SCORE_WEIGHTS, window=int(w.window), c_begin=0, c_end=n)
+        elif w.window:
             oracle.placement_sweep_windowed(w, window=int(w.window), c_begin=0, c_end=n)
         else:
             oracle.placement_sweep(w, 0, n)
@@ -128,7 +137,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="cfg1",
-                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "stream"])
+                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "cfg4score", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-triples", type=float, default=3.0e9,
                     help="size of the oracle's timed sample, in triples")
@@ -169,17 +178,33 @@ def main() -> int:
                       slack=torch.empty(w.n_req, dtype=torch.float32, device=dev),
                       n_satisfied=torch.empty(1, dtype=torch.int64, device=dev))
 
+    if kind == "sweep" and w.name.endswith("_score"):
+        score_out = dict(sat_count=sweep_out[0], best_cand=sweep_out[2])
+        for k in ("phi_s", "phi_t", "phi_l", "score"):
+            score_out[k] = torch.empty(w.n_cand, dtype=torch.float32, device=dev)
+        cw = dict(zip(("alpha", "beta", "gamma_t", "gamma_l"), SCORE_WEIGHTS))
+
+        def run_sweep():
+            binding.maaso_placement_score(
+                dw.ctx, n_cand=w.n_cand, i_pad=w.i_pad, n_inst=dw.n_inst, tp_idx=dw.tp_idx,
+                max_batch=dw.max_batch, occ=dw.occ, q_ticks=dw.q_ticks, **dw.request_args(),
+                arrival_ticks=dw.arrival_ticks, window=sweep_window, **dw.param_args(), **cw,
+                stream=stream, **score_out)
+    else:
+        def run_sweep():
+            dw.sweep(out=sweep_out, stream=stream, window=sweep_window)
+
     if kind == "sweep":
         # the distributor runs on the winning deployment; its index is fixed by a first sweep so
         # that the timed steps need no device-to-host copy
-        dw.sweep(out=sweep_out, window=sweep_window)
+        run_sweep()
         torch.cuda.synchronize()
         best = int(sweep_out[2].item())
         triples_sweep = w.valid_triples()
         triples_assign = w.n_req * int(w.n_inst[best])
 
         def step():
-            dw.sweep(out=sweep_out, stream=stream, window=sweep_window)
+            run_sweep()
             dw.assign(cand=best, window=0, latencies=False, out=assign_out, stream=stream)
     else:
         best = 0
@@ -206,7 +231,7 @@ def main() -> int:
     n_timed = min(args.steps, 100)
     for _ in range(n_timed):
         if kind == "sweep":
-            dw.sweep(out=sweep_out, stream=stream, window=sweep_window)
+            run_sweep()
         else:
             step()
     torch.cuda.synchronize()
@@ -271,8 +296,8 @@ def main() -> int:
         "config": {"workload": w.name, "n_cand": w.n_cand, "i_pad": w.i_pad, "n_req": w.n_req,
                    "n_slo": w.n_slo, "window": int(w.window), "seed": w.seed,
                    "triples_per_step": triples_step, "padded_triples": w.padded_triples(),
-                   "step": "placement_sweep + score_assign(best candidate)" if kind == "sweep"
-                   else "score_assign"},
+                   "step": ("placement_score" if w.name.endswith("_score") else "placement_sweep")
+                   + " + score_assign(best candidate)" if kind == "sweep" else "score_assign"},
         "roofline": roofline,
         "device_status": status,
     }
