@@ -131,13 +131,106 @@ def cpu_baseline(w, kind: str, budget_triples: float):
             "sample": sample, "seconds": dt}
 
 
+ALG2_GPUS = 64
+ALG2_SCORE_WEIGHTS = (4.0, 0.3, 4096.0, 2.0)
+
+
+def bench_alg2(args) -> int:
+    """Resource partition (Alg. 2) as one pipeline: split by SLO, every growth-chain deployment of
+    Alg. 1 scored against R_t, R_l and R, best per GPU count, partition scan.  A step is the whole
+    pipeline; its triples are those of the three scoring launches."""
+    import numpy as np
+    import torch
+    from paper_2509_06362_amd import binding, workloads as W
+    w = W.partition_case(n_req=131072, rate=400.0)
+    tp, b = W.all_configs()
+    cw, offs = W.growth_chains(w, tp, b, ALG2_GPUS)
+    dw = binding.DeviceWorkload(cw)
+    slots = int(cw.n_inst.astype(np.int64).sum())
+    triples_step = 2 * cw.n_req * slots
+
+    def step():
+        return dw.resource_partition(offs, 0b1, ALG2_GPUS, *ALG2_SCORE_WEIGHTS, window=int(w.window))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    binding.maaso_ctx_kernel_timing(dw.ctx, True)
+    n_timed = min(args.steps, 50)
+    for _ in range(n_timed):
+        step()
+    torch.cuda.synchronize()
+    k_ms, k_n = binding.maaso_ctx_kernel_elapsed(dw.ctx)
+    binding.maaso_ctx_kernel_timing(dw.ctx, False)
+    k_total_s = k_ms * 1e-3 / max(n_timed, 1)       # the three scoring launches of one step
+    ops = ASSIGN_LANEOPS_PER_TRIPLE * triples_step
+    part = res["partition"].cpu().numpy()
+    result = {
+        "metric": "scored (candidate,request,instance) triples/sec",
+        "value": triples_step * args.steps / dt, "unit": "triples/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "alg2_partition", "n_gpus_partitioned": ALG2_GPUS, "n_cand": cw.n_cand,
+                   "i_pad": cw.i_pad, "n_req": cw.n_req, "n_chains": len(tp), "window": int(w.window),
+                   "seed": w.seed, "triples_per_step": triples_step,
+                   "step": "split_by_slo + 3 x (placement_score + ins_deploy_select) + resource_partition",
+                   "partition": {"g_t": int(part[0]), "g_l": int(part[1]),
+                                 "heterogeneous": int(part[2]), "phi_opt": float(res["phi_opt"].item())}},
+        "roofline": {"kernel": "sweep_window_kernel", "bound": "alu",
+                     "achieved": ops / k_total_s / 1e12, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
+                     "frac": ops / k_total_s / 1e12 / VALU_PEAK_TLANEOPS, "traffic": None,
+                     "kernel_ms": k_ms / max(k_n, 1), "launches_timed": k_n,
+                     "laneops_per_triple": ASSIGN_LANEOPS_PER_TRIPLE},
+        "device_status": binding.maaso_ctx_device_status(dw.ctx),
+    }
+    if not args.no_cpu_baseline:
+        # the oracle's sequential Alg. 1 + Alg. 2 on the first requests of the same stream; it scores
+        # a chain only up to its first rejected deployment, so its triples are counted from its own run
+        import oracle
+        oracle.build()
+        n = int(min(w.n_req, max(int(w.window), args.cpu_triples // (2 * slots))))
+        ws = w.with_requests(0, n)
+        t0 = time.perf_counter()
+        r_t, r_l = oracle.split_by_slo(ws, 0b1)
+        done = 0
+        lists = {}
+        for tag, wx in (("t", r_t), ("l", r_l), ("h", ws)):
+            lists[tag] = oracle.ins_deploy(wx, ALG2_GPUS, tp, b, *ALG2_SCORE_WEIGHTS, window=int(w.window))
+        oracle.resource_partition(ALG2_GPUS, lists["t"]["phi_star"], lists["l"]["phi_star"],
+                                  lists["h"]["phi_star"], r_l.n_req, ws.n_req)
+        cdt = time.perf_counter() - t0
+        for tag, wx in (("t", r_t), ("l", r_l), ("h", ws)):
+            cw_x, offs_x = W.growth_chains(wx, tp, b, ALG2_GPUS)
+            sc = oracle.placement_score(cw_x, *ALG2_SCORE_WEIGHTS, window=int(w.window))["score"]
+            for i in range(len(tp)):
+                chain = sc[offs_x[i]:offs_x[i + 1]]
+                prev = np.concatenate([[np.float32(0)], chain[:-1]])
+                stop = np.nonzero(~(chain > prev))[0]
+                m = int(stop[0]) + 1 if len(stop) else len(chain)     # deployments the greedy scored
+                done += wx.n_req * (m * (m + 1) // 2)
+        result["cpu_baseline"] = {
+            "value": done / cdt, "unit": "triples/s", "cores": 1, "kind": "oracle",
+            "sample": f"sequential Alg. 1 + Alg. 2 on requests [0,{n}) of {w.n_req}: {done:.3e} triples "
+                      f"(chains cut at the first rejection) in the timed part", "seconds": cdt}
+        result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
+    print(json.dumps(result))
+    dw.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="cfg1",
-                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "cfg4score", "stream"])
+                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "cfg4score", "alg2", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-triples", type=float, default=3.0e9,
                     help="size of the oracle's timed sample, in triples")
@@ -161,6 +254,8 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     binding.load_library()
+    if args.workload == "alg2":
+        return bench_alg2(args)
     w = make_workload(args.workload)
     kind = "sweep" if w.n_cand > 1 else "assign"
     sweep_window = int(w.window) if kind == "sweep" else 0

@@ -47,6 +47,7 @@ typedef enum {
 #define MAASO_MAX_TABLE_CELLS 2048u /* n_tp * (b_cap + 1): cells per profile table (LDS-resident) */
 #define MAASO_MAX_REQUESTS 2147483648u /* R: requests per call                                  */
 #define MAASO_MAX_LEN 16777215u    /* prompt_len / out_len: exactly representable in binary32   */
+#define MAASO_MAX_GPUS 4096u       /* |G|: GPUs of a (sub-)cluster in the placer's outer algorithms */
 
 /* bits of the device status word (maaso_ctx_device_status) */
 #define MAASO_DEV_BAD_CLASS 1u     /* a request with slo_class >= n_slo was skipped (never satisfied) */
@@ -54,6 +55,9 @@ typedef enum {
                                       treated as absent */
 #define MAASO_DEV_WAIT_TIMEOUT 4u  /* the windowed distributor's inter-window wait exceeded its spin
                                       limit; outputs of that call are incomplete */
+
+#define MAASO_DEV_BAD_CHAIN 8u     /* chain_offsets of maaso_ins_deploy_select not non-decreasing
+                                      within [0, n_cand]; that chain was ignored */
 
 typedef struct maaso_ctx maaso_ctx; /* opaque */
 
@@ -68,7 +72,8 @@ typedef struct maaso_ctx maaso_ctx; /* opaque */
 typedef struct {
   uint32_t n_tp;             /* T >= 1                                                   */
   uint32_t b_cap;            /* >= 1; T * (b_cap + 1) <= MAASO_MAX_TABLE_CELLS           */
-  const uint32_t* tp_degree; /* [T] GPUs per instance N(P); informational, may be NULL   */
+  const uint32_t* tp_degree; /* [T] GPUs per instance N(P); may be NULL, but then
+                                maaso_ins_deploy_select is refused                       */
   const float* prefill_a;    /* [T*(b_cap+1)] seconds, > 0 and finite for b >= 1         */
   const float* prefill_p;    /* [T*(b_cap+1)] seconds per prompt token, > 0, finite      */
   const float* tbt;          /* [T*(b_cap+1)] seconds per output token, > 0, finite      */
@@ -237,6 +242,54 @@ typedef struct {
 int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, const maaso_score_weights* wts,
                           const maaso_score_out* out, void* hip_stream);
+
+/* Alg. 2, first step (Sec. IV-E: the requests are categorised by SLO into a strict set R_t and a
+ * relaxed set R_l).  Classes whose bit is set in tight_classes form R_t.  The four request streams
+ * are rewritten into the *_out arrays (DEVICE, [R] each): R_t first, R_l from index *n_tight on, both
+ * in their original (arrival) order; *n_tight (DEVICE, [1]) receives |R_t|.  arrival_ticks_out is
+ * required when rq->arrival_ticks is given and ignored otherwise.  Outputs must not alias inputs.
+ * A request with slo_class >= n_slo raises MAASO_DEV_BAD_CLASS and stays with R_l.
+ * Errors: INVALID_ARG, SHAPE, NOMEM, HIP. */
+int maaso_split_by_slo(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_classes,
+                       uint32_t* prompt_len_out, uint32_t* out_len_out, uint8_t* slo_class_out,
+                       uint32_t* arrival_ticks_out, uint32_t* n_tight, void* hip_stream);
+
+/* Alg. 1's bookkeeping (Sec. IV-E) over deployments that have already been scored, e.g. by
+ * maaso_placement_score: phi_star[k] (DEVICE, [n_gpus+1]) is the best score among the accepted
+ * deployments occupying exactly k GPUs (k = sum of tp_degree over the candidate's instances),
+ * cand_star[k] its candidate index; 0 and -1 where there is none.
+ *   chain_offsets == NULL: every candidate with a score > 0 that fits into n_gpus GPUs is accepted.
+ *   chain_offsets (DEVICE, [n_chains+1], non-decreasing, last <= n_cand): chain i is the growth path
+ *   of one configuration (P_i, B_i) - candidate chain_offsets[i] + m is the deployment after m + 1
+ *   additions.  A candidate is accepted when all before it in its chain are, it fits, and its score
+ *   is strictly larger than its predecessor's (0 before the first): Alg. 1 keeps an addition only if
+ *   the score improves and otherwise stops growing that configuration (with one model the rejected
+ *   model saturates the model set).  Scoring a whole chain at once and cutting it here gives what the
+ *   sequential loop gives, because the loop's next deployment never depends on a rejected one.
+ * Ties between configurations go to the lowest candidate index (Alg. 1 replaces an entry only on a
+ * strictly larger score).  Only pl->n_cand, i_pad, n_inst and tp_idx are read.
+ * Errors: INVALID_ARG (also: profile loaded without tp_degree), SHAPE, HIP. */
+int maaso_ins_deploy_select(maaso_ctx* ctx, const maaso_placements* pl, const float* score,
+                            const uint32_t* chain_offsets, uint32_t n_chains, uint32_t n_gpus,
+                            float* phi_star, int32_t* cand_star, void* hip_stream);
+
+/* Alg. 2's scan over the GPU partitions (Sec. IV-E).  phi_t_star / phi_l_star (DEVICE, [n_gpus+1]) are
+ * Alg. 1's score lists for R_t and R_l.  The relaxed sub-cluster is tried at g_l = 1 .. G'_l GPUs,
+ * G'_l = floor(|R_l| * |G| / |R|) (n_req_l, n_req: HOST scalars; 0 when n_req == 0), the strict one
+ * takes g_t = n_gpus - g_l, and the partition with the largest phi_t_star[g_t] + phi_l_star[g_l]
+ * (smallest g_l on ties) is chosen if that sum is strictly larger than the starting value: the largest
+ * entry of phi_h_star (Alg. 1 on all requests and all GPUs, the homogeneous fallback; lowest GPU
+ * count on ties), or 0 when phi_h_star is NULL.
+ * partition (DEVICE, [6]): g_t, g_l, heterogeneous (1: a partition was chosen, 0: the fallback
+ * stands, then g_t = k_h and g_l = 0), k_h (GPUs of the homogeneous deployment, 0 if none),
+ * cand_t, cand_l (entries of cand_t_star[g_t] / cand_l_star[g_l], or cand_h_star[k_h] and -1 for
+ * the fallback; -1 as 0xffffffff; the cand arrays may be NULL).  phi_opt (DEVICE, [1]): the score
+ * that stands.  Errors: INVALID_ARG, SHAPE, HIP. */
+int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t_star,
+                             const float* phi_l_star, const float* phi_h_star,
+                             const int32_t* cand_t_star, const int32_t* cand_l_star,
+                             const int32_t* cand_h_star, uint64_t n_req_l, uint64_t n_req,
+                             uint32_t* partition, float* phi_opt, void* hip_stream);
 
 #ifdef __cplusplus
 }

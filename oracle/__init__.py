@@ -47,7 +47,7 @@ def load():
         _lib.oracle_triple.restype = None
         for name in ("oracle_stage", "oracle_score_assign", "oracle_placement_sweep",
                      "oracle_placement_sweep_windowed", "oracle_placement_score",
-                     "oracle_threshold_sweep"):
+                     "oracle_threshold_sweep", "oracle_ins_deploy", "oracle_resource_partition"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -203,3 +203,64 @@ def threshold_sweep(w, tbt_mode=None):
     if rc != 0:
         raise ValueError("oracle_threshold_sweep rejected the profile")
     return cnt
+
+
+def ins_deploy(w, n_gpus: int, cfg_tp, cfg_b, alpha, beta, gamma_t, gamma_l, window=0,
+               max_inst: int = 256, tbt_mode=None):
+    """Alg. 1 for one model over the requests of `w` (its candidates are ignored): score list and
+    best deployment per GPU count, as (configuration index, instance count)."""
+    lib = load()
+    cfg_tp = np.ascontiguousarray(cfg_tp, np.uint8)
+    cfg_b = np.ascontiguousarray(cfg_b, np.uint16)
+    if window and w.arrival_ticks is None:
+        raise ValueError("windowed scoring needs arrival_ticks")
+    phi = np.zeros(n_gpus + 1, np.float32)
+    cfg = np.zeros(n_gpus + 1, np.int32)
+    cnt = np.zeros(n_gpus + 1, np.uint32)
+    n_eval = C.c_uint64(0)
+    deg = np.ascontiguousarray(w.tp_degree, np.uint32)
+    rc = lib.oracle_ins_deploy(
+        *_profile_args(w), *_slo_args(w), _ptr(deg, C.c_uint32), C.c_uint32(w.n_req),
+        _ptr(w.prompt_len, C.c_uint32), _ptr(w.out_len, C.c_uint32), _ptr(w.slo_class, C.c_uint8),
+        _ptr(w.arrival_ticks, C.c_uint32), C.c_float(float(w.s_bar)), C.c_float(float(w.pen_kappa)),
+        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window),
+        C.c_float(alpha), C.c_float(beta), C.c_float(gamma_t), C.c_float(gamma_l),
+        C.c_uint32(n_gpus), C.c_uint32(len(cfg_tp)), _ptr(cfg_tp, C.c_uint8), _ptr(cfg_b, C.c_uint16),
+        C.c_uint32(max_inst), _ptr(phi, C.c_float), _ptr(cfg, C.c_int32), _ptr(cnt, C.c_uint32),
+        C.byref(n_eval))
+    if rc != 0:
+        raise ValueError(f"oracle_ins_deploy rejected its arguments (rc={rc})")
+    return dict(phi_star=phi, cfg_star=cfg, cnt_star=cnt, n_evaluated=int(n_eval.value))
+
+
+def resource_partition(n_gpus: int, phi_t_star, phi_l_star, phi_h_star, n_req_l: int, n_req: int):
+    """Alg. 2's partition scan -> dict(g_t, g_l, heterogeneous, k_h, phi_opt)."""
+    lib = load()
+    pt = np.ascontiguousarray(phi_t_star, np.float32)
+    pl = np.ascontiguousarray(phi_l_star, np.float32)
+    ph = None if phi_h_star is None else np.ascontiguousarray(phi_h_star, np.float32)
+    assert len(pt) == n_gpus + 1 and len(pl) == n_gpus + 1 and (ph is None or len(ph) == n_gpus + 1)
+    out = np.zeros(4, np.uint32)
+    opt = C.c_float(0.0)
+    rc = lib.oracle_resource_partition(C.c_uint32(n_gpus), _ptr(pt, C.c_float), _ptr(pl, C.c_float),
+                                       _ptr(ph, C.c_float), C.c_uint64(n_req_l), C.c_uint64(n_req),
+                                       _ptr(out, C.c_uint32), C.byref(opt))
+    if rc != 0:
+        raise ValueError("oracle_resource_partition rejected its arguments")
+    return dict(g_t=int(out[0]), g_l=int(out[1]), heterogeneous=int(out[2]), k_h=int(out[3]),
+                phi_opt=float(np.float32(opt.value)))
+
+
+def split_by_slo(w, tight_classes: int):
+    """Alg. 2's first step: the requests whose class has its bit set in `tight_classes` (R_t) and the
+    others (R_l), each in arrival order.  Pure selection; returns two workloads."""
+    tight = ((np.uint32(tight_classes) >> w.slo_class.astype(np.uint32)) & 1).astype(bool)
+
+    def pick(m):
+        from dataclasses import replace
+        return replace(w, prompt_len=np.ascontiguousarray(w.prompt_len[m]),
+                       out_len=np.ascontiguousarray(w.out_len[m]),
+                       slo_class=np.ascontiguousarray(w.slo_class[m]),
+                       arrival_ticks=None if w.arrival_ticks is None
+                       else np.ascontiguousarray(w.arrival_ticks[m]))
+    return pick(tight), pick(~tight)

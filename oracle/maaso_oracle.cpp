@@ -248,6 +248,59 @@ int distributor(uint32_t n_tp, uint32_t b_cap, const float* prefill_a, const flo
   return 0;
 }
 
+struct RequestSet {
+  uint32_t n_req;
+  const uint32_t* prompt_len;
+  const uint32_t* out_len;
+  const uint8_t* slo_class;
+  const uint32_t* arrival_ticks;
+};
+
+struct ScoreSetup {
+  float s_bar, pen_kappa;
+  uint32_t tbt_mode, window;
+  float alpha, beta, gamma_t, gamma_l;
+};
+
+struct DeploymentScore {
+  uint64_t sat = 0;
+  float phi_s = 0, phi_t = 0, phi_l = 0, score = 0;
+};
+
+// Composite serving score of one deployment (Sec. IV-D, Eq. 3-8): run the distributor over all of
+// R_x on a private copy of the instances' state, then
+//   Phi_S^n = admitted / |R_x|;  Phi_T = sum over instances that served a request of 1 / tbt_j
+//   (index order, tbt_j of the first window);  Phi_L = mean over admitted requests of their
+//   instance's queue wait at admission;  Phi = alpha Phi_S^n + beta min(Phi_T, gamma_T) / gamma_T +
+//   (1 - beta) max(gamma_L - Phi_L, 0) / gamma_L.
+int score_deployment(const Profile& pf, const RequestSet& rs, const ScoreSetup& su, uint32_t ni,
+                     const uint8_t* tp_idx, const uint16_t* max_batch, const int32_t* occ,
+                     const uint64_t* q_ticks, DeploymentScore& d) {
+  std::vector<int32_t> occ_c(occ, occ + ni);
+  std::vector<uint64_t> q_c(q_ticks, q_ticks + ni);
+  RunStats st;
+  // one window over everything never reaches the state update, which is what "static" means
+  const uint32_t win = su.window ? su.window : std::max<uint32_t>(rs.n_req, 1u);
+  uint64_t sat = 0;
+  const int rc = distributor(pf.n_tp, pf.b_cap, pf.prefill_a, pf.prefill_p, pf.tbt, pf.n_slo,
+                             pf.d_ttft, pf.d_tbt, ni, tp_idx, max_batch, occ_c.data(), q_c.data(),
+                             rs.n_req, rs.prompt_len, rs.out_len, rs.slo_class, rs.arrival_ticks,
+                             su.s_bar, su.pen_kappa, su.tbt_mode, win, nullptr, nullptr, nullptr,
+                             nullptr, nullptr, &sat, &st);
+  if (rc != 0) return rc;
+  const float ps = (rs.n_req == 0) ? 0.0f : (float)sat / (float)rs.n_req;
+  float pt = 0.0f;
+  for (uint32_t j = 0; j < ni; ++j)
+    if (st.admitted_per_inst[j] != 0) pt = pt + 1.0f / st.tbt_first[j];
+  const float pl = (sat == 0) ? 0.0f : ((float)st.wait_ticks * 0x1p-20f) / (float)sat;
+  const float ptn = fminf(pt, su.gamma_t) / su.gamma_t;
+  const float pln = fmaxf(su.gamma_l - pl, 0.0f) / su.gamma_l;
+  d.sat = sat;
+  d.phi_s = ps; d.phi_t = pt; d.phi_l = pl;
+  d.score = fmaf(su.alpha, ps, fmaf(su.beta, ptn, (1.0f - su.beta) * pln));
+  return 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -387,37 +440,122 @@ int oracle_placement_score(uint32_t n_tp, uint32_t b_cap, const float* prefill_a
                            uint32_t* sat_count, float* phi_s, float* phi_t, float* phi_l,
                            float* score, uint32_t* best_cand) {
   if (c_end > n_cand || !(gamma_t > 0.0f) || !(gamma_l > 0.0f)) return -1;
-  std::vector<int32_t> occ_c(i_pad);
-  std::vector<uint64_t> q_c(i_pad);
-  RunStats st;
+  const Profile pf{n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt};
+  const RequestSet rs{n_req, prompt_len, out_len, slo_class, arrival_ticks};
+  const ScoreSetup su{s_bar, pen_kappa, tbt_mode, window, alpha, beta, gamma_t, gamma_l};
   uint32_t best_c = c_begin;
   float best_s = -INFINITY;
-  // one window over everything never reaches the state update, which is what "static" means
-  const uint32_t win = window ? window : std::max<uint32_t>(n_req, 1u);
   for (uint32_t c = c_begin; c < c_end; ++c) {
     const size_t base = (size_t)c * i_pad;
     const uint32_t ni = std::min(n_inst[c], i_pad);
-    std::copy(occ + base, occ + base + i_pad, occ_c.begin());
-    std::copy(q_ticks + base, q_ticks + base + i_pad, q_c.begin());
-    uint64_t sat = 0;
-    const int rc = distributor(n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt, ni,
-                               tp_idx + base, max_batch + base, occ_c.data(), q_c.data(), n_req,
-                               prompt_len, out_len, slo_class, arrival_ticks, s_bar, pen_kappa,
-                               tbt_mode, win, nullptr, nullptr, nullptr, nullptr, nullptr, &sat, &st);
+    DeploymentScore d;
+    const int rc = score_deployment(pf, rs, su, ni, tp_idx + base, max_batch + base, occ + base,
+                                    q_ticks + base, d);
     if (rc != 0) return rc;
-    const float ps = (n_req == 0) ? 0.0f : (float)sat / (float)n_req;
-    float pt = 0.0f;
-    for (uint32_t j = 0; j < ni; ++j)
-      if (st.admitted_per_inst[j] != 0) pt = pt + 1.0f / st.tbt_first[j];
-    const float pl = (sat == 0) ? 0.0f : ((float)st.wait_ticks * 0x1p-20f) / (float)sat;
-    const float ptn = fminf(pt, gamma_t) / gamma_t;
-    const float pln = fmaxf(gamma_l - pl, 0.0f) / gamma_l;
-    const float sc = fmaf(alpha, ps, fmaf(beta, ptn, (1.0f - beta) * pln));
-    sat_count[c] = (uint32_t)sat;
-    phi_s[c] = ps; phi_t[c] = pt; phi_l[c] = pl; score[c] = sc;
-    if (sc > best_s) { best_s = sc; best_c = c; }
+    sat_count[c] = (uint32_t)d.sat;
+    phi_s[c] = d.phi_s; phi_t[c] = d.phi_t; phi_l[c] = d.phi_l; score[c] = d.score;
+    if (d.score > best_s) { best_s = d.score; best_c = c; }
   }
   if (best_cand) *best_cand = best_c;
+  return 0;
+}
+
+// Alg. 1 (simulator-based instance configuration, Sec. IV-E) for a single model.
+//
+// With one model the set M has one element, so "the model with most unserved requests" is always that
+// model and the first rejected instance saturates it, which ends the inner loop.  For every
+// configuration (P_i, B_i) in the given order the deployment grows by one fresh instance (empty, no
+// queued work) at a time; the grown deployment I' is scored against all of R_x with the composite
+// score (the distributor run of oracle_placement_score); it replaces I when its score is strictly
+// larger than I's (the empty deployment scores 0), and otherwise the configuration is finished.
+// Phi*[k] / I*[k] keep, per GPU count k = gpuCount(I) of the accepted deployment, the best score seen
+// (strictly larger replaces, so the earliest configuration wins ties); I*[k] is reported as
+// (configuration index, instance count), cfg_star[k] = -1 where nothing was stored (Phi*[k] = 0).
+// Readings: k is taken after acceptance; a grown deployment that would not fit in n_gpus GPUs, or
+// would have more than max_inst instances, is not evaluated and finishes the configuration.
+// n_evaluated (may be null) receives the number of deployments scored.
+// Returns 0, -1 bad arguments, -2 invalid profile or configuration.
+int oracle_ins_deploy(uint32_t n_tp, uint32_t b_cap, const float* prefill_a, const float* prefill_p,
+                      const float* tbt, uint32_t n_slo, const float* d_ttft, const float* d_tbt,
+                      const uint32_t* tp_degree, uint32_t n_req, const uint32_t* prompt_len,
+                      const uint32_t* out_len, const uint8_t* slo_class,
+                      const uint32_t* arrival_ticks, float s_bar, float pen_kappa, uint32_t tbt_mode,
+                      uint32_t window, float alpha, float beta, float gamma_t, float gamma_l,
+                      uint32_t n_gpus, uint32_t n_cfg, const uint8_t* cfg_tp, const uint16_t* cfg_b,
+                      uint32_t max_inst, float* phi_star, int32_t* cfg_star, uint32_t* cnt_star,
+                      uint64_t* n_evaluated) {
+  if (!tp_degree || !(gamma_t > 0.0f) || !(gamma_l > 0.0f)) return -1;
+  const Profile pf{n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt};
+  const RequestSet rs{n_req, prompt_len, out_len, slo_class, arrival_ticks};
+  const ScoreSetup su{s_bar, pen_kappa, tbt_mode, window, alpha, beta, gamma_t, gamma_l};
+  for (uint32_t k = 0; k <= n_gpus; ++k) { phi_star[k] = 0.0f; cfg_star[k] = -1; cnt_star[k] = 0; }
+  uint64_t evaluated = 0;
+  for (uint32_t i = 0; i < n_cfg; ++i) {
+    if (cfg_tp[i] >= n_tp || tp_degree[cfg_tp[i]] == 0) return -2;
+    const uint32_t deg = tp_degree[cfg_tp[i]];
+    std::vector<uint8_t> tp;       // the accepted deployment I: identical fresh instances
+    std::vector<uint16_t> mb;
+    float phi = 0.0f;
+    while ((uint64_t)tp.size() * deg < n_gpus) {
+      const size_t grown = tp.size() + 1;
+      if (grown * deg > n_gpus || grown > max_inst) break;
+      std::vector<uint8_t> tp2(tp);
+      std::vector<uint16_t> mb2(mb);
+      tp2.push_back(cfg_tp[i]);
+      mb2.push_back(cfg_b[i]);
+      const std::vector<int32_t> occ2(grown, 0);
+      const std::vector<uint64_t> q2(grown, 0);
+      DeploymentScore d;
+      const int rc = score_deployment(pf, rs, su, (uint32_t)grown, tp2.data(), mb2.data(),
+                                      occ2.data(), q2.data(), d);
+      if (rc != 0) return -2;
+      ++evaluated;
+      if (!(d.score > phi)) break;  // the model is saturated under this configuration
+      phi = d.score;
+      tp.swap(tp2);
+      mb.swap(mb2);
+      const size_t k = tp.size() * deg;
+      if (phi > phi_star[k]) {
+        phi_star[k] = phi;
+        cfg_star[k] = (int32_t)i;
+        cnt_star[k] = (uint32_t)tp.size();
+      }
+    }
+  }
+  if (n_evaluated) *n_evaluated = evaluated;
+  return 0;
+}
+
+// Alg. 2's scan over the two-way GPU partitions (dynamic resource partition, Sec. IV-E).
+//
+// phi_t_star / phi_l_star are Alg. 1's score lists (index = GPU count, 0..n_gpus) for the strict and
+// the relaxed request sets.  The relaxed sub-cluster may take g_l = 1 .. G'_l GPUs with
+// G'_l = floor(|R_l| / |R| * |G|) (taken as the floor of the exact quotient |R_l| * |G| / |R|; 0 when
+// R is empty), the strict one gets the rest, and the pair with the largest phi_t + phi_l (one binary32
+// addition) wins if it is strictly larger than the starting value; ascending g_l with a strict
+// comparison, so the smallest such g_l.  The starting value is the largest entry of phi_h_star
+// (Alg. 1 on all of R and all GPUs: the homogeneous fallback; its lowest index on ties) or 0 when
+// phi_h_star is null.  out[0..4] = g_t, g_l, heterogeneous (1/0), k_h (GPU count of the homogeneous
+// deployment, 0 without one); when the fallback stands, g_t = k_h and g_l = 0.
+int oracle_resource_partition(uint32_t n_gpus, const float* phi_t_star, const float* phi_l_star,
+                              const float* phi_h_star, uint64_t n_req_l, uint64_t n_req,
+                              uint32_t* out, float* phi_opt) {
+  if (n_req_l > n_req) return -1;
+  const uint32_t g_l_cap =
+      n_req == 0 ? 0u : (uint32_t)(((unsigned __int128)n_req_l * n_gpus) / n_req);
+  float opt = 0.0f;
+  uint32_t k_h = 0;
+  if (phi_h_star)
+    for (uint32_t k = 0; k <= n_gpus; ++k)
+      if (phi_h_star[k] > opt) { opt = phi_h_star[k]; k_h = k; }
+  uint32_t g_t = k_h, g_l = 0, hetero = 0;
+  for (uint32_t gl = 1; gl <= g_l_cap && gl <= n_gpus; ++gl) {
+    const uint32_t gt = n_gpus - gl;
+    const float sum = phi_t_star[gt] + phi_l_star[gl];
+    if (sum > opt) { opt = sum; g_t = gt; g_l = gl; hetero = 1; }
+  }
+  out[0] = g_t; out[1] = g_l; out[2] = hetero; out[3] = k_h;
+  *phi_opt = opt;
   return 0;
 }
 

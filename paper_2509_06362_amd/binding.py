@@ -23,7 +23,8 @@ EXPORTS = (
     "maaso_profile_tables_load", "maaso_ctx_destroy", "maaso_ctx_device_status", "maaso_strerror",
     "maaso_ctx_set_launch_shape", "maaso_ctx_set_wait_limit", "maaso_ctx_kernel_timing",
     "maaso_ctx_kernel_elapsed", "maaso_ctx_sweep_evaluated", "maaso_score_assign",
-    "maaso_placement_sweep", "maaso_placement_score",
+    "maaso_placement_sweep", "maaso_placement_score", "maaso_split_by_slo",
+    "maaso_ins_deploy_select", "maaso_resource_partition",
 )
 
 
@@ -104,6 +105,12 @@ def load_library() -> C.CDLL:
         lib.maaso_placement_score.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                               C.POINTER(Params), C.POINTER(ScoreWeights),
                                               C.POINTER(ScoreOut), C.c_void_p]
+        lib.maaso_split_by_slo.argtypes = [C.c_void_p, C.POINTER(Requests), C.c_uint32] + [C.c_void_p] * 6
+        lib.maaso_ins_deploy_select.argtypes = [C.c_void_p, C.POINTER(Placements), C.c_void_p,
+                                                C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p,
+                                                C.c_void_p, C.c_void_p]
+        lib.maaso_resource_partition.argtypes = [C.c_void_p, C.c_uint32] + [C.c_void_p] * 6 + [
+            C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -285,6 +292,42 @@ def maaso_placement_score(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_ba
            "maaso_placement_score")
 
 
+def maaso_split_by_slo(ctx: Context, *, n_req, prompt_len, out_len, slo_class, arrival_ticks=None,
+                       tight_classes, prompt_len_out, out_len_out, slo_class_out,
+                       arrival_ticks_out=None, n_tight, stream=None) -> None:
+    import torch
+    rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
+    _check(load_library().maaso_split_by_slo(
+        ctx.handle, C.byref(rq), int(tight_classes), _dptr(prompt_len_out, torch.int32),
+        _dptr(out_len_out, torch.int32), _dptr(slo_class_out, torch.uint8),
+        _dptr(arrival_ticks_out, torch.int32), _dptr(n_tight, torch.int32), _stream_handle(stream)),
+        "maaso_split_by_slo")
+
+
+def maaso_ins_deploy_select(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, score, chain_offsets=None,
+                            n_gpus, phi_star, cand_star, stream=None) -> None:
+    import torch
+    pl = Placements(int(n_cand), int(i_pad), _dptr(n_inst, torch.int32), _dptr(tp_idx, torch.uint8),
+                    None, None, None)
+    n_chains = 0 if chain_offsets is None else int(chain_offsets.numel()) - 1
+    _check(load_library().maaso_ins_deploy_select(
+        ctx.handle, C.byref(pl), _dptr(score, torch.float32), _dptr(chain_offsets, torch.int32),
+        n_chains, int(n_gpus), _dptr(phi_star, torch.float32), _dptr(cand_star, torch.int32),
+        _stream_handle(stream)), "maaso_ins_deploy_select")
+
+
+def maaso_resource_partition(ctx: Context, *, n_gpus, phi_t_star, phi_l_star, phi_h_star=None,
+                             cand_t_star=None, cand_l_star=None, cand_h_star=None, n_req_l, n_req,
+                             partition, phi_opt, stream=None) -> None:
+    import torch
+    _check(load_library().maaso_resource_partition(
+        ctx.handle, int(n_gpus), _dptr(phi_t_star, torch.float32), _dptr(phi_l_star, torch.float32),
+        _dptr(phi_h_star, torch.float32), _dptr(cand_t_star, torch.int32),
+        _dptr(cand_l_star, torch.int32), _dptr(cand_h_star, torch.int32), int(n_req_l), int(n_req),
+        _dptr(partition, torch.int32), _dptr(phi_opt, torch.float32), _stream_handle(stream)),
+        "maaso_resource_partition")
+
+
 # ------------------------------------------------------------------------------------------------
 # plumbing for tests and the benchmark: a workload's arrays as GPU tensors
 # ------------------------------------------------------------------------------------------------
@@ -355,6 +398,68 @@ class DeviceWorkload:
             **self.param_args(), alpha=alpha, beta=beta, gamma_t=gamma_t, gamma_l=gamma_l,
             stream=stream, **out)
         return out
+
+    def split_by_slo(self, tight_classes: int, stream=None):
+        """maaso_split_by_slo of the resident requests; returns the four reordered streams (arrival
+        None when the workload has none) and the device word holding |R_t|."""
+        import torch
+        dev = self.prompt_len.device
+        out = dict(prompt_len_out=torch.empty_like(self.prompt_len),
+                   out_len_out=torch.empty_like(self.out_len),
+                   slo_class_out=torch.empty_like(self.slo_class),
+                   arrival_ticks_out=None if self.arrival_ticks is None
+                   else torch.empty_like(self.arrival_ticks),
+                   n_tight=torch.empty(1, dtype=torch.int32, device=dev))
+        maaso_split_by_slo(self.ctx, **self.request_args(), arrival_ticks=self.arrival_ticks,
+                           tight_classes=tight_classes, stream=stream, **out)
+        return out
+
+    def resource_partition(self, chain_offsets, tight_classes: int, n_gpus: int, alpha, beta, gamma_t,
+                           gamma_l, window=0, homogeneous=True, stream=None):
+        """Alg. 2 over the resident candidates (growth chains of Alg. 1) and requests: split by SLO,
+        score every chain candidate against R_t, R_l (and all of R for the homogeneous fallback),
+        keep the best accepted deployment per GPU count, scan the partitions.  One device-to-host
+        copy (|R_t|) in the middle; everything else stays on the stream.  Returns a dict of tensors."""
+        import torch
+        dev = self.prompt_len.device
+        C_, R = self.w.n_cand, self.w.n_req
+        sp = self.split_by_slo(tight_classes, stream=stream)
+        n_t = int(sp["n_tight"].item())
+        offs = torch.from_numpy(np.ascontiguousarray(chain_offsets).view(np.int32)).to(dev)
+        res = dict(n_tight=n_t)
+
+        def deploy(tag, lo, hi, src):
+            sub = dict(n_req=hi - lo, prompt_len=src[0][lo:hi], out_len=src[1][lo:hi],
+                       slo_class=src[2][lo:hi],
+                       arrival_ticks=None if (src[3] is None or not window) else src[3][lo:hi])
+            sat = torch.empty(C_, dtype=torch.int32, device=dev)
+            score = torch.empty(C_, dtype=torch.float32, device=dev)
+            maaso_placement_score(
+                self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
+                max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, **sub, window=window,
+                **self.param_args(), alpha=alpha, beta=beta, gamma_t=gamma_t, gamma_l=gamma_l,
+                sat_count=sat, score=score, stream=stream)
+            phi = torch.empty(n_gpus + 1, dtype=torch.float32, device=dev)
+            cand = torch.empty(n_gpus + 1, dtype=torch.int32, device=dev)
+            maaso_ins_deploy_select(self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst,
+                                    tp_idx=self.tp_idx, score=score, chain_offsets=offs, n_gpus=n_gpus,
+                                    phi_star=phi, cand_star=cand, stream=stream)
+            res[f"score_{tag}"], res[f"phi_{tag}_star"], res[f"cand_{tag}_star"] = score, phi, cand
+
+        split = (sp["prompt_len_out"], sp["out_len_out"], sp["slo_class_out"], sp["arrival_ticks_out"])
+        deploy("t", 0, n_t, split)
+        deploy("l", n_t, R, split)
+        if homogeneous:
+            deploy("h", 0, R, (self.prompt_len, self.out_len, self.slo_class, self.arrival_ticks))
+        res["partition"] = torch.empty(6, dtype=torch.int32, device=dev)
+        res["phi_opt"] = torch.empty(1, dtype=torch.float32, device=dev)
+        maaso_resource_partition(
+            self.ctx, n_gpus=n_gpus, phi_t_star=res["phi_t_star"], phi_l_star=res["phi_l_star"],
+            phi_h_star=res.get("phi_h_star"), cand_t_star=res["cand_t_star"],
+            cand_l_star=res["cand_l_star"], cand_h_star=res.get("cand_h_star"), n_req_l=R - n_t,
+            n_req=R, partition=res["partition"], phi_opt=res["phi_opt"], stream=stream)
+        res["split"] = sp
+        return res
 
     def assign(self, cand: int = 0, window=None, latencies: bool = True, stream=None, out=None,
                tbt_mode=None):

@@ -13,6 +13,7 @@
 
 #include "assign_kernels.hpp"
 #include "sweep_kernels.hpp"
+#include "partition_kernels.hpp"
 #include "sweep_window_kernels.hpp"
 #include "window_kernels.hpp"
 
@@ -27,7 +28,8 @@ struct maaso_ctx {
   int device;
   uint32_t n_tp, b_cap, cells, n_slo;
   float d_ttft[kMaxSlo], d_tbt[kMaxSlo], i_ttft[kMaxSlo], i_tbt[kMaxSlo];
-  float* tab;           // device: three tables back to back
+  float* tab;           // device: three tables back to back, then tp_degree [n_tp] as uint32
+  bool has_degree;      // the profile came with GPUs-per-instance figures
   uint32_t* status;     // device status word
   uint32_t* cls_count;  // device [kMaxSlo]
   void* ws;             // device workspace, grow-only
@@ -159,6 +161,19 @@ void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placement
   a.sat_acc = reinterpret_cast<unsigned long long*>(ctx->status + 36);
 }
 
+// One block per candidate; requests per lane chosen so that a window keeps the lanes busy.
+template <bool kScore>
+int launch_sweep_window(const SweepWindowArgs& a, uint32_t n_cand, size_t lds, hipStream_t s) {
+  const uint64_t per_window = a.window < a.n_req ? a.window : a.n_req;
+  if (per_window > 2u * kAssignThreads)
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 4>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+  else if (per_window > kAssignThreads)
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 2>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+  else
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 1>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
 void fill_sweep_window_args(SweepWindowArgs& a, const maaso_ctx* ctx, const maaso_placements* pl,
                             const maaso_requests* rq, const maaso_params* prm, uint32_t window,
                             uint32_t* sat_count) {
@@ -262,7 +277,8 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   std::memcpy(host + cells, d->prefill_p, (size_t)cells * 4);
   std::memcpy(host + 2 * (size_t)cells, d->tbt, (size_t)cells * 4);
   int rc = MAASO_OK;
-  if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->tab), (size_t)3 * cells * 4))) rc = MAASO_E_NOMEM;
+  if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->tab), ((size_t)3 * cells + d->n_tp) * 4)))
+    rc = MAASO_E_NOMEM;
   if (rc == MAASO_OK && !hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->status), kSmallBytes))) rc = MAASO_E_NOMEM;
   if (rc == MAASO_OK) {
     // one small allocation, in 32-bit words: [0] status, [16..31] class counts, [32..33] evaluated
@@ -271,6 +287,11 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
     ctx->cls_count = ctx->status + 16;
     if (!hip_ok(hipMemcpy(ctx->tab, host, (size_t)3 * cells * 4, hipMemcpyHostToDevice)) ||
         !hip_ok(hipMemset(ctx->status, 0, kSmallBytes)))
+      rc = MAASO_E_HIP;
+    ctx->has_degree = d->tp_degree != nullptr;
+    if (rc == MAASO_OK && ctx->has_degree &&
+        !hip_ok(hipMemcpy(ctx->tab + (size_t)3 * cells, d->tp_degree, (size_t)d->n_tp * 4,
+                          hipMemcpyHostToDevice)))
       rc = MAASO_E_HIP;
   }
   std::free(host);
@@ -345,9 +366,8 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
     fill_sweep_window_args(a, ctx, pl, rq, prm, prm->window, sat_count);
     {
       TimedRegion timed(ctx, s);
-      hipLaunchKernelGGL(sweep_window_kernel<false>, dim3(C), dim3(kAssignThreads),
-                         (size_t)3 * ctx->cells * sizeof(float), s, a);
-      if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+      if (launch_sweep_window<false>(a, C, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
+        return MAASO_E_HIP;
     }
     unsigned long long* eval_total = reinterpret_cast<unsigned long long*>(ctx->status + 32);
     hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
@@ -501,9 +521,8 @@ int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maas
   a.score = out->score;
   {
     TimedRegion timed(ctx, s);
-    hipLaunchKernelGGL(sweep_window_kernel<true>, dim3(pl->n_cand), dim3(kAssignThreads),
-                       (size_t)3 * ctx->cells * sizeof(float), s, a);
-    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+    if (launch_sweep_window<true>(a, pl->n_cand, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
+      return MAASO_E_HIP;
   }
   if (out->best_cand) {
     hipLaunchKernelGGL(score_argmax_kernel, dim3(1), dim3(1024), 0, s, out->score, pl->n_cand,
@@ -511,6 +530,99 @@ int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maas
     if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
   }
   return MAASO_OK;
+}
+
+int maaso_split_by_slo(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_classes,
+                       uint32_t* prompt_len_out, uint32_t* out_len_out, uint8_t* slo_class_out,
+                       uint32_t* arrival_ticks_out, uint32_t* n_tight, void* hip_stream) {
+  if (!ctx || !rq || !n_tight) return MAASO_E_INVALID_ARG;
+  if (rq->n_req > MAASO_MAX_REQUESTS) return MAASO_E_SHAPE;
+  if (rq->n_req != 0 && (!rq->prompt_len || !rq->out_len || !rq->slo_class || !prompt_len_out ||
+                         !out_len_out || !slo_class_out))
+    return MAASO_E_INVALID_ARG;
+  if (rq->n_req != 0 && rq->arrival_ticks && !arrival_ticks_out) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint32_t n_blocks = (uint32_t)(((uint64_t)rq->n_req + kSplitPerBlock - 1) / kSplitPerBlock);
+  const int rc = ensure_workspace(ctx, (size_t)(n_blocks ? n_blocks : 1u) * sizeof(uint32_t));
+  if (rc != MAASO_OK) return rc;
+  SplitArgs a;
+  a.n_req = rq->n_req;
+  a.prompt_len = rq->prompt_len;
+  a.out_len = rq->out_len;
+  a.slo_class = rq->slo_class;
+  a.arrival_ticks = rq->arrival_ticks;
+  a.tight_classes = tight_classes;
+  a.n_slo = ctx->n_slo;
+  a.block_tight = static_cast<uint32_t*>(ctx->ws);
+  a.n_tight = n_tight;
+  a.prompt_out = prompt_len_out;
+  a.out_len_out = out_len_out;
+  a.class_out = slo_class_out;
+  a.arrival_out = arrival_ticks_out;
+  a.status = ctx->status;
+  if (n_blocks) hipLaunchKernelGGL(split_count_kernel, dim3(n_blocks), dim3(kPartitionThreads), 0, s, a);
+  hipLaunchKernelGGL(split_scan_kernel, dim3(1), dim3(kPartitionThreads), 0, s, a.block_tight, n_blocks,
+                     n_tight);
+  if (n_blocks) hipLaunchKernelGGL(split_scatter_kernel, dim3(n_blocks), dim3(kPartitionThreads), 0, s, a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+int maaso_ins_deploy_select(maaso_ctx* ctx, const maaso_placements* pl, const float* score,
+                            const uint32_t* chain_offsets, uint32_t n_chains, uint32_t n_gpus,
+                            float* phi_star, int32_t* cand_star, void* hip_stream) {
+  if (!ctx || !pl || !score || !phi_star || !cand_star) return MAASO_E_INVALID_ARG;
+  if (pl->n_cand == 0 || !pl->n_inst || !pl->tp_idx) return MAASO_E_INVALID_ARG;
+  if (!ctx->has_degree) return MAASO_E_INVALID_ARG;
+  if (pl->i_pad == 0 || pl->i_pad > MAASO_MAX_INSTANCES || n_gpus > MAASO_MAX_GPUS) return MAASO_E_SHAPE;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  SelectArgs a;
+  a.score = score;
+  a.n_cand = pl->n_cand;
+  a.i_pad = pl->i_pad;
+  a.n_inst = pl->n_inst;
+  a.tp_idx = pl->tp_idx;
+  a.tp_degree = reinterpret_cast<const uint32_t*>(ctx->tab + (size_t)3 * ctx->cells);
+  a.n_tp = ctx->n_tp;
+  a.chain_offsets = chain_offsets;
+  a.n_chains = chain_offsets ? n_chains : 0u;
+  a.n_gpus = n_gpus;
+  a.phi_star = phi_star;
+  a.cand_star = cand_star;
+  a.status = ctx->status;
+  hipLaunchKernelGGL(ins_deploy_select_kernel, dim3(1), dim3(kPartitionThreads),
+                     ((size_t)n_gpus + 1) * sizeof(unsigned long long),
+                     static_cast<hipStream_t>(hip_stream), a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t_star,
+                             const float* phi_l_star, const float* phi_h_star,
+                             const int32_t* cand_t_star, const int32_t* cand_l_star,
+                             const int32_t* cand_h_star, uint64_t n_req_l, uint64_t n_req,
+                             uint32_t* partition, float* phi_opt, void* hip_stream) {
+  if (!ctx || !phi_t_star || !phi_l_star || !partition || !phi_opt) return MAASO_E_INVALID_ARG;
+  if (n_req_l > n_req) return MAASO_E_INVALID_ARG;
+  if (n_gpus > MAASO_MAX_GPUS) return MAASO_E_SHAPE;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  PartitionArgs a;
+  a.n_gpus = n_gpus;
+  // initial share of the relaxed sub-cluster: floor(|R_l| / |R| * |G|), from the exact quotient
+  a.g_l_cap = n_req == 0 ? 0u : (uint32_t)(((unsigned __int128)n_req_l * n_gpus) / n_req);
+  a.phi_t_star = phi_t_star;
+  a.phi_l_star = phi_l_star;
+  a.phi_h_star = phi_h_star;
+  a.cand_t_star = cand_t_star;
+  a.cand_l_star = cand_l_star;
+  a.cand_h_star = cand_h_star;
+  a.out = partition;
+  a.phi_opt = phi_opt;
+  hipLaunchKernelGGL(resource_partition_kernel, dim3(1), dim3(kPartitionThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
 
 int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,

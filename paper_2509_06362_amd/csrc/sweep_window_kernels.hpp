@@ -56,7 +56,9 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 // candidate's score in the block: Phi = alpha * Phi_S^n + beta * min(Phi_T, gamma_T) / gamma_T +
 // (1 - beta) * max(gamma_L - Phi_L, 0) / gamma_L with Phi_T = sum of 1 / tbt_j over the serving
 // instances in index order (tbt_j of the first window) and Phi_L = mean wait of the admitted requests.
-template <bool kScore>
+// V: requests a lane scores at a time (4 for windows of a thousand requests or more; smaller windows
+// leave most of those idle, so they run with 2 or 1).
+template <bool kScore, int V>
 __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const SweepWindowArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* tab = reinterpret_cast<float*>(smem);
@@ -85,7 +87,6 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   const uint64_t R = a.n_req;
   const uint64_t n_windows = (R + a.window - 1) / a.window;
   uint32_t sat = 0;
-  constexpr int V = 4;
   uint32_t served = 0;                // requests admitted to instance tid over all windows
   unsigned long long wait_sum = 0ull; // their queue waits at admission, in ticks
   unsigned long long wait_ticks = 0ull;

@@ -243,6 +243,58 @@ def occupancy_below_cap(rng, max_batch, n_inst):
     return np.where(valid, occ, 0).astype(np.int32)
 
 
+def growth_chains(w: "Workload", cfg_tp, cfg_b, n_gpus: int, max_inst: int = 256):
+    """Candidate layout for Alg. 1's growth of a deployment (Sec. IV-E): for every configuration
+    (strategy row, batch size), in the given order, the deployments of 1, 2, ... identical fresh
+    instances (empty, nothing queued) that fit into `n_gpus` GPUs, at most `max_inst` instances.
+
+    Returns (workload with these candidates, chain_offsets): chain i is candidates
+    [chain_offsets[i], chain_offsets[i+1]) and its m-th candidate has m + 1 instances."""
+    cfg_tp = np.asarray(cfg_tp, dtype=np.uint8)
+    cfg_b = np.asarray(cfg_b, dtype=np.uint16)
+    lens = np.minimum(n_gpus // w.tp_degree[cfg_tp].astype(np.int64), max_inst)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
+    n_cand = int(offsets[-1])
+    i_pad = max(int(lens.max()) if len(lens) else 1, 1)
+    n_inst = np.concatenate([np.arange(1, n + 1) for n in lens] + [np.zeros(0)]).astype(np.uint32)
+    chain = np.repeat(np.arange(len(lens)), lens)
+    tp_idx = np.ascontiguousarray(np.broadcast_to(cfg_tp[chain][:, None], (n_cand, i_pad)))
+    max_batch = np.ascontiguousarray(np.broadcast_to(cfg_b[chain][:, None], (n_cand, i_pad)))
+    cw = replace(w, n_inst=n_inst, tp_idx=tp_idx, max_batch=max_batch,
+                 occ=np.zeros((n_cand, i_pad), dtype=np.int32),
+                 q_ticks=np.zeros((n_cand, i_pad), dtype=np.uint64))
+    return cw, offsets
+
+
+def all_configs(batch_set=BATCH_SET_128, n_tp: int = 4):
+    """Every (strategy row, batch size) pair, strategy-major: the unpruned configuration list."""
+    tp = np.repeat(np.arange(n_tp, dtype=np.uint8), len(batch_set))
+    b = np.tile(np.asarray(batch_set, dtype=np.uint16), n_tp)
+    return tp, b
+
+
+def partition_case(n_req: int = 65536, rate: float = 400.0, seed: int = 5,
+                   tight_share: float = 0.5) -> "Workload":
+    """Requests for the resource-partition scan (Alg. 2): a strict class (0.5 s, 50 ms) and a relaxed
+    one (10 s, 200 ms) mixed `tight_share` : 1 - `tight_share`, Poisson arrivals at `rate` requests/s,
+    shorter prompts and outputs than the sweep workloads so that a few dozen GPUs can keep up.
+    Carries one placeholder candidate; the placer's candidates come from growth_chains()."""
+    a, p, t = profile_tables(128)
+    rng = rng_for(seed, 1)
+    prompt = log_uniform_int(rng, 16, 2048, n_req)
+    out = log_uniform_int(rng, 8, 512, n_req)
+    cls = (rng.random(n_req) >= tight_share).astype(np.uint8)
+    return Workload(
+        name="alg2_partition", seed=seed, tp_degree=TP_DEGREES.copy(), b_cap=128,
+        prefill_a=a, prefill_p=p, tbt=t,
+        d_ttft=np.array([0.5, 10.0], dtype=np.float32), d_tbt=np.array([0.05, 0.2], dtype=np.float32),
+        prompt_len=prompt, out_len=out, slo_class=cls,
+        arrival_ticks=poisson_arrivals(rng_for(seed, 3), rate, n_req),
+        n_inst=np.array([1], dtype=np.uint32), tp_idx=np.zeros((1, 1), dtype=np.uint8),
+        max_batch=np.full((1, 1), 4, dtype=np.uint16), occ=np.zeros((1, 1), dtype=np.int32),
+        q_ticks=np.zeros((1, 1), dtype=np.uint64), s_bar=mean_out_len(out), window=256)
+
+
 # --------------------------------------------------------------------------------------------
 # the five workloads (+ one bandwidth-bound shape)
 # --------------------------------------------------------------------------------------------

@@ -325,6 +325,223 @@ def test_score_config_shapes():
 
 
 # ------------------------------------------------------------------------------------------------
+# placer's outer algorithms (Sec. IV-E): split by SLO, Alg. 1 bookkeeping, Alg. 2 partition scan
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_req,n_slo,mask,arrivals", [
+    (0, 3, 0b1, True), (1, 2, 0b10, False), (4095, 5, 0b01001, True), (4096, 5, 0b11111, True),
+    (4097, 5, 0, False), (70001, 16, 0xA5A5, True), (300000, 3, 0b100, True),
+])
+def test_split_by_slo(n_req, n_slo, mask, arrivals):
+    w = W.random_small(81, 1, 4, max(n_req, 1), n_slo=n_slo).with_requests(0, n_req)
+    arr = W.poisson_arrivals(W.rng_for(81, 3), 3000.0, n_req) if arrivals else None
+    w = W.replace(w, arrival_ticks=arr)
+    t, l = oracle.split_by_slo(w, mask)
+    dw = binding.DeviceWorkload(w)
+    try:
+        print(f"split R={n_req} K={n_slo} mask={mask:#x}", flush=True)
+        sp = dw.split_by_slo(mask)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        n_t = int(sp["n_tight"].item())
+        assert n_t == t.n_req
+        for key, name in (("prompt_len_out", "prompt_len"), ("out_len_out", "out_len"),
+                          ("slo_class_out", "slo_class"), ("arrival_ticks_out", "arrival_ticks")):
+            if sp[key] is None:
+                continue
+            got = sp[key].cpu().numpy()
+            got = got.view(np.uint32) if got.dtype == np.int32 else got
+            assert np.array_equal(got[:n_t], getattr(t, name)), name
+            assert np.array_equal(got[n_t:], getattr(l, name)), name
+    finally:
+        dw.close()
+
+
+def chain_case(n_req, rate, n_gpus, seed, batch_set=(4, 32, 128), max_inst=256):
+    w = W.partition_case(n_req=max(n_req, 1), rate=rate, seed=seed).with_requests(0, n_req)
+    tp, b = W.all_configs(batch_set=list(batch_set))
+    cw, offs = W.growth_chains(w, tp, b, n_gpus, max_inst=max_inst)
+    return w, cw, offs, tp, b
+
+
+def star_as_config(cand_star, offs):
+    """Candidate indices of a chain layout -> (configuration, instance count), -1/0 where empty."""
+    cfg = np.full(len(cand_star), -1, np.int64)
+    cnt = np.zeros(len(cand_star), np.int64)
+    for k, c in enumerate(cand_star):
+        if c >= 0:
+            cfg[k] = np.searchsorted(offs, c, side="right") - 1
+            cnt[k] = c - offs[cfg[k]] + 1
+    return cfg, cnt
+
+
+@pytest.mark.parametrize("n_req,rate,n_gpus,window,max_inst", [
+    (3000, 400.0, 32, 64, 256), (2000, 20.0, 16, 64, 256), (1500, 5.0, 16, 16, 256),
+    (1200, 150.0, 12, 32, 5), (800, 900.0, 9, 0, 256), (0, 400.0, 8, 16, 256), (2500, 300.0, 70, 128, 256),
+])
+def test_ins_deploy_select_reproduces_the_sequential_greedy(n_req, rate, n_gpus, window, max_inst):
+    """Scores from the oracle, bookkeeping on the GPU: Phi*[k] and I*[k] equal Alg. 1 run one
+    deployment at a time."""
+    w, cw, offs, tp, b = chain_case(n_req, rate, n_gpus, seed=20 + n_gpus, max_inst=max_inst)
+    ref = oracle.ins_deploy(w, n_gpus, tp, b, *SCORE_WEIGHTS[0], window=window, max_inst=max_inst)
+    scores = oracle.placement_score(cw, *SCORE_WEIGHTS[0], window=window)["score"]
+    dw = binding.DeviceWorkload(cw)
+    try:
+        dev = dw.prompt_len.device
+        phi = torch.empty(n_gpus + 1, dtype=torch.float32, device=dev)
+        cand = torch.empty(n_gpus + 1, dtype=torch.int32, device=dev)
+        print(f"select chains C={cw.n_cand} I={cw.i_pad} G={n_gpus} window={window}", flush=True)
+        binding.maaso_ins_deploy_select(
+            dw.ctx, n_cand=cw.n_cand, i_pad=cw.i_pad, n_inst=dw.n_inst, tp_idx=dw.tp_idx,
+            score=torch.from_numpy(scores).to(dev),
+            chain_offsets=torch.from_numpy(offs.view(np.int32)).to(dev), n_gpus=n_gpus,
+            phi_star=phi, cand_star=cand)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        assert np.array_equal(phi.cpu().numpy(), ref["phi_star"])
+        cfg, cnt = star_as_config(cand.cpu().numpy(), offs)
+        assert np.array_equal(cfg, ref["cfg_star"]) and np.array_equal(cnt, ref["cnt_star"])
+    finally:
+        dw.close()
+
+
+def test_ins_deploy_select_without_chains_and_with_ties():
+    """Every candidate eligible: per GPU count the largest positive score, lowest index on ties."""
+    w = W.random_small(83, 700, 12, 10, n_slo=2)
+    rng = np.random.default_rng(83)
+    scores = (rng.integers(-2, 6, w.n_cand) * 0.25).astype(np.float32)   # many equal values, some <= 0
+    k = np.array([int(w.tp_degree[w.tp_idx[c, :w.n_inst[c]]].sum()) for c in range(w.n_cand)])
+    n_gpus = int(np.percentile(k, 80))                                   # some candidates do not fit
+    phi_ref = np.zeros(n_gpus + 1, np.float32)
+    cand_ref = np.full(n_gpus + 1, -1, np.int32)
+    for c in range(w.n_cand):
+        if k[c] <= n_gpus and scores[c] > phi_ref[k[c]]:
+            phi_ref[k[c]], cand_ref[k[c]] = scores[c], c
+    dw = binding.DeviceWorkload(w)
+    try:
+        dev = dw.prompt_len.device
+        phi = torch.empty(n_gpus + 1, dtype=torch.float32, device=dev)
+        cand = torch.empty(n_gpus + 1, dtype=torch.int32, device=dev)
+        binding.maaso_ins_deploy_select(
+            dw.ctx, n_cand=w.n_cand, i_pad=w.i_pad, n_inst=dw.n_inst, tp_idx=dw.tp_idx,
+            score=torch.from_numpy(scores).to(dev), n_gpus=n_gpus, phi_star=phi, cand_star=cand)
+        torch.cuda.synchronize()
+        assert np.array_equal(phi.cpu().numpy(), phi_ref)
+        assert np.array_equal(cand.cpu().numpy(), cand_ref)
+        assert (cand_ref >= 0).sum() > 3
+    finally:
+        dw.close()
+
+
+def test_resource_partition_scan():
+    w = W.random_small(84, 1, 4, 10)
+    dw = binding.DeviceWorkload(w)
+    rng = np.random.default_rng(84)
+    try:
+        dev = dw.prompt_len.device
+        part = torch.empty(6, dtype=torch.int32, device=dev)
+        opt = torch.empty(1, dtype=torch.float32, device=dev)
+        seen = set()
+        for trial in range(60):
+            n_gpus = int(rng.integers(0, 40)) if trial % 10 else 4096
+            coarse = trial % 2 == 0   # coarse values: equal sums are common
+            draw = (lambda n: (rng.integers(0, 6, n) * 0.5).astype(np.float32)) if coarse else \
+                (lambda n: rng.random(n, dtype=np.float32) * 5)
+            pt, pl = draw(n_gpus + 1), draw(n_gpus + 1)
+            ph = None if trial % 3 == 0 else draw(n_gpus + 1) * np.float32(1.7)
+            ct, cl, ch = (rng.integers(-1, 1000, n_gpus + 1).astype(np.int32) for _ in range(3))
+            n = int(rng.integers(0, 50))
+            n_l = int(rng.integers(0, n + 1))
+            ref = oracle.resource_partition(n_gpus, pt, pl, ph, n_l, n)
+            up = lambda a: None if a is None else torch.from_numpy(a).to(dev)  # noqa: E731
+            binding.maaso_resource_partition(
+                dw.ctx, n_gpus=n_gpus, phi_t_star=up(pt), phi_l_star=up(pl), phi_h_star=up(ph),
+                cand_t_star=up(ct), cand_l_star=up(cl), cand_h_star=up(ch), n_req_l=n_l, n_req=n,
+                partition=part, phi_opt=opt)
+            torch.cuda.synchronize()
+            got = part.cpu().numpy()
+            assert got[:4].tolist() == [ref["g_t"], ref["g_l"], ref["heterogeneous"], ref["k_h"]], trial
+            assert float(opt.item()) == ref["phi_opt"]
+            if ref["heterogeneous"]:
+                assert got[4] == ct[ref["g_t"]] and got[5] == cl[ref["g_l"]]
+            else:
+                assert got[5] == -1
+                assert got[4] == (ch[ref["k_h"]] if (ph is not None and ref["phi_opt"] > 0) else -1)
+            seen.add(ref["heterogeneous"])
+        assert seen == {0, 1}
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("n_req,rate,n_gpus,window,share", [
+    (6000, 400.0, 32, 64, 0.5), (4000, 60.0, 24, 32, 0.2), (3000, 900.0, 16, 256, 0.8),
+    (2000, 300.0, 12, 64, 1.0), (2000, 300.0, 12, 64, 0.0),
+])
+def test_resource_partition_end_to_end(n_req, rate, n_gpus, window, share):
+    """Alg. 2 as one pipeline of library calls against the oracle's sequential Alg. 1 + Alg. 2."""
+    w = W.partition_case(n_req=n_req, rate=rate, seed=30 + n_gpus, tight_share=share)
+    tp, b = W.all_configs(batch_set=[4, 16, 64])
+    cw, offs = W.growth_chains(w, tp, b, n_gpus)
+    wts = SCORE_WEIGHTS[0]
+    r_t, r_l = oracle.split_by_slo(w, 0b1)
+    ref = {tag: oracle.ins_deploy(ws, n_gpus, tp, b, *wts, window=window)
+           for tag, ws in (("t", r_t), ("l", r_l), ("h", w))}
+    part = oracle.resource_partition(n_gpus, ref["t"]["phi_star"], ref["l"]["phi_star"],
+                                     ref["h"]["phi_star"], r_l.n_req, w.n_req)
+    dw = binding.DeviceWorkload(cw)
+    try:
+        print(f"alg2 R={n_req} G={n_gpus} C={cw.n_cand} window={window} share={share}", flush=True)
+        got = dw.resource_partition(offs, 0b1, n_gpus, *wts, window=window)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        assert got["n_tight"] == r_t.n_req
+        for tag in ("t", "l", "h"):
+            assert np.array_equal(got[f"phi_{tag}_star"].cpu().numpy(), ref[tag]["phi_star"]), tag
+            cfg, cnt = star_as_config(got[f"cand_{tag}_star"].cpu().numpy(), offs)
+            assert np.array_equal(cfg, ref[tag]["cfg_star"]) and np.array_equal(cnt, ref[tag]["cnt_star"])
+        p = got["partition"].cpu().numpy()
+        assert p[:4].tolist() == [part["g_t"], part["g_l"], part["heterogeneous"], part["k_h"]]
+        assert float(got["phi_opt"].item()) == part["phi_opt"]
+    finally:
+        dw.close()
+
+
+def test_outer_algorithm_error_paths():
+    w, cw, offs, tp, b = chain_case(200, 100.0, 8, seed=7)
+    dw = binding.DeviceWorkload(cw)
+    try:
+        dev = dw.prompt_len.device
+        score = torch.ones(cw.n_cand, dtype=torch.float32, device=dev)
+        phi = torch.empty(4098, dtype=torch.float32, device=dev)
+        cand = torch.empty(4098, dtype=torch.int32, device=dev)
+        args = dict(n_cand=cw.n_cand, i_pad=cw.i_pad, n_inst=dw.n_inst, tp_idx=dw.tp_idx, score=score,
+                    phi_star=phi, cand_star=cand)
+        with pytest.raises(binding.MaasoError) as e:
+            binding.maaso_ins_deploy_select(dw.ctx, n_gpus=4097, **args)
+        assert e.value.status == -2
+        # a chain list that runs backwards, and one that runs past the candidates: flagged, ignored
+        bad = torch.tensor([0, 5, 3, cw.n_cand + 1], dtype=torch.int32, device=dev)
+        binding.maaso_ins_deploy_select(dw.ctx, n_gpus=8, chain_offsets=bad, **args)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 8
+        assert np.count_nonzero(cand[:9].cpu().numpy() >= 0) == 1     # only chain [0, 5) counted
+        with pytest.raises(binding.MaasoError) as e:
+            binding.maaso_resource_partition(dw.ctx, n_gpus=4, phi_t_star=phi, phi_l_star=phi,
+                                             n_req_l=5, n_req=4, partition=cand, phi_opt=phi)
+        assert e.value.status == -1
+        # a profile loaded without GPU counts cannot drive Alg. 1's bookkeeping
+        ctx = binding.maaso_profile_tables_load(cw.n_tp, cw.b_cap, cw.prefill_a, cw.prefill_p, cw.tbt,
+                                                cw.d_ttft, cw.d_tbt, None, 0)
+        try:
+            with pytest.raises(binding.MaasoError) as e:
+                binding.maaso_ins_deploy_select(ctx, n_gpus=8, **args)
+            assert e.value.status == -1
+        finally:
+            ctx.close()
+    finally:
+        dw.close()
+
+
+# ------------------------------------------------------------------------------------------------
 # distributor, static
 # ------------------------------------------------------------------------------------------------
 
