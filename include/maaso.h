@@ -162,6 +162,13 @@ typedef struct {
                         1: worst case w = B (the distributor's conservative estimate, Sec. IV-F)   */
   uint32_t window;   /* 0: every request is scored against the state as given (static);
                         n > 0: requests are taken n at a time and the state advances in between    */
+  uint32_t policy;   /* which instance a request is given (Sec. IV-F step 2):
+                        0: the one with the largest slack (lowest index on ties);
+                        1: among the instances able to meet its SLO (slack >= 0) the one with the
+                           shortest request queue - fewest requests W_j on it at the start of the
+                           window - lowest index on ties; the paper's wording.  With no capable
+                           instance the request is blocked either way and the largest-slack instance
+                           is reported.  The static sweep's counts do not depend on it.          */
 } maaso_params;
 
 /* Per-request outputs of the distributor.  DEVICE pointers; any of them may be NULL (not written),

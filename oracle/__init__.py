@@ -110,7 +110,7 @@ def score_assign(w, cand: int = 0, window=None, tbt_mode=None, latencies: bool =
         _ptr(occ, C.c_int32), _ptr(q, C.c_uint64), C.c_uint32(R),
         _ptr(w.prompt_len, C.c_uint32), _ptr(w.out_len, C.c_uint32), _ptr(w.slo_class, C.c_uint8),
         _ptr(arr, C.c_uint32), C.c_float(float(w.s_bar)), C.c_float(float(w.pen_kappa)),
-        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window),
+        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window), C.c_uint32(int(w.policy)),
         _ptr(chosen, C.c_int32), _ptr(slack, C.c_float), _ptr(lt, C.c_float), _ptr(lb, C.c_float),
         _ptr(le, C.c_float), C.byref(n_sat))
     if rc != 0:
@@ -156,7 +156,7 @@ def placement_sweep_windowed(w, window=None, c_begin: int = 0, c_end=None, tbt_m
         _ptr(w.occ, C.c_int32), _ptr(w.q_ticks, C.c_uint64), C.c_uint32(w.n_req),
         _ptr(w.prompt_len, C.c_uint32), _ptr(w.out_len, C.c_uint32), _ptr(w.slo_class, C.c_uint8),
         _ptr(w.arrival_ticks, C.c_uint32), C.c_float(float(w.s_bar)), C.c_float(float(w.pen_kappa)),
-        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window),
+        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window), C.c_uint32(int(w.policy)),
         C.c_uint32(c_begin), C.c_uint32(c_end), _ptr(cnt, C.c_uint32), _ptr(ratio, C.c_float),
         C.byref(best))
     if rc != 0:
@@ -180,7 +180,7 @@ def placement_score(w, alpha, beta, gamma_t, gamma_l, window=0, c_begin: int = 0
         _ptr(w.occ, C.c_int32), _ptr(w.q_ticks, C.c_uint64), C.c_uint32(w.n_req),
         _ptr(w.prompt_len, C.c_uint32), _ptr(w.out_len, C.c_uint32), _ptr(w.slo_class, C.c_uint8),
         _ptr(w.arrival_ticks, C.c_uint32), C.c_float(float(w.s_bar)), C.c_float(float(w.pen_kappa)),
-        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window),
+        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window), C.c_uint32(int(w.policy)),
         C.c_float(alpha), C.c_float(beta), C.c_float(gamma_t), C.c_float(gamma_l),
         C.c_uint32(c_begin), C.c_uint32(c_end), _ptr(cnt, C.c_uint32), _ptr(ps, C.c_float),
         _ptr(pt, C.c_float), _ptr(pl, C.c_float), _ptr(sc, C.c_float), C.byref(best))
@@ -223,7 +223,7 @@ def ins_deploy(w, n_gpus: int, cfg_tp, cfg_b, alpha, beta, gamma_t, gamma_l, win
         *_profile_args(w), *_slo_args(w), _ptr(deg, C.c_uint32), C.c_uint32(w.n_req),
         _ptr(w.prompt_len, C.c_uint32), _ptr(w.out_len, C.c_uint32), _ptr(w.slo_class, C.c_uint8),
         _ptr(w.arrival_ticks, C.c_uint32), C.c_float(float(w.s_bar)), C.c_float(float(w.pen_kappa)),
-        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window),
+        C.c_uint32(w.tbt_mode if tbt_mode is None else tbt_mode), C.c_uint32(window), C.c_uint32(int(w.policy)),
         C.c_float(alpha), C.c_float(beta), C.c_float(gamma_t), C.c_float(gamma_l),
         C.c_uint32(n_gpus), C.c_uint32(len(cfg_tp)), _ptr(cfg_tp, C.c_uint8), _ptr(cfg_b, C.c_uint16),
         C.c_uint32(max_inst), _ptr(phi, C.c_float), _ptr(cfg, C.c_int32), _ptr(cnt, C.c_uint32),

@@ -168,11 +168,12 @@ int distributor(uint32_t n_tp, uint32_t b_cap, const float* prefill_a, const flo
                 uint32_t n_inst, const uint8_t* tp_idx, const uint16_t* max_batch, int32_t* occ,
                 uint64_t* q_ticks, uint32_t n_req, const uint32_t* prompt_len,
                 const uint32_t* out_len, const uint8_t* slo_class, const uint32_t* arrival_ticks,
-                float s_bar, float pen_kappa, uint32_t tbt_mode, uint32_t window, int32_t* chosen,
+                float s_bar, float pen_kappa, uint32_t tbt_mode, uint32_t window, uint32_t policy,
+                int32_t* chosen,
                 float* slack, float* lat_ttft, float* lat_tbt, float* lat_e2e, uint64_t* n_satisfied,
                 RunStats* stats) {
   Profile pf{n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt};
-  if (!profile_ok(pf)) return -1;
+  if (!profile_ok(pf) || policy > 1u) return -1;
   if (stats) {
     stats->admitted_per_inst.assign(n_inst, 0);
     stats->tbt_first.assign(n_inst, 0.0f);
@@ -210,6 +211,20 @@ int distributor(uint32_t n_tp, uint32_t b_cap, const float* prefill_a, const flo
       for (uint32_t j = 0; j < n_inst; ++j) {
         Triple t = score_triple(st[j], L, S, Dt, Db, De, iDt[k], iDb[k], iDe);
         if (t.slack > best) { best = t.slack; idx = (int32_t)j; bt = t; }
+      }
+      if (policy == 1) {
+        // Sec. IV-F step 2 as the paper words it: among the instances able to meet the request's
+        // SLO (slack >= 0) the one with the shortest request queue - the fewest requests on it at
+        // the start of the window - and the lowest index among those.  Without a capable instance
+        // the request is blocked and the largest-slack instance found above is reported.
+        int32_t pick = -1;
+        Triple pt{nan, nan, nan, nan, nan, nan, nan};
+        for (uint32_t j = 0; j < n_inst; ++j) {
+          Triple t = score_triple(st[j], L, S, Dt, Db, De, iDt[k], iDb[k], iDe);
+          if (!(t.slack >= 0.0f)) continue;
+          if (pick < 0 || occ[j] < occ[pick]) { pick = (int32_t)j; pt = t; }
+        }
+        if (pick >= 0) { idx = pick; best = pt.slack; bt = pt; }
       }
       const bool admitted = best >= 0.0f;
       if (admitted) {
@@ -258,7 +273,7 @@ struct RequestSet {
 
 struct ScoreSetup {
   float s_bar, pen_kappa;
-  uint32_t tbt_mode, window;
+  uint32_t tbt_mode, window, policy;
   float alpha, beta, gamma_t, gamma_l;
 };
 
@@ -285,7 +300,7 @@ int score_deployment(const Profile& pf, const RequestSet& rs, const ScoreSetup& 
   const int rc = distributor(pf.n_tp, pf.b_cap, pf.prefill_a, pf.prefill_p, pf.tbt, pf.n_slo,
                              pf.d_ttft, pf.d_tbt, ni, tp_idx, max_batch, occ_c.data(), q_c.data(),
                              rs.n_req, rs.prompt_len, rs.out_len, rs.slo_class, rs.arrival_ticks,
-                             su.s_bar, su.pen_kappa, su.tbt_mode, win, nullptr, nullptr, nullptr,
+                             su.s_bar, su.pen_kappa, su.tbt_mode, win, su.policy, nullptr, nullptr, nullptr,
                              nullptr, nullptr, &sat, &st);
   if (rc != 0) return rc;
   const float ps = (rs.n_req == 0) ? 0.0f : (float)sat / (float)rs.n_req;
@@ -319,11 +334,13 @@ int oracle_score_assign(uint32_t n_tp, uint32_t b_cap, const float* prefill_a,
                         uint64_t* q_ticks, uint32_t n_req, const uint32_t* prompt_len,
                         const uint32_t* out_len, const uint8_t* slo_class,
                         const uint32_t* arrival_ticks, float s_bar, float pen_kappa,
-                        uint32_t tbt_mode, uint32_t window, int32_t* chosen, float* slack,
+                        uint32_t tbt_mode, uint32_t window, uint32_t policy, int32_t* chosen,
+                        float* slack,
                         float* lat_ttft, float* lat_tbt, float* lat_e2e, uint64_t* n_satisfied) {
   return distributor(n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt, n_inst, tp_idx,
                      max_batch, occ, q_ticks, n_req, prompt_len, out_len, slo_class, arrival_ticks,
-                     s_bar, pen_kappa, tbt_mode, window, chosen, slack, lat_ttft, lat_tbt, lat_e2e,
+                     s_bar, pen_kappa, tbt_mode, window, policy, chosen, slack, lat_ttft, lat_tbt,
+                     lat_e2e,
                      n_satisfied, nullptr);
 }
 
@@ -390,6 +407,7 @@ int oracle_placement_sweep_windowed(uint32_t n_tp, uint32_t b_cap, const float* 
                                     const uint32_t* prompt_len, const uint32_t* out_len,
                                     const uint8_t* slo_class, const uint32_t* arrival_ticks,
                                     float s_bar, float pen_kappa, uint32_t tbt_mode, uint32_t window,
+                                    uint32_t policy,
                                     uint32_t c_begin, uint32_t c_end, uint32_t* sat_count,
                                     float* sat_ratio, uint32_t* best_cand) {
   if (c_end > n_cand || window == 0) return -1;
@@ -405,7 +423,8 @@ int oracle_placement_sweep_windowed(uint32_t n_tp, uint32_t b_cap, const float* 
     const int rc = oracle_score_assign(n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt,
                                        std::min(n_inst[c], i_pad), tp_idx + base, max_batch + base,
                                        occ_c.data(), q_c.data(), n_req, prompt_len, out_len, slo_class,
-                                       arrival_ticks, s_bar, pen_kappa, tbt_mode, window, nullptr,
+                                       arrival_ticks, s_bar, pen_kappa, tbt_mode, window, policy,
+                                       nullptr,
                                        nullptr, nullptr, nullptr, nullptr, &sat);
     if (rc != 0) return rc;
     sat_count[c] = (uint32_t)sat;
@@ -435,14 +454,15 @@ int oracle_placement_score(uint32_t n_tp, uint32_t b_cap, const float* prefill_a
                            const int32_t* occ, const uint64_t* q_ticks, uint32_t n_req,
                            const uint32_t* prompt_len, const uint32_t* out_len,
                            const uint8_t* slo_class, const uint32_t* arrival_ticks, float s_bar,
-                           float pen_kappa, uint32_t tbt_mode, uint32_t window, float alpha,
+                           float pen_kappa, uint32_t tbt_mode, uint32_t window, uint32_t policy,
+                           float alpha,
                            float beta, float gamma_t, float gamma_l, uint32_t c_begin, uint32_t c_end,
                            uint32_t* sat_count, float* phi_s, float* phi_t, float* phi_l,
                            float* score, uint32_t* best_cand) {
   if (c_end > n_cand || !(gamma_t > 0.0f) || !(gamma_l > 0.0f)) return -1;
   const Profile pf{n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt};
   const RequestSet rs{n_req, prompt_len, out_len, slo_class, arrival_ticks};
-  const ScoreSetup su{s_bar, pen_kappa, tbt_mode, window, alpha, beta, gamma_t, gamma_l};
+  const ScoreSetup su{s_bar, pen_kappa, tbt_mode, window, policy, alpha, beta, gamma_t, gamma_l};
   uint32_t best_c = c_begin;
   float best_s = -INFINITY;
   for (uint32_t c = c_begin; c < c_end; ++c) {
@@ -480,14 +500,14 @@ int oracle_ins_deploy(uint32_t n_tp, uint32_t b_cap, const float* prefill_a, con
                       const uint32_t* tp_degree, uint32_t n_req, const uint32_t* prompt_len,
                       const uint32_t* out_len, const uint8_t* slo_class,
                       const uint32_t* arrival_ticks, float s_bar, float pen_kappa, uint32_t tbt_mode,
-                      uint32_t window, float alpha, float beta, float gamma_t, float gamma_l,
-                      uint32_t n_gpus, uint32_t n_cfg, const uint8_t* cfg_tp, const uint16_t* cfg_b,
+                      uint32_t window, uint32_t policy, float alpha, float beta, float gamma_t,
+                      float gamma_l, uint32_t n_gpus, uint32_t n_cfg, const uint8_t* cfg_tp, const uint16_t* cfg_b,
                       uint32_t max_inst, float* phi_star, int32_t* cfg_star, uint32_t* cnt_star,
                       uint64_t* n_evaluated) {
   if (!tp_degree || !(gamma_t > 0.0f) || !(gamma_l > 0.0f)) return -1;
   const Profile pf{n_tp, b_cap, prefill_a, prefill_p, tbt, n_slo, d_ttft, d_tbt};
   const RequestSet rs{n_req, prompt_len, out_len, slo_class, arrival_ticks};
-  const ScoreSetup su{s_bar, pen_kappa, tbt_mode, window, alpha, beta, gamma_t, gamma_l};
+  const ScoreSetup su{s_bar, pen_kappa, tbt_mode, window, policy, alpha, beta, gamma_t, gamma_l};
   for (uint32_t k = 0; k <= n_gpus; ++k) { phi_star[k] = 0.0f; cfg_star[k] = -1; cnt_star[k] = 0; }
   uint64_t evaluated = 0;
   for (uint32_t i = 0; i < n_cfg; ++i) {

@@ -53,7 +53,7 @@ class Placements(C.Structure):
 
 class Params(C.Structure):
     _fields_ = [("s_bar", C.c_float), ("pen_kappa", C.c_float), ("tbt_mode", C.c_uint32),
-                ("window", C.c_uint32)]
+                ("window", C.c_uint32), ("policy", C.c_uint32)]
 
 
 class AssignOut(C.Structure):
@@ -243,7 +243,7 @@ def _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks) -> Place
 
 def maaso_score_assign(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
                        n_req, prompt_len, out_len, slo_class, arrival_ticks=None,
-                       s_bar, pen_kappa=0.0, tbt_mode=0, window=0,
+                       s_bar, pen_kappa=0.0, tbt_mode=0, window=0, policy=0,
                        chosen=None, slack=None, ttft=None, tbt=None, e2e=None, n_satisfied=None,
                        stream=None) -> None:
     """All array arguments are GPU torch tensors holding the C types' bit patterns
@@ -251,7 +251,7 @@ def maaso_score_assign(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch
     import torch
     pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
     rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
-    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window))
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window), int(policy))
     out = AssignOut(_dptr(chosen, torch.int32), _dptr(slack, torch.float32),
                     _dptr(ttft, torch.float32), _dptr(tbt, torch.float32),
                     _dptr(e2e, torch.float32), _dptr(n_satisfied, torch.int64))
@@ -262,12 +262,12 @@ def maaso_score_assign(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch
 
 def maaso_placement_sweep(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
                           n_req, prompt_len, out_len, slo_class, arrival_ticks=None, s_bar,
-                          pen_kappa=0.0, tbt_mode=0, window=0, sat_count, sat_ratio=None,
+                          pen_kappa=0.0, tbt_mode=0, window=0, policy=0, sat_count, sat_ratio=None,
                           best_cand=None, stream=None) -> None:
     import torch
     pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
     rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
-    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window))
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window), int(policy))
     _check(load_library().maaso_placement_sweep(
         ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm), _dptr(sat_count, torch.int32),
         _dptr(sat_ratio, torch.float32), _dptr(best_cand, torch.int32), _stream_handle(stream)),
@@ -276,13 +276,13 @@ def maaso_placement_sweep(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_ba
 
 def maaso_placement_score(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
                           n_req, prompt_len, out_len, slo_class, arrival_ticks=None, s_bar,
-                          pen_kappa=0.0, tbt_mode=0, window=0, alpha, beta, gamma_t, gamma_l,
+                          pen_kappa=0.0, tbt_mode=0, window=0, policy=0, alpha, beta, gamma_t, gamma_l,
                           sat_count, score, phi_s=None, phi_t=None, phi_l=None, best_cand=None,
                           stream=None) -> None:
     import torch
     pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
     rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
-    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window))
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window), int(policy))
     wts = ScoreWeights(float(alpha), float(beta), float(gamma_t), float(gamma_l))
     out = ScoreOut(_dptr(sat_count, torch.int32), _dptr(phi_s, torch.float32),
                    _dptr(phi_t, torch.float32), _dptr(phi_l, torch.float32),
@@ -363,7 +363,7 @@ class DeviceWorkload:
 
     def param_args(self):
         return dict(s_bar=float(self.w.s_bar), pen_kappa=float(self.w.pen_kappa),
-                    tbt_mode=int(self.w.tbt_mode))
+                    tbt_mode=int(self.w.tbt_mode), policy=int(self.w.policy))
 
     def sweep(self, stream=None, out=None, window=0):
         """maaso_placement_sweep over all candidates; returns (sat_count, sat_ratio, best_cand).

@@ -71,6 +71,23 @@ __device__ __forceinline__ void stage_placement(const AssignArgs& a, uint32_t n,
   }
 }
 
+// Shortest-queue rule (Sec. IV-F step 2 as worded in the paper: among the instances able to meet the
+// request's SLO, the one with the shortest request queue, lowest index on ties).  Every instance gets
+// a value from its place in the order of (requests on it, index): 512 - place, in [257, 512].  A
+// triple whose slack is non-negative competes with that value instead of its slack; slacks never
+// exceed 1, so capable instances beat incapable ones, the shortest queue beats the longer one, and
+// the values being distinct, no ties arise.  With no capable instance the comparison is the ordinary
+// one on (negative) slacks, and the request is blocked as before.
+__device__ __forceinline__ float queue_rank_value(const int32_t* occ_s, uint32_t n, uint32_t j) {
+  const int32_t mine = occ_s[j];
+  uint32_t place = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    const int32_t o = occ_s[i];
+    place += (o < mine || (o == mine && i < j)) ? 1u : 0u;
+  }
+  return (float)(512u - place);
+}
+
 constexpr int kS2Stride = 257;  // odd: the per-class rows of the margin table fall on different banks
 
 // V consecutive requests starting at r0 (V = 4: 16-byte loads and stores; V = 1: any alignment).
@@ -82,13 +99,19 @@ constexpr int kS2Stride = 257;  // odd: the per-class rows of the margin table f
 // NREG > 0: the placement has at most NREG instances and the caller holds their records in
 // registers (`rreg`); the margin is recomputed from the class row, so the loop touches no LDS - the
 // form used when there are so few instances that the request stream from HBM is the bound.
-template <bool kLat, int V, int NREG>
+//
+// kSQ: shortest-queue rule; `rankv` (LDS) or `rrank` (registers, with NREG) hold the instances'
+// queue_rank_value, and the slack written out is the chosen instance's own.
+template <bool kLat, int V, int NREG, bool kSQ>
 __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_t r0, uint32_t n,
                                                     const float4* __restrict__ recs,
                                                     const ClassRow* __restrict__ cls,
                                                     const float* __restrict__ s2tab,
-                                                    const float4* rreg) {
+                                                    const float4* rreg,
+                                                    const float* __restrict__ rankv,
+                                                    const float* rrank) {
   float L[V], S[V], best[V], De[V], iDe[V], Dt[V], iDt[V], Db[V], iDb[V];
+  float b_slack[V];
   float b_ttft[V], b_tbt[V], b_e2e[V];
   uint32_t k[V];
   int32_t idx[V];
@@ -117,10 +140,11 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
     De[v] = fmaf(S[v], c.Db, c.Dt);
     iDe[v] = 1.0f / De[v];
     best[v] = -INFINITY;
+    b_slack[v] = -INFINITY;
     idx[v] = -1;
     b_ttft[v] = b_tbt[v] = b_e2e[v] = __builtin_nanf("");
   }
-  auto score = [&](const float4 r, uint32_t j) {  // r = {a, p, tbt, wait}
+  auto score = [&](const float4 r, uint32_t j, float rank) {  // r = {a, p, tbt, wait}
 #pragma unroll
     for (int v = 0; v < V; ++v) {
       const float pre = fmaf(r.y, L[v], r.x);
@@ -130,9 +154,11 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
       const float s2 = NREG ? (Db[v] - r.z) * iDb[v] : s2tab[k[v] * kS2Stride + j];
       const float s3 = (De[v] - e2e) * iDe[v];
       const float slack = fminf(fminf(s1, s2), s3);
-      if (slack > best[v]) {
-        best[v] = slack;
+      const float val = (kSQ && slack >= 0.0f) ? rank : slack;
+      if (val > best[v]) {
+        best[v] = val;
         idx[v] = (int32_t)j;
+        if (kSQ) b_slack[v] = slack;
         if (kLat) { b_ttft[v] = ttft; b_tbt[v] = r.z; b_e2e[v] = e2e; }
       }
     }
@@ -140,15 +166,16 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
   if (NREG) {
 #pragma unroll
     for (int j = 0; j < (NREG ? NREG : 1); ++j)
-      if ((uint32_t)j < n) score(rreg[j], (uint32_t)j);
+      if ((uint32_t)j < n) score(rreg[j], (uint32_t)j, kSQ ? rrank[j] : 0.0f);
   } else {
-    for (uint32_t j = 0; j < n; ++j) score(recs[j], j);
+    for (uint32_t j = 0; j < n; ++j) score(recs[j], j, kSQ ? rankv[j] : 0.0f);
   }
   uint32_t sat = 0;
 #pragma unroll
   for (int v = 0; v < V; ++v) {
     if (!ok[v]) { best[v] = -INFINITY; idx[v] = -1; b_ttft[v] = b_tbt[v] = b_e2e[v] = __builtin_nanf(""); }
-    sat += (best[v] >= 0.0f) ? 1u : 0u;
+    sat += (best[v] >= 0.0f) ? 1u : 0u;   // a rank value is positive: some instance can serve
+    if (kSQ && ok[v]) best[v] = b_slack[v];  // what is written out is the chosen instance's slack
   }
   if (V == 4) {
     if (a.chosen) *reinterpret_cast<int4*>(a.chosen + r0) = make_int4(idx[0], idx[1], idx[2], idx[3]);
@@ -189,15 +216,21 @@ __device__ __forceinline__ void fill_class_tables(const AssignArgs& a, uint32_t 
 
 // V = 4 needs 16-byte aligned request and output arrays (slo_class 4-byte aligned); the host checks.
 // NREG > 0 requires n_inst <= NREG (the host checks against the i_pad it was given).
-template <bool kLat, int V, int NREG>
+template <bool kLat, int V, int NREG, bool kSQ>
 __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const AssignArgs a) {
   __shared__ float4 recs[256];
   __shared__ ClassRow cls[kMaxSlo];
   __shared__ float s2tab[NREG ? 1 : kMaxSlo * kS2Stride];
   __shared__ uint32_t wave_sat[kAssignThreads / 64];
+  __shared__ int32_t occ_s[kSQ ? 256 : 1];
+  __shared__ float rankv[kSQ ? 256 : 1];
   const uint32_t n = min(min(a.n_inst[0], a.i_pad), NREG ? (uint32_t)NREG : 256u);
   stage_placement(a, n, recs, nullptr);
+  if (kSQ)
+    for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) occ_s[j] = a.occ[j];
   __syncthreads();
+  if (kSQ)
+    for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) rankv[j] = queue_rank_value(occ_s, n, j);
   if (NREG) {
     if (threadIdx.x < a.n_slo) {
       const uint32_t k = threadIdx.x;
@@ -208,18 +241,21 @@ __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const Ass
   }
   __syncthreads();
   float4 rreg[NREG ? NREG : 1];
+  float rrank[NREG ? NREG : 1];
 #pragma unroll
-  for (int j = 0; j < (NREG ? NREG : 1); ++j)
+  for (int j = 0; j < (NREG ? NREG : 1); ++j) {
     rreg[j] = (NREG && (uint32_t)j < n) ? recs[j] : make_float4(1.0f, 1.0f, 1.0f, INFINITY);
+    rrank[j] = (kSQ && NREG && (uint32_t)j < n) ? rankv[j] : 0.0f;
+  }
 
   uint32_t sat = 0;
   const uint64_t n_vec = (uint64_t)a.n_req / V;  // groups of V requests
   for (uint64_t g = (uint64_t)blockIdx.x * kAssignThreads + threadIdx.x; g < n_vec;
        g += (uint64_t)gridDim.x * kAssignThreads)
-    sat += assign_requests<kLat, V, NREG>(a, g * V, n, recs, cls, s2tab, rreg);
+    sat += assign_requests<kLat, V, NREG, kSQ>(a, g * V, n, recs, cls, s2tab, rreg, rankv, rrank);
   if (V > 1 && blockIdx.x == 0) {  // the ragged tail, one request per thread
     const uint64_t r = n_vec * V + threadIdx.x;
-    if (r < a.n_req) sat += assign_requests<kLat, 1, NREG>(a, r, n, recs, cls, s2tab, rreg);
+    if (r < a.n_req) sat += assign_requests<kLat, 1, NREG, kSQ>(a, r, n, recs, cls, s2tab, rreg, rankv, rrank);
   }
   // Admitted count: wavefront shuffle, block sum in LDS, one atomic per block into an accumulator
   // the library owns and keeps at zero between calls.  Every block then takes a ticket; the block

@@ -108,7 +108,7 @@ int check_common(const maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
   if (rq->n_req > MAASO_MAX_REQUESTS) return MAASO_E_SHAPE;
   if (!(prm->s_bar > 0.0f) || !std::isfinite(prm->s_bar)) return MAASO_E_INVALID_ARG;
   if (!(prm->pen_kappa >= 0.0f) || !std::isfinite(prm->pen_kappa)) return MAASO_E_INVALID_ARG;
-  if (prm->tbt_mode > 1u) return MAASO_E_INVALID_ARG;
+  if (prm->tbt_mode > 1u || prm->policy > 1u) return MAASO_E_INVALID_ARG;
   return MAASO_OK;
 }
 
@@ -162,16 +162,23 @@ void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placement
 }
 
 // One block per candidate; requests per lane chosen so that a window keeps the lanes busy.
-template <bool kScore>
-int launch_sweep_window(const SweepWindowArgs& a, uint32_t n_cand, size_t lds, hipStream_t s) {
+template <bool kScore, bool kSQ>
+int launch_sweep_window_v(const SweepWindowArgs& a, uint32_t n_cand, size_t lds, hipStream_t s) {
   const uint64_t per_window = a.window < a.n_req ? a.window : a.n_req;
   if (per_window > 2u * kAssignThreads)
-    hipLaunchKernelGGL((sweep_window_kernel<kScore, 4>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 4, kSQ>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
   else if (per_window > kAssignThreads)
-    hipLaunchKernelGGL((sweep_window_kernel<kScore, 2>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 2, kSQ>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
   else
-    hipLaunchKernelGGL((sweep_window_kernel<kScore, 1>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 1, kSQ>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+template <bool kScore>
+int launch_sweep_window(const SweepWindowArgs& a, uint32_t policy, uint32_t n_cand, size_t lds,
+                        hipStream_t s) {
+  return policy ? launch_sweep_window_v<kScore, true>(a, n_cand, lds, s)
+                : launch_sweep_window_v<kScore, false>(a, n_cand, lds, s);
 }
 
 void fill_sweep_window_args(SweepWindowArgs& a, const maaso_ctx* ctx, const maaso_placements* pl,
@@ -366,7 +373,7 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
     fill_sweep_window_args(a, ctx, pl, rq, prm, prm->window, sat_count);
     {
       TimedRegion timed(ctx, s);
-      if (launch_sweep_window<false>(a, C, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
+      if (launch_sweep_window<false>(a, prm->policy, C, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
         return MAASO_E_HIP;
     }
     unsigned long long* eval_total = reinterpret_cast<unsigned long long*>(ctx->status + 32);
@@ -521,7 +528,7 @@ int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maas
   a.score = out->score;
   {
     TimedRegion timed(ctx, s);
-    if (launch_sweep_window<true>(a, pl->n_cand, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
+    if (launch_sweep_window<true>(a, prm->policy, pl->n_cand, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
       return MAASO_E_HIP;
   }
   if (out->best_cand) {
@@ -656,8 +663,15 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
     // few instance slots: records live in registers and the loop needs no LDS (HBM-bound shape)
     const bool few = pl->i_pad <= 8u;
     TimedRegion timed(ctx, s);
-#define MAASO_LAUNCH_STATIC(LAT, V, NREG)                                                       \
-  hipLaunchKernelGGL((assign_static_kernel<LAT, V, NREG>), dim3(blocks), dim3(kAssignThreads), 0, s, a)
+#define MAASO_LAUNCH_STATIC(LAT, V, NREG)                                                          \
+  do {                                                                                             \
+    if (prm->policy)                                                                               \
+      hipLaunchKernelGGL((assign_static_kernel<LAT, V, NREG, true>), dim3(blocks),                 \
+                         dim3(kAssignThreads), 0, s, a);                                           \
+    else                                                                                           \
+      hipLaunchKernelGGL((assign_static_kernel<LAT, V, NREG, false>), dim3(blocks),                \
+                         dim3(kAssignThreads), 0, s, a);                                           \
+  } while (0)
     if (vec) {
       if (few) { if (lat) MAASO_LAUNCH_STATIC(true, 4, 8); else MAASO_LAUNCH_STATIC(false, 4, 8); }
       else     { if (lat) MAASO_LAUNCH_STATIC(true, 4, 0); else MAASO_LAUNCH_STATIC(false, 4, 0); }
@@ -693,12 +707,15 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
   TimedRegion timed(ctx, s);
 #define MAASO_LAUNCH_WINDOW(LPR)                                                                  \
   do {                                                                                            \
-    if (lat)                                                                                      \
-      hipLaunchKernelGGL((assign_window_kernel<LPR, true>), dim3(nb), dim3(kWindowThreads), wlds, s, \
-                         a, prm->window, ws, spin);                                               \
-    else                                                                                          \
-      hipLaunchKernelGGL((assign_window_kernel<LPR, false>), dim3(nb), dim3(kWindowThreads), wlds, s, \
-                         a, prm->window, ws, spin);                                               \
+    if (prm->policy) /* latency outputs are null-checked in the kernel: one variant serves both */ \
+      hipLaunchKernelGGL((assign_window_kernel<LPR, true, true>), dim3(nb), dim3(kWindowThreads),  \
+                         wlds, s, a, prm->window, ws, spin);                                       \
+    else if (lat)                                                                                  \
+      hipLaunchKernelGGL((assign_window_kernel<LPR, true, false>), dim3(nb), dim3(kWindowThreads), \
+                         wlds, s, a, prm->window, ws, spin);                                       \
+    else                                                                                           \
+      hipLaunchKernelGGL((assign_window_kernel<LPR, false, false>), dim3(nb), dim3(kWindowThreads), \
+                         wlds, s, a, prm->window, ws, spin);                                       \
   } while (0)
   switch (lpr) {
     case 1: MAASO_LAUNCH_WINDOW(1); break;

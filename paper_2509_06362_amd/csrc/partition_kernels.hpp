@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kPartitionThreads) void ins_deploy_select_kernel(co
       }
     }
   }
-  __syncthreads();
+  lds_atomics_barrier();
   for (uint32_t k = tid; k <= a.n_gpus; k += kPartitionThreads) {
     const unsigned long long key = keys[k];
     a.phi_star[k] = key ? order_float((uint32_t)(key >> 32)) : 0.0f;

@@ -47,6 +47,17 @@ constexpr int kMaxGroup = 64;                                 // candidates per 
 constexpr int kStageSlotsPerBlock = 512;   // two per thread: short blocks, their loads overlap
 constexpr int kBucketPerBlock = 1024;
 
+// Barrier that publishes LDS atomics.  For atomics whose result is unused the compiler emits no wait
+// on the LDS counter before the s_barrier of __syncthreads(), and on gfx950 a wavefront reading behind
+// that barrier can then see the location without some of the additions (observed as run-to-run
+// differences in the per-window admission counts).  Waiting for this wavefront's outstanding LDS
+// operations (s_waitcnt lgkmcnt(0), all other counters left at their maxima) before the barrier
+// closes that window.  Atomics whose result is used need nothing: the use already waits.
+__device__ __forceinline__ void lds_atomics_barrier() {
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  __syncthreads();
+}
+
 __device__ __forceinline__ void raise_status(uint32_t* status, uint32_t bit) {
   if ((__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit) == 0u)
     atomicOr(status, bit);

@@ -58,7 +58,8 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 // instances in index order (tbt_j of the first window) and Phi_L = mean wait of the admitted requests.
 // V: requests a lane scores at a time (4 for windows of a thousand requests or more; smaller windows
 // leave most of those idle, so they run with 2 or 1).
-template <bool kScore, int V>
+// kSQ: the distributor's shortest-queue rule (see queue_rank_value) instead of the largest slack.
+template <bool kScore, int V, bool kSQ>
 __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const SweepWindowArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* tab = reinterpret_cast<float*>(smem);
@@ -68,6 +69,8 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   __shared__ uint32_t n_blk[256];
   __shared__ unsigned long long t_blk[256];
   __shared__ uint32_t wave_sat[kAssignThreads / 64];
+  __shared__ int32_t occ_s[kSQ ? 256 : 1];
+  __shared__ float rankv[kSQ ? 256 : 1];
 
   const uint32_t tid = threadIdx.x;
   const uint32_t c = blockIdx.x;
@@ -113,8 +116,10 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
       }
       n_blk[tid] = 0u;
       t_blk[tid] = 0ull;
+      if (kSQ) occ_s[tid] = occ;
     }
     __syncthreads();
+    if (kSQ && tid < n) rankv[tid] = queue_rank_value(occ_s, n, tid);
     for (uint32_t i = tid; i < a.n_slo * n; i += kAssignThreads) {
       const uint32_t k = i / n, j = i - k * n;
       s2tab[k * kS2Stride + j] = (a.d_tbt[k] - recs[j].z) * a.i_tbt[k];
@@ -152,7 +157,8 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
           const float s2 = s2tab[k[v] * kS2Stride + j];
           const float s3 = (De[v] - e2e) * iDe[v];
           const float slack = fminf(fminf(s1, s2), s3);
-          if (slack > best[v]) { best[v] = slack; idx[v] = (int32_t)j; bpre[v] = pre; }
+          const float val = (kSQ && slack >= 0.0f) ? rankv[j] : slack;
+          if (val > best[v]) { best[v] = val; idx[v] = (int32_t)j; bpre[v] = pre; }
         }
       }
 #pragma unroll
@@ -175,7 +181,7 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
         }
       }
     }
-    __syncthreads();
+    lds_atomics_barrier();
 
     if (tid < n) {
       if (kScore) {

@@ -92,7 +92,9 @@ __device__ __forceinline__ bool grid_barrier(WindowWs* ws, unsigned long long ta
   return *lds_flag != 0;
 }
 
-template <int LPR, bool kLat>
+// kSQ: shortest-queue rule (see queue_rank_value); the rank values are rebuilt at every window from
+// the queue lengths the window starts with.
+template <int LPR, bool kLat, bool kSQ>
 __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const AssignArgs a,
                                                                        uint32_t window,
                                                                        WindowWs* ws,
@@ -105,6 +107,8 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
   __shared__ unsigned long long t_blk[256];
   __shared__ uint32_t wave_sat[kWindowThreads / 64];
   __shared__ int bar_ok;
+  __shared__ int32_t occ_s[kSQ ? 256 : 1];
+  __shared__ float rankv[kSQ ? 256 : 1];
 
   const uint32_t tid = threadIdx.x;
   const uint32_t n = min(a.n_inst[0], a.i_pad);
@@ -154,6 +158,7 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
       }
       n_blk[tid] = 0u;
       t_blk[tid] = 0ull;
+      if (kSQ) occ_s[tid] = occ;
     }
     if (blockIdx.x == 0 && tid < 256u) {  // recycle the accumulators that window w+2 will use
       __hip_atomic_store(&ws->ring_n[(w + 2) % kRing][tid], 0u, __ATOMIC_RELAXED,
@@ -162,6 +167,13 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
                          __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
+    if (kSQ) {
+      if (tid < n) rankv[tid] = queue_rank_value(occ_s, n, tid);
+      __syncthreads();
+    }
+    // what a triple competes with: its slack, or under the shortest-queue rule its instance's rank
+    // value once the slack is non-negative
+    auto value = [&](float slack, uint32_t j) { return (kSQ && slack >= 0.0f) ? rankv[j] : slack; };
 
     const uint64_t base0 = s0 + (uint64_t)blockIdx.x * kReqPerBlock;
     for (uint64_t base = base0; base < e0; base += (uint64_t)gridDim.x * kReqPerBlock) {
@@ -186,10 +198,10 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
           uint32_t j = sl;
           for (; j + 3u * LPR < n; j += 4u * LPR) {  // four records per trip: one LDS wait for four reads
             const float4 r0 = recs[j], r1 = recs[j + LPR], r2 = recs[j + 2u * LPR], r3 = recs[j + 3u * LPR];
-            const float s0 = score_triple(r0.x, r0.y, r0.z, r0.w, L, S, d).slack;
-            const float s1 = score_triple(r1.x, r1.y, r1.z, r1.w, L, S, d).slack;
-            const float s2 = score_triple(r2.x, r2.y, r2.z, r2.w, L, S, d).slack;
-            const float s3 = score_triple(r3.x, r3.y, r3.z, r3.w, L, S, d).slack;
+            const float s0 = value(score_triple(r0.x, r0.y, r0.z, r0.w, L, S, d).slack, j);
+            const float s1 = value(score_triple(r1.x, r1.y, r1.z, r1.w, L, S, d).slack, j + LPR);
+            const float s2 = value(score_triple(r2.x, r2.y, r2.z, r2.w, L, S, d).slack, j + 2u * LPR);
+            const float s3 = value(score_triple(r3.x, r3.y, r3.z, r3.w, L, S, d).slack, j + 3u * LPR);
             if (s0 > best) { best = s0; idx = (int32_t)j; }
             if (s1 > best) { best = s1; idx = (int32_t)(j + LPR); }
             if (s2 > best) { best = s2; idx = (int32_t)(j + 2u * LPR); }
@@ -197,8 +209,8 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
           }
           for (; j < n; j += LPR) {
             const float4 rc = recs[j];
-            const Margins m = score_triple(rc.x, rc.y, rc.z, rc.w, L, S, d);
-            if (m.slack > best) { best = m.slack; idx = (int32_t)j; }
+            const float sv = value(score_triple(rc.x, rc.y, rc.z, rc.w, L, S, d).slack, j);
+            if (sv > best) { best = sv; idx = (int32_t)j; }
           }
         } else if (sl == 0) {
           raise_status(a.status, 1u);
@@ -207,10 +219,12 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
       argmax_lanes<LPR>(best, idx);
       if (live && sl == 0) {
         float o_ttft = __builtin_nanf(""), o_tbt = o_ttft, o_e2e = o_ttft;
+        float o_slack = best;
         if (idx >= 0) {
           const float4 rc = recs[idx];
           const Margins m = score_triple(rc.x, rc.y, rc.z, rc.w, L, S, d);
           o_ttft = m.ttft; o_tbt = rc.z; o_e2e = m.e2e;
+          if (kSQ) o_slack = m.slack;  // `best` may be a rank value; report the instance's own slack
           if (best >= 0.0f) {  // admitted: it loads the instance; a blocked request does not
             ++sat;
             atomicAdd(&n_blk[idx], 1u);
@@ -218,7 +232,7 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
           }
         }
         if (a.chosen) a.chosen[r] = idx;
-        if (a.slack) a.slack[r] = best;
+        if (a.slack) a.slack[r] = o_slack;
         if (kLat) {
           if (a.ttft) a.ttft[r] = o_ttft;
           if (a.tbt) a.tbt[r] = o_tbt;
@@ -227,7 +241,7 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
       }
     }
     prefetch(w + 1);
-    __syncthreads();
+    lds_atomics_barrier();
     if (tid < n && n_blk[tid] != 0u) {
       atomicAdd(&ws->ring_n[w % kRing][tid], n_blk[tid]);
       atomicAdd(&ws->ring_t[w % kRing][tid], t_blk[tid]);

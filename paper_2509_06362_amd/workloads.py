@@ -58,6 +58,7 @@ class Workload:
     pen_kappa: np.float32 = np.float32(0.0)
     tbt_mode: int = 0
     window: int = 0
+    policy: int = 0   # 0: largest slack; 1: shortest request queue among the capable instances
     notes: dict = field(default_factory=dict)
 
     @property

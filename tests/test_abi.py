@@ -39,7 +39,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(binding.ProfileDesc) == 64
     assert C.sizeof(binding.Requests) == 40
     assert C.sizeof(binding.Placements) == 48
-    assert C.sizeof(binding.Params) == 16
+    assert C.sizeof(binding.Params) == 20
     assert C.sizeof(binding.AssignOut) == 48
     assert C.sizeof(binding.ScoreWeights) == 16
     assert C.sizeof(binding.ScoreOut) == 48

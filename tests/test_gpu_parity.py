@@ -218,6 +218,26 @@ def test_windowed_sweep_small_irregular(seed, n_cand, i_pad, n_req, n_slo, windo
     assert spread > 1
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+def test_windowed_sweep_repeats_exactly(policy):
+    """Short windows, many of them, repeated on fresh contexts: every call must give the oracle's
+    counts.  (Guards the publication of the per-window LDS sums: unused-result LDS atomics need an
+    explicit wait before the barrier, without it single candidates came out differently from call to
+    call.)"""
+    w = W.random_small(161, 30, 16, 3000, n_slo=3, pen_kappa=0.5)
+    w = W.replace(w, policy=policy, occ=(w.occ // 3).astype(np.int32))
+    ref = oracle.placement_sweep_windowed(w, window=256)["sat_count"]
+    for trial in range(3):
+        dw = binding.DeviceWorkload(w)
+        try:
+            for rep in range(6):
+                cnt, _, _ = dw.sweep(window=256)
+                torch.cuda.synchronize()
+                assert np.array_equal(u32(cnt), ref), (trial, rep)
+        finally:
+            dw.close()
+
+
 def test_windowed_sweep_one_window_equals_static_sweep():
     w = W.stressed(W.config1(n_cand=64, n_req=4096), seed=9)
     w = W.replace(w, arrival_ticks=W.poisson_arrivals(W.rng_for(9, 3), 2000.0, 4096))
@@ -578,6 +598,90 @@ def test_assign_streaming_shape_sampled():
     """The bandwidth-bound shape (4 instances, long stream) at 2^22 requests."""
     w = W.streaming_shape(n_req=1 << 22)
     check_assign(w, window=0)
+
+
+# ------------------------------------------------------------------------------------------------
+# shortest-queue rule (policy 1) on every path that chooses an instance
+# ------------------------------------------------------------------------------------------------
+def shortest_queue(w, coarse_queues=True):
+    """Policy 1 on `w`; with coarse_queues the queue lengths collide often (ties by index)."""
+    occ = (w.occ // 3).astype(np.int32) if coarse_queues else w.occ
+    return W.replace(w, policy=1, occ=occ)
+
+
+@pytest.mark.parametrize("seed,i_pad,n_req,n_slo", [(121, 12, 5000, 3), (122, 1, 300, 1),
+                                                    (123, 200, 2000, 8), (124, 256, 1027, 16),
+                                                    (125, 7, 10001, 2), (126, 8, 4099, 3)])
+def test_assign_static_shortest_queue(seed, i_pad, n_req, n_slo):
+    w = W.random_small(seed, 1, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
+    w = W.replace(w, n_inst=np.array([i_pad], np.uint32))
+    differs = 0
+    for v in (w, W.stressed(w, seed=seed), W.stressed(w, seed=seed, deadline_scale=0.05)):
+        for coarse in (True, False):
+            for lat in (True, False):
+                got = check_assign(shortest_queue(v, coarse), window=0, latencies=lat)
+            ref0 = oracle.score_assign(v, window=0)
+            differs += int((got["chosen"].cpu().numpy() != ref0["chosen"]).sum())
+    assert differs > 0 or i_pad == 1
+
+
+def test_assign_static_shortest_queue_unaligned():
+    w = shortest_queue(W.stressed(W.random_small(127, 1, 20, 3001, n_slo=3), seed=3))
+    w = W.replace(w, n_inst=np.array([20], np.uint32))
+    dw = binding.DeviceWorkload(w)
+    try:
+        dev = dw.prompt_len.device
+        R = w.n_req - 1
+        chosen = torch.empty(R + 1, dtype=torch.int32, device=dev)
+        slack = torch.empty(R + 1, dtype=torch.float32, device=dev)
+        n_sat = torch.empty(1, dtype=torch.int64, device=dev)
+        binding.maaso_score_assign(
+            dw.ctx, n_cand=1, i_pad=w.i_pad, n_inst=dw.n_inst, tp_idx=dw.tp_idx, max_batch=dw.max_batch,
+            occ=dw.occ, q_ticks=dw.q_ticks, n_req=R, prompt_len=dw.prompt_len[1:],
+            out_len=dw.out_len[1:], slo_class=dw.slo_class[1:], **dw.param_args(), chosen=chosen[1:],
+            slack=slack[1:], n_satisfied=n_sat)
+        torch.cuda.synchronize()
+        ref = oracle.score_assign(w.with_requests(1, R + 1), window=0)
+        assert np.array_equal(chosen[1:].cpu().numpy(), ref["chosen"])
+        assert np.array_equal(slack[1:].cpu().numpy(), ref["slack"])
+        assert int(n_sat.item()) == ref["n_satisfied"]
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("seed,i_pad,n_inst,window,blocks", [
+    (141, 8, 5, 64, 2), (142, 100, 77, 200, 32), (143, 256, 256, 128, 64), (144, 3, 3, 1000, 0),
+    (145, 64, 64, 1, 1),
+])
+def test_assign_windowed_shortest_queue(seed, i_pad, n_inst, window, blocks):
+    w = W.random_small(seed, 1, i_pad, 6000 if window > 1 else 300, n_slo=3, pen_kappa=0.25)
+    w = W.replace(w, n_inst=np.array([n_inst], np.uint32), policy=1,
+                  arrival_ticks=W.poisson_arrivals(W.rng_for(seed, 3), 800.0, w.n_req))
+    check_assign(w, window=window, window_blocks=blocks)
+    check_assign(W.stressed(w, seed=seed), window=window, window_blocks=blocks, latencies=False)
+
+
+def test_assign_windowed_shortest_queue_config2_reduced():
+    w = W.replace(W.config2(n_req=16384, window=512), policy=1)
+    got = check_assign(w, window=512)
+    ref0 = oracle.score_assign(W.replace(w, policy=0), window=512)
+    assert (got["chosen"].cpu().numpy() != ref0["chosen"]).mean() > 0.05
+    check_assign(W.replace(w, tbt_mode=1), window=512)      # with the worst-case estimate: the paper's rule
+
+
+@pytest.mark.parametrize("seed,n_cand,i_pad,n_req,n_slo,window", [
+    (161, 30, 16, 3000, 3, 256), (162, 9, 48, 2500, 5, 1000), (163, 4, 256, 900, 16, 333),
+    (164, 20, 7, 300, 2, 1), (165, 12, 32, 2000, 3, 0),
+])
+def test_sweep_and_score_shortest_queue(seed, n_cand, i_pad, n_req, n_slo, window):
+    w = W.random_small(seed, n_cand, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
+    for v in (w, W.stressed(w, seed=seed, deadline_scale=0.25)):
+        v = shortest_queue(v)
+        if window:
+            check_sweep_windowed(v, window)
+        else:
+            check_sweep(v)                      # static counts do not depend on the rule
+        check_score(v, window, weights=SCORE_WEIGHTS[:2])
 
 
 def test_assign_static_unaligned_arrays_take_the_scalar_path():
