@@ -48,28 +48,31 @@ SCORE_WEIGHTS = (4.0, 0.3, 16384.0, 2.0)
 
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by the
-# readings of a 1 GiB copy kernel (see profiles/).  A figure only holds for the kernel sources it
-# was taken with: it is reported while their digest matches and as null afterwards.
+# readings of a 1 GiB copy kernel (see profiles/).  A figure only holds for the kernel it was taken
+# with: it is reported while the digest of that kernel's source files matches and as null afterwards.
+KERNEL_SOURCES = {
+    "sweep_kernel": ("device_model.hpp", "sweep_kernels.hpp"),
+    "assign_static_kernel": ("device_model.hpp", "sweep_kernels.hpp", "assign_kernels.hpp"),
+}
 TRAFFIC = {
-    "cfg1_placer_sweep": (6.710e6, "bb9d81ab373b9c46"),
-    "streaming_i4": (1.1411e9, "bb9d81ab373b9c46"),
+    "cfg1_placer_sweep": ("sweep_kernel", 6.710e6, "653b4e45f6286630"),
+    "streaming_i4": ("assign_static_kernel", 1.1411e9, "47ab7fff637e03c7"),
 }
 
 
-def kernel_source_digest() -> str:
+def kernel_source_digest(kernel: str) -> str:
     import hashlib
     h = hashlib.sha256()
-    for f in sorted((ROOT / "paper_2509_06362_amd" / "csrc").glob("*")):
-        if f.suffix in (".hpp", ".hip"):
-            h.update(f.read_bytes())
+    for name in KERNEL_SOURCES[kernel]:
+        h.update((ROOT / "paper_2509_06362_amd" / "csrc" / name).read_bytes())
     return h.hexdigest()[:16]
 
 
 def measured_traffic(workload_name: str):
     entry = TRAFFIC.get(workload_name)
-    if entry is None or entry[1] != kernel_source_digest():
+    if entry is None or entry[2] != kernel_source_digest(entry[0]):
         return None
-    return entry[0]
+    return entry[1]
 
 
 def make_workload(name: str):
