@@ -82,6 +82,25 @@ typedef struct {
   const float* d_tbt;        /* [K] seconds, within [2^-20, 2^20]                        */
 } maaso_profile_desc;
 
+/* Profiler (Sec. IV-B): least-squares fit of the throughput-decay function of Eq. 1,
+ *   F(w) = T0 * (1 - delta * log(eps + w)),  w = min(B, W),
+ * to measured samples, one fit per parallelism strategy, and the per-token latency table the scoring
+ * reads: tbt[t][b] = 1 / F_t(b), b = 1..b_cap (column 0 = NaN), ready for maaso_profile_desc.tbt.
+ * All pointers are HOST memory; the call copies in, runs on `device`, copies out and synchronises.
+ *   offsets [n_tp+1]: the samples of strategy t are [offsets[t], offsets[t+1]) (at least 3 each);
+ *   level [N]: w of a sample, >= 1;  thr [N]: its measured throughput in tokens/s, > 0;
+ *   eps is searched in [eps_lo, eps_hi], 0 < eps_lo < eps_hi;
+ *   params [n_tp][4] (binary64): T0, delta, eps, residual sum of squares;  tbt [n_tp*(b_cap+1)].
+ * For a fixed eps the fit is a straight line in log(eps + w) with a closed-form solution; eps itself is
+ * found by a nested grid search on log(eps) (256 points, shrinking to the best point's neighbours,
+ * 10 levels).  Binary64 arithmetic throughout; the table is rounded once to binary32.
+ * Errors: INVALID_ARG, SHAPE (table too large for the scoring kernels), TABLE (a sample out of range,
+ * fewer than 3 samples for a strategy, T0 <= 0 or F(b) <= 0 for some b <= b_cap: params and tbt are
+ * still written, NaN where undefined), HIP, NOMEM. */
+int maaso_profile_fit(int device, uint32_t n_tp, const uint32_t* offsets, const float* level,
+                      const float* thr, uint32_t b_cap, float eps_lo, float eps_hi, double* params,
+                      float* tbt);
+
 /* Validates and copies the tables to `device` (a HIP device ordinal) and creates a context.
  * Profiles are the placer's and distributor's input F(.) (Alg. 1 and Alg. 2, "Model profiles").
  * Errors: INVALID_ARG (NULL), SHAPE, TABLE, HIP, NOMEM.  On error *out_ctx is set to NULL. */

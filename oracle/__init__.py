@@ -14,6 +14,8 @@ from pathlib import Path
 
 import numpy as np
 
+from .profile_fit import profile_fit  # noqa: F401  (numpy oracle of the profiler's fit)
+
 _HERE = Path(__file__).resolve().parent
 SRC = _HERE / "maaso_oracle.cpp"
 LIB = _HERE / "libmaaso_oracle.so"

@@ -24,7 +24,7 @@ EXPORTS = (
     "maaso_ctx_set_launch_shape", "maaso_ctx_set_wait_limit", "maaso_ctx_kernel_timing",
     "maaso_ctx_kernel_elapsed", "maaso_ctx_sweep_evaluated", "maaso_score_assign",
     "maaso_placement_sweep", "maaso_placement_score", "maaso_split_by_slo",
-    "maaso_ins_deploy_select", "maaso_resource_partition",
+    "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
 )
 
 
@@ -105,6 +105,8 @@ def load_library() -> C.CDLL:
         lib.maaso_placement_score.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                               C.POINTER(Params), C.POINTER(ScoreWeights),
                                               C.POINTER(ScoreOut), C.c_void_p]
+        lib.maaso_profile_fit.argtypes = [C.c_int, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_uint32, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         lib.maaso_split_by_slo.argtypes = [C.c_void_p, C.POINTER(Requests), C.c_uint32] + [C.c_void_p] * 6
         lib.maaso_ins_deploy_select.argtypes = [C.c_void_p, C.POINTER(Placements), C.c_void_p,
                                                 C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p,
@@ -290,6 +292,25 @@ def maaso_placement_score(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_ba
     _check(load_library().maaso_placement_score(ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm),
                                                 C.byref(wts), C.byref(out), _stream_handle(stream)),
            "maaso_placement_score")
+
+
+def maaso_profile_fit(offsets, level, thr, b_cap: int, eps_lo: float = 2.0 ** -10,
+                      eps_hi: float = 2.0 ** 10, device: int = 0):
+    """Host numpy samples -> (params [T, 4] float64: T0, delta, eps, sse; tbt [T, b_cap + 1] float32).
+    Raises MaasoError; on MAASO_E_TABLE the partial outputs are attached to the exception."""
+    off = _host(offsets, np.uint32)
+    lv, th = _host(level, np.float32), _host(thr, np.float32)
+    n_tp = off.shape[0] - 1
+    params = np.full((n_tp, 4), np.nan, np.float64)
+    tbt = np.full((n_tp, b_cap + 1), np.nan, np.float32)
+    rc = load_library().maaso_profile_fit(int(device), n_tp, off.ctypes.data, lv.ctypes.data,
+                                          th.ctypes.data, int(b_cap), float(eps_lo), float(eps_hi),
+                                          params.ctypes.data, tbt.ctypes.data)
+    if rc != 0:
+        err = MaasoError(rc, "maaso_profile_fit")
+        err.partial = (params, tbt)
+        raise err
+    return params, tbt
 
 
 def maaso_split_by_slo(ctx: Context, *, n_req, prompt_len, out_len, slo_class, arrival_ticks=None,

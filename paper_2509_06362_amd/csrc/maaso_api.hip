@@ -14,6 +14,7 @@
 #include "assign_kernels.hpp"
 #include "sweep_kernels.hpp"
 #include "partition_kernels.hpp"
+#include "profile_fit_kernels.hpp"
 #include "sweep_window_kernels.hpp"
 #include "window_kernels.hpp"
 
@@ -537,6 +538,62 @@ int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maas
     if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
   }
   return MAASO_OK;
+}
+
+int maaso_profile_fit(int device, uint32_t n_tp, const uint32_t* offsets, const float* level,
+                      const float* thr, uint32_t b_cap, float eps_lo, float eps_hi, double* params,
+                      float* tbt) {
+  if (!offsets || !level || !thr || !params || !tbt) return MAASO_E_INVALID_ARG;
+  if (n_tp == 0 || b_cap == 0 || !(eps_lo > 0.0f) || !(eps_hi > eps_lo) || !std::isfinite(eps_hi))
+    return MAASO_E_INVALID_ARG;
+  if ((uint64_t)n_tp * ((uint64_t)b_cap + 1u) > MAASO_MAX_TABLE_CELLS) return MAASO_E_SHAPE;
+  for (uint32_t t = 0; t < n_tp; ++t)
+    if (offsets[t] > offsets[t + 1]) return MAASO_E_INVALID_ARG;
+  const size_t n_samples = offsets[n_tp];
+  for (size_t i = offsets[0]; i < n_samples; ++i)
+    if (!(level[i] >= 1.0f) || !std::isfinite(level[i]) || !(thr[i] > 0.0f) || !std::isfinite(thr[i]))
+      return MAASO_E_TABLE;
+  int n_dev = 0;
+  if (!hip_ok(hipGetDeviceCount(&n_dev)) || device < 0 || device >= n_dev) return MAASO_E_HIP;
+  DeviceGuard guard(device);
+  if (!guard.ok) return MAASO_E_HIP;
+  // one device block: offsets | level | thr | params | tbt | flag
+  const size_t cells = (size_t)n_tp * (b_cap + 1u);
+  const size_t b_off = 0, b_par = (((size_t)n_tp + 1u) * 4u + 7u) & ~(size_t)7u;
+  const size_t b_lvl = b_par + (size_t)n_tp * 4u * sizeof(double);
+  const size_t b_thr = b_lvl + (n_samples ? n_samples : 1u) * 4u;
+  const size_t b_tbt = b_thr + (n_samples ? n_samples : 1u) * 4u;
+  const size_t b_bad = b_tbt + cells * 4u;
+  unsigned char* dev = nullptr;
+  if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&dev), b_bad + 4u))) return MAASO_E_NOMEM;
+  int rc = MAASO_OK;
+  uint32_t bad = 0;
+  if (!hip_ok(hipMemcpy(dev + b_off, offsets, ((size_t)n_tp + 1u) * 4u, hipMemcpyHostToDevice)) ||
+      (n_samples && !hip_ok(hipMemcpy(dev + b_lvl, level, n_samples * 4u, hipMemcpyHostToDevice))) ||
+      (n_samples && !hip_ok(hipMemcpy(dev + b_thr, thr, n_samples * 4u, hipMemcpyHostToDevice))) ||
+      !hip_ok(hipMemset(dev + b_bad, 0, 4u)))
+    rc = MAASO_E_HIP;
+  if (rc == MAASO_OK) {
+    FitArgs a;
+    a.offsets = reinterpret_cast<const uint32_t*>(dev + b_off);
+    a.level = reinterpret_cast<const float*>(dev + b_lvl);
+    a.thr = reinterpret_cast<const float*>(dev + b_thr);
+    a.b_cap = b_cap;
+    a.log_eps_lo = std::log((double)eps_lo);
+    a.log_eps_hi = std::log((double)eps_hi);
+    a.params = reinterpret_cast<double*>(dev + b_par);
+    a.tbt = reinterpret_cast<float*>(dev + b_tbt);
+    a.bad = reinterpret_cast<uint32_t*>(dev + b_bad);
+    hipLaunchKernelGGL(profile_fit_kernel, dim3(n_tp), dim3(kFitGrid), 0, nullptr, a);
+    if (!hip_ok(hipGetLastError()) ||
+        !hip_ok(hipMemcpy(params, dev + b_par, (size_t)n_tp * 4u * sizeof(double), hipMemcpyDeviceToHost)) ||
+        !hip_ok(hipMemcpy(tbt, dev + b_tbt, cells * 4u, hipMemcpyDeviceToHost)) ||
+        !hip_ok(hipMemcpy(&bad, dev + b_bad, 4u, hipMemcpyDeviceToHost)))
+      rc = MAASO_E_HIP;
+  }
+  (void)hipFree(dev);
+  if (rc == MAASO_OK && bad) rc = MAASO_E_TABLE;
+  return rc;
 }
 
 int maaso_split_by_slo(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_classes,

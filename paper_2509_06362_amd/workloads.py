@@ -296,6 +296,25 @@ def partition_case(n_req: int = 65536, rate: float = 400.0, seed: int = 5,
         q_ticks=np.zeros((1, 1), dtype=np.uint64), s_bar=mean_out_len(out), window=256)
 
 
+def throughput_samples(seed: int, levels=(1, 2, 4, 8, 16, 32, 64, 128), repeats: int = 3,
+                       noise: float = 0.02, truth=None):
+    """Synthetic profiler measurements for the least-squares fit of the throughput-decay function
+    (Sec. IV-B): for every strategy, `repeats` noisy throughput readings at each workload level.
+    truth: [T, 3] rows (T0 tokens/s, delta, eps); default: four strategies of decreasing sensitivity.
+    Returns (offsets [T+1] uint32, level [N] float32, thr [N] float32, truth [T, 3] float64)."""
+    if truth is None:
+        truth = np.array([[80.0, 0.16, 0.5], [130.0, 0.14, 1.5], [210.0, 0.12, 3.0], [330.0, 0.09, 6.0]])
+    truth = np.asarray(truth, dtype=np.float64)
+    rng = rng_for(seed, 7)
+    lv = np.tile(np.repeat(np.asarray(levels, dtype=np.float64), repeats), (truth.shape[0], 1))
+    clean = truth[:, :1] * (1.0 - truth[:, 1:2] * np.log(truth[:, 2:3] + lv))
+    thr = clean * (1.0 + noise * rng.standard_normal(lv.shape))
+    n = lv.shape[1]
+    offsets = (np.arange(truth.shape[0] + 1) * n).astype(np.uint32)
+    return (offsets, np.ascontiguousarray(lv.reshape(-1), dtype=np.float32),
+            np.ascontiguousarray(thr.reshape(-1), dtype=np.float32), truth)
+
+
 # --------------------------------------------------------------------------------------------
 # the five workloads (+ one bandwidth-bound shape)
 # --------------------------------------------------------------------------------------------

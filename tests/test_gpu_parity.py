@@ -345,6 +345,58 @@ def test_score_config_shapes():
 
 
 # ------------------------------------------------------------------------------------------------
+# profiler: least-squares fit of the throughput-decay function (Sec. IV-B, Eq. 1)
+# ------------------------------------------------------------------------------------------------
+FIT_REL = 1e-6   # binary64 on both sides; the two log / exp implementations differ in the last place
+
+
+@pytest.mark.parametrize("seed,noise,repeats,b_cap,levels", [
+    (1, 0.0, 3, 128, (1, 2, 4, 8, 16, 32, 64, 128)), (2, 0.02, 3, 128, (1, 2, 4, 8, 16, 32, 64, 128)),
+    (3, 0.05, 5, 64, (1, 3, 9, 27, 64)), (4, 0.1, 2, 256, (1, 2, 4, 8, 16, 32, 64, 128, 256)),
+    (5, 0.002, 1, 16, (1, 2, 16)),
+])
+def test_profile_fit(seed, noise, repeats, b_cap, levels):
+    off, lv, th, truth = W.throughput_samples(seed, levels=levels, repeats=repeats, noise=noise)
+    ref_p, ref_t, ok = oracle.profile_fit(off, lv, th, b_cap)
+    assert ok
+    print(f"profile fit seed={seed} noise={noise} samples={len(lv)} b_cap={b_cap}", flush=True)
+    params, tbt = binding.maaso_profile_fit(off, lv, th, b_cap)
+    assert np.allclose(params[:, 0], ref_p[:, 0], rtol=FIT_REL)                    # T0
+    assert np.allclose(params[:, 1], ref_p[:, 1], rtol=1e-5)                       # delta
+    # eps is the flat direction of the residual: equal to grid resolution, not to rounding
+    assert np.allclose(params[:, 2], ref_p[:, 2], rtol=1e-4)
+    assert np.allclose(params[:, 3], ref_p[:, 3], rtol=1e-6, atol=1e-9)            # residual
+    assert np.allclose(tbt[:, 1:], ref_t[:, 1:], rtol=FIT_REL) and np.isnan(tbt[:, 0]).all()
+    # the fitted table drives the scoring path like any other
+    w = W.config0()
+    if b_cap >= w.b_cap:
+        fitted = W.replace(w, tbt=np.ascontiguousarray(tbt[:, :w.b_cap + 1]))
+        check_assign(fitted, window=0)
+
+
+def test_profile_fit_error_paths():
+    off, lv, th, _ = W.throughput_samples(7, levels=(1, 2, 4, 8), noise=0.0, truth=[[100.0, 0.3, 1.0]])
+    with pytest.raises(binding.MaasoError) as e:                # F(b) <= 0 inside the table
+        binding.maaso_profile_fit(off, lv, th, 64)
+    assert e.value.status == -3
+    params, tbt = e.value.partial
+    ref_p, ref_t, ok = oracle.profile_fit(off, lv, th, 64)
+    assert not ok and np.allclose(params[:, :3], ref_p[:, :3], rtol=1e-4)
+    with pytest.raises(binding.MaasoError) as e:                # two samples for three parameters
+        binding.maaso_profile_fit(np.array([0, 2], np.uint32), lv[:2], th[:2], 8)
+    assert e.value.status == -3
+    with pytest.raises(binding.MaasoError) as e:                # a level below 1
+        binding.maaso_profile_fit(off, lv * 0.5, th, 8)
+    assert e.value.status == -3
+    with pytest.raises(binding.MaasoError) as e:
+        binding.maaso_profile_fit(off, lv, th, 8, eps_lo=1.0, eps_hi=0.5)
+    assert e.value.status == -1
+    with pytest.raises(binding.MaasoError) as e:                # more cells than the kernels stage
+        binding.maaso_profile_fit(off, lv, th, 4096)
+    assert e.value.status == -2
+
+
+# ------------------------------------------------------------------------------------------------
 # placer's outer algorithms (Sec. IV-E): split by SLO, Alg. 1 bookkeeping, Alg. 2 partition scan
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n_req,n_slo,mask,arrivals", [
