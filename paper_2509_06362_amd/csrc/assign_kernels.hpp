@@ -260,17 +260,19 @@ __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const Ass
   // Admitted count: wavefront shuffle, block sum in LDS, one atomic per block into an accumulator
   // the library owns and keeps at zero between calls.  Every block then takes a ticket; the block
   // with the last ticket swaps the total out (leaving zero behind) and writes the output, so no
-  // clearing launch is needed.  All shared words are touched by returning atomics only, each issued
-  // after the previous one has returned, so no cache write-back fence is involved (a fence here would
-  // flush the per-request outputs of the whole kernel out of the L2).
+  // clearing launch is needed.  The shared words are touched by device-scope atomics only; a block's
+  // addition is waited for (vmcnt) before its ticket is drawn, and the last block's swap returns the
+  // total, so no cache write-back fence is involved (a fence here would flush the per-request outputs
+  // of the whole kernel out of the L2).
   for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);
   if ((threadIdx.x & 63u) == 0u) wave_sat[threadIdx.x >> 6] = sat;
   __syncthreads();
   if (threadIdx.x == 0 && a.n_satisfied) {
     unsigned long long t = 0;
     for (int w = 0; w < kAssignThreads / 64; ++w) t += wave_sat[w];
-    const unsigned long long before = atomicAdd(a.sat_acc, t);
-    const uint32_t ticket = atomicAdd(a.sat_done, 1u + (uint32_t)(before & 0ull));
+    atomicAdd(a.sat_acc, t);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the addition has completed before the ticket is drawn
+    const uint32_t ticket = atomicAdd(a.sat_done, 1u);
     if (ticket == gridDim.x - 1u) {
       *a.n_satisfied = atomicExch(a.sat_acc, 0ull);
       atomicExch(a.sat_done, 0u);

@@ -70,6 +70,12 @@ __device__ __forceinline__ float min_no_nan(float x, float y) {
   return r;
 }
 
+__device__ __forceinline__ float max_no_nan(float x, float y) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+  return r;
+}
+
 // ---------------------------------------------------------------------------------------------
 struct PrepArgs {
   // bucket job

@@ -158,9 +158,14 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
           const float s3 = (De[v] - e2e) * iDe[v];
           const float slack = fminf(fminf(s1, s2), s3);
           const float val = (kSQ && slack >= 0.0f) ? rankv[j] : slack;
-          if (val > best[v]) { best[v] = val; idx[v] = (int32_t)j; bpre[v] = pre; }
+          // one compare, one select, one max: the winner's prefill time is recomputed after the loop
+          idx[v] = (val > best[v]) ? (int32_t)j : idx[v];
+          best[v] = max_no_nan(best[v], val);
         }
       }
+#pragma unroll
+      for (int v = 0; v < V; ++v)
+        if (idx[v] >= 0) { const float4 r = recs[idx[v]]; bpre[v] = fmaf(r.y, L[v], r.x); }
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         const bool adm = live[v] && best[v] >= 0.0f;  // admitted requests load their instance
