@@ -41,8 +41,7 @@ struct AssignArgs {
   float* e2e;
   unsigned long long* n_satisfied;
   uint32_t* status;
-  unsigned long long* sat_acc;  // [1] admitted-count accumulator of the static kernel; zero between calls
-  uint32_t* sat_done;           // [1] blocks that have delivered their count; zero between calls
+  unsigned long long* sat_acc;  // [1] admitted count and delivered-blocks counter of the static kernel; zero between calls
 };
 
 __global__ void assign_init_kernel(unsigned long long* n_satisfied) {
@@ -100,6 +99,19 @@ constexpr int kS2Stride = 257;  // odd: the per-class rows of the margin table f
 // registers (`rreg`); the margin is recomputed from the class row, so the loop touches no LDS - the
 // form used when there are so few instances that the request stream from HBM is the bound.
 //
+// Four consecutive requests as they come from memory: two 16-byte loads and one 4-byte load.
+struct RequestVec {
+  uint4 pl, ol;
+  uint32_t kk;
+};
+__device__ __forceinline__ RequestVec load_request_vec(const AssignArgs& a, uint64_t r0) {
+  RequestVec v;
+  v.pl = *reinterpret_cast<const uint4*>(a.prompt_len + r0);
+  v.ol = *reinterpret_cast<const uint4*>(a.out_len + r0);
+  v.kk = *reinterpret_cast<const uint32_t*>(a.slo_class + r0);
+  return v;
+}
+
 // kSQ: shortest-queue rule; `rankv` (LDS) or `rrank` (registers, with NREG) hold the instances'
 // queue_rank_value, and the slack written out is the chosen instance's own.
 template <bool kLat, int V, int NREG, bool kSQ>
@@ -109,16 +121,17 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
                                                     const float* __restrict__ s2tab,
                                                     const float4* rreg,
                                                     const float* __restrict__ rankv,
-                                                    const float* rrank) {
+                                                    const float* rrank,
+                                                    const RequestVec* pre = nullptr) {
   float L[V], S[V], best[V], De[V], iDe[V], Dt[V], iDt[V], Db[V], iDb[V];
   float b_slack[V];
   float b_ttft[V], b_tbt[V], b_e2e[V];
   uint32_t k[V];
   int32_t idx[V];
   if (V == 4) {
-    const uint4 pl = *reinterpret_cast<const uint4*>(a.prompt_len + r0);
-    const uint4 ol = *reinterpret_cast<const uint4*>(a.out_len + r0);
-    const uint32_t kk = *reinterpret_cast<const uint32_t*>(a.slo_class + r0);
+    const RequestVec rv = pre ? *pre : load_request_vec(a, r0);
+    const uint4 pl = rv.pl, ol = rv.ol;
+    const uint32_t kk = rv.kk;
     const uint32_t p4[4] = {pl.x, pl.y, pl.z, pl.w}, o4[4] = {ol.x, ol.y, ol.z, ol.w};
 #pragma unroll
     for (int v = 0; v < V; ++v) {
@@ -224,6 +237,13 @@ __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const Ass
   __shared__ uint32_t wave_sat[kAssignThreads / 64];
   __shared__ int32_t occ_s[kSQ ? 256 : 1];
   __shared__ float rankv[kSQ ? 256 : 1];
+  // the block's first requests are asked for before anything else: their latency then overlaps the
+  // staging of the instances below
+  const uint64_t n_vec = (uint64_t)a.n_req / V;  // groups of V requests
+  const uint64_t g0 = (uint64_t)blockIdx.x * kAssignThreads + threadIdx.x;
+  const uint64_t stride = (uint64_t)gridDim.x * kAssignThreads;
+  RequestVec cur{}, nxt{};
+  if (V == 4 && g0 < n_vec) cur = load_request_vec(a, g0 * V);
   const uint32_t n = min(min(a.n_inst[0], a.i_pad), NREG ? (uint32_t)NREG : 256u);
   stage_placement(a, n, recs, nullptr);
   if (kSQ)
@@ -249,33 +269,40 @@ __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const Ass
   }
 
   uint32_t sat = 0;
-  const uint64_t n_vec = (uint64_t)a.n_req / V;  // groups of V requests
-  for (uint64_t g = (uint64_t)blockIdx.x * kAssignThreads + threadIdx.x; g < n_vec;
-       g += (uint64_t)gridDim.x * kAssignThreads)
-    sat += assign_requests<kLat, V, NREG, kSQ>(a, g * V, n, recs, cls, s2tab, rreg, rankv, rrank);
+  if (V == 4) {
+    // the next group's requests are loaded before the current group is scored, so that a thread
+    // always has loads in flight (the loop is otherwise load -> wait -> compute -> store)
+    for (uint64_t g = g0; g < n_vec; g += stride) {
+      if (g + stride < n_vec) nxt = load_request_vec(a, (g + stride) * V);
+      sat += assign_requests<kLat, V, NREG, kSQ>(a, g * V, n, recs, cls, s2tab, rreg, rankv, rrank, &cur);
+      cur = nxt;
+    }
+  } else {
+    for (uint64_t g = g0; g < n_vec; g += stride)
+      sat += assign_requests<kLat, V, NREG, kSQ>(a, g * V, n, recs, cls, s2tab, rreg, rankv, rrank);
+  }
   if (V > 1 && blockIdx.x == 0) {  // the ragged tail, one request per thread
     const uint64_t r = n_vec * V + threadIdx.x;
     if (r < a.n_req) sat += assign_requests<kLat, 1, NREG, kSQ>(a, r, n, recs, cls, s2tab, rreg, rankv, rrank);
   }
-  // Admitted count: wavefront shuffle, block sum in LDS, one atomic per block into an accumulator
-  // the library owns and keeps at zero between calls.  Every block then takes a ticket; the block
-  // with the last ticket swaps the total out (leaving zero behind) and writes the output, so no
-  // clearing launch is needed.  The shared words are touched by device-scope atomics only; a block's
-  // addition is waited for (vmcnt) before its ticket is drawn, and the last block's swap returns the
-  // total, so no cache write-back fence is involved (a fence here would flush the per-request outputs
-  // of the whole kernel out of the L2).
+  // Admitted count: wavefront shuffle, block sum in LDS, then ONE returning device-scope atomic per
+  // block on a 64-bit word the library owns and keeps at zero between calls: the block's count goes
+  // into the low 40 bits and a 1 into the bits above, so the returned value tells the block how many
+  // blocks delivered before it.  The last one knows the total, writes the output and zeroes the word:
+  // no clearing launch, no fence (a write-back fence here would flush the kernel's per-request
+  // outputs out of the L2), and a single same-address atomic per block (they serialise device-wide:
+  // thousands of them at the kernel's end are measurable).
   for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);
   if ((threadIdx.x & 63u) == 0u) wave_sat[threadIdx.x >> 6] = sat;
   __syncthreads();
   if (threadIdx.x == 0 && a.n_satisfied) {
     unsigned long long t = 0;
     for (int w = 0; w < kAssignThreads / 64; ++w) t += wave_sat[w];
-    atomicAdd(a.sat_acc, t);
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the addition has completed before the ticket is drawn
-    const uint32_t ticket = atomicAdd(a.sat_done, 1u);
-    if (ticket == gridDim.x - 1u) {
-      *a.n_satisfied = atomicExch(a.sat_acc, 0ull);
-      atomicExch(a.sat_done, 0u);
+    // one word carries both: the admitted count in its low 40 bits, the blocks delivered above them
+    const unsigned long long before = atomicAdd(a.sat_acc, (1ull << 40) | t);
+    if ((before >> 40) == (unsigned long long)gridDim.x - 1ull) {
+      *a.n_satisfied = (before & ((1ull << 40) - 1ull)) + t;
+      atomicExch(a.sat_acc, 0ull);
     }
   }
 }

@@ -7,7 +7,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -158,7 +157,6 @@ void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placement
   a.e2e = out->e2e;
   a.n_satisfied = reinterpret_cast<unsigned long long*>(out->n_satisfied);
   a.status = ctx->status;
-  a.sat_done = ctx->status + 34;
   a.sat_acc = reinterpret_cast<unsigned long long*>(ctx->status + 36);
 }
 
@@ -715,10 +713,12 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
                      al(out->tbt, 15) && al(out->e2e, 15);
     const uint32_t per_block = kAssignThreads * (vec ? 4u : 1u);
     uint32_t blocks = (uint32_t)(((uint64_t)R + per_block - 1) / per_block);
-    const uint32_t cap = (uint32_t)ctx->n_cu * 8u;
-    if (blocks > cap) blocks = cap;
     // few instance slots: records live in registers and the loop needs no LDS (HBM-bound shape)
     const bool few = pl->i_pad <= 8u;
+    // persistent blocks; measured on the HBM-bound shape: 3 per compute unit (all resident, 213 us)
+    // beat 2 (228), 4 (219), 5 (254) and 8 (222)
+    const uint32_t cap = (uint32_t)ctx->n_cu * (few ? 3u : 8u);
+    if (blocks > cap) blocks = cap;
     TimedRegion timed(ctx, s);
 #define MAASO_LAUNCH_STATIC(LAT, V, NREG)                                                          \
   do {                                                                                             \
