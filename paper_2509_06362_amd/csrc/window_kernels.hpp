@@ -66,11 +66,15 @@ __device__ __forceinline__ void argmax_lanes(float& s, int32_t& i) {
 
 // Device-wide barrier on a monotone counter.  Returns false if the wait gave up or another block
 // did; the caller must then leave the kernel.  Must be reached by all threads of the block.
+// What crosses the barrier are device-scope atomics only (the per-window sums): every thread waits for
+// its own to complete (vmcnt) before the block gathers, the arrival is an atomic issued after that, and
+// the sums are read back with device-scope atomic loads - so no cache write-back or invalidate is
+// needed, and none is issued (a full fence here writes the L2 back at every window).
 __device__ __forceinline__ bool grid_barrier(WindowWs* ws, unsigned long long target,
                                              uint32_t spin_limit, uint32_t* status, int* lds_flag) {
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this thread's atomics on the sums have completed
   __syncthreads();
   if (threadIdx.x == 0) {
-    __threadfence();
     atomicAdd(&ws->bar, 1ull);
     bool ok = true;
     uint32_t spins = 0;
@@ -85,7 +89,6 @@ __device__ __forceinline__ bool grid_barrier(WindowWs* ws, unsigned long long ta
       ++spins;
       __builtin_amdgcn_s_sleep(4);
     }
-    __threadfence();
     *lds_flag = ok ? 1 : 0;
   }
   __syncthreads();
