@@ -824,6 +824,47 @@ def test_assign_windowed_config2_full():
 # argument and precondition handling
 # ------------------------------------------------------------------------------------------------
 
+def largest_tables(n_tp, b_cap, seed):
+    """A profile that fills the table limit (n_tp * (b_cap + 1) = 2048 cells), eight instances per
+    candidate drawn over all rows and batch sizes, Poisson arrivals."""
+    rng = np.random.default_rng(seed)
+    t = np.arange(n_tp, dtype=np.float64)[:, None]
+    b = np.arange(b_cap + 1, dtype=np.float64)[None, :]
+    a = np.broadcast_to(0.02 / (1 + t) ** 0.3, (n_tp, b_cap + 1)) * rng.uniform(0.9, 1.1, (n_tp, b_cap + 1))
+    p = np.broadcast_to(4e-5 / (1 + t) ** 0.3, (n_tp, b_cap + 1)) * rng.uniform(0.9, 1.1, (n_tp, b_cap + 1))
+    tb = 0.012 / (1 + t) ** 0.2 * (1 + 0.002 * b) * rng.uniform(0.9, 1.1, (n_tp, b_cap + 1))
+    tabs = []
+    for m in (a, p, tb):
+        m32 = m.astype(np.float32)
+        m32[:, 0] = np.nan
+        tabs.append(np.ascontiguousarray(m32))
+    n_cand, i_pad, n_req = 12, 8, 3000
+    w = W.random_small(seed, n_cand, i_pad, n_req, n_slo=3)
+    max_batch = rng.integers(1, b_cap + 1, size=(n_cand, i_pad)).astype(np.uint16)
+    return W.replace(
+        w, name=f"largest_tables_{n_tp}x{b_cap}", tp_degree=np.ones(n_tp, np.uint32), b_cap=b_cap,
+        prefill_a=tabs[0], prefill_p=tabs[1], tbt=tabs[2],
+        tp_idx=rng.integers(0, n_tp, size=(n_cand, i_pad)).astype(np.uint16).astype(np.uint8)
+        if n_tp <= 256 else (rng.integers(0, 256, size=(n_cand, i_pad))).astype(np.uint8),
+        max_batch=max_batch, occ=(rng.random((n_cand, i_pad)) * max_batch * 1.5).astype(np.int32),
+        arrival_ticks=W.poisson_arrivals(W.rng_for(seed, 3), 500.0, n_req))
+
+
+@pytest.mark.parametrize("n_tp,b_cap", [(1, 2047), (1024, 1), (8, 255)])
+def test_tables_at_the_size_limit(n_tp, b_cap):
+    w = largest_tables(n_tp, b_cap, seed=300 + n_tp)
+    check_sweep(w, threshold=True)
+    check_sweep_windowed(w, 256)
+    check_score(w, 500, weights=SCORE_WEIGHTS[:1])
+    one = W.replace(w.with_candidates(3, 4), n_inst=np.array([8], np.uint32))
+    check_assign(one, window=0)
+    check_assign(one, window=200)
+    with pytest.raises(binding.MaasoError) as e:        # one more cell is refused at load
+        binding.maaso_profile_tables_load(1, 2048, np.ones((1, 2049), np.float32), np.ones((1, 2049), np.float32),
+                                          np.ones((1, 2049), np.float32), w.d_ttft, w.d_tbt, None, 0)
+    assert e.value.status == -2
+
+
 def test_host_side_argument_errors():
     w = W.random_small(51, 2, 8, 100)
     dw = binding.DeviceWorkload(w)
