@@ -577,6 +577,38 @@ def test_resource_partition_end_to_end(n_req, rate, n_gpus, window, share):
         dw.close()
 
 
+def test_resource_partition_at_bench_size():
+    """The workload `bench.py --workload alg2` times (131,072 requests, 64 GPUs, 24 configurations ->
+    720 deployments), whole pipeline against the sequential oracle."""
+    import bench
+    n_gpus, wts = bench.ALG2_GPUS, bench.ALG2_SCORE_WEIGHTS
+    w = W.partition_case(n_req=131072, rate=400.0)
+    tp, b = W.all_configs()
+    cw, offs = W.growth_chains(w, tp, b, n_gpus)
+    window = int(w.window)
+    r_t, r_l = oracle.split_by_slo(w, 0b1)
+    print("oracle: sequential Alg. 1 on R_t, R_l, R ...", flush=True)
+    ref = {tag: oracle.ins_deploy(ws, n_gpus, tp, b, *wts, window=window)
+           for tag, ws in (("t", r_t), ("l", r_l), ("h", w))}
+    part = oracle.resource_partition(n_gpus, ref["t"]["phi_star"], ref["l"]["phi_star"],
+                                     ref["h"]["phi_star"], r_l.n_req, w.n_req)
+    dw = binding.DeviceWorkload(cw)
+    try:
+        print(f"alg2 full size C={cw.n_cand} I={cw.i_pad} R={cw.n_req}", flush=True)
+        got = dw.resource_partition(offs, 0b1, n_gpus, *wts, window=window)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        for tag in ("t", "l", "h"):
+            assert np.array_equal(got[f"phi_{tag}_star"].cpu().numpy(), ref[tag]["phi_star"]), tag
+            cfg, cnt = star_as_config(got[f"cand_{tag}_star"].cpu().numpy(), offs)
+            assert np.array_equal(cfg, ref[tag]["cfg_star"]) and np.array_equal(cnt, ref[tag]["cnt_star"])
+        p = got["partition"].cpu().numpy()
+        assert p[:4].tolist() == [part["g_t"], part["g_l"], part["heterogeneous"], part["k_h"]]
+        assert float(got["phi_opt"].item()) == part["phi_opt"]
+    finally:
+        dw.close()
+
+
 def test_outer_algorithm_error_paths():
     w, cw, offs, tp, b = chain_case(200, 100.0, 8, seed=7)
     dw = binding.DeviceWorkload(cw)
