@@ -133,8 +133,8 @@ int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane,
 int maaso_ctx_set_wait_limit(maaso_ctx* ctx, uint32_t polls);
 
 /* Instrumentation.  With timing enabled, each compute call records a pair of HIP events on its
- * stream directly around its dominant kernel (the sweep kernel of maaso_placement_sweep, the scoring
- * kernel of maaso_score_assign), for up to 256 calls.  maaso_ctx_kernel_elapsed waits for the
+ * stream directly around its dominant kernel (the sweep kernel of maaso_placement_sweep and of
+ * maaso_placement_score, the scoring kernel of maaso_score_assign), for up to 256 calls.  maaso_ctx_kernel_elapsed waits for the
  * recorded events, returns the sum of the kernel durations in milliseconds and their number, and
  * starts a new series.  Enabling allocates the events once; no other call is affected.
  * Errors: INVALID_ARG, HIP. */
@@ -208,7 +208,9 @@ typedef struct {
  *   prefill = p_j*L + a_j (fused);  ttft = wait_j + prefill;  e2e = S*tbt_j + ttft (fused);
  *   margins (D - latency) / D against the TTFT, TBT and end-to-end deadlines;  slack = their min
  * (L_r = L_q + L_d against the deadline, Eq. 2 and Eq. 3).  The request goes to the instance of
- * largest slack and is admitted iff that slack is >= 0 (equality counts, Eq. 3), else blocked.
+ * largest slack (prm->policy == 0; with policy 1 to the capable instance with the shortest queue, see
+ * maaso_params) and is admitted iff that instance's slack is >= 0 (equality counts, Eq. 3), else
+ * blocked.
  * With window > 0 the state (occ, q_ticks) is advanced after every window from the admitted
  * requests: occupancy and queued prefill ticks are added, the queue drains by the arrival time that
  * passed, and min(W,B) * elapsed / (s_bar * tbt_j) requests complete; blocked requests add no load.
