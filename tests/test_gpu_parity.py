@@ -856,6 +856,35 @@ def test_assign_windowed_config2_full():
 # argument and precondition handling
 # ------------------------------------------------------------------------------------------------
 
+# ------------------------------------------------------------------------------------------------
+# seeded random combinations of shape, window, rule, estimate mode and penalty on every entry point
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(40))
+def test_random_combinations(seed):
+    rng = np.random.default_rng(9000 + seed)
+    n_cand = int(rng.integers(1, 25))
+    i_pad = int(rng.choice([1, 2, 3, 5, 8, 9, 16, 31, 64, 100, 256]))
+    n_req = int(rng.choice([0, 1, 63, 64, 65, 255, 257, 1000, 1024, 2500, 4099]))
+    n_slo = int(rng.choice([1, 2, 3, 7, 16]))
+    window = int(rng.choice([0, 1, 17, 64, 256, 300, 1024, 5000]))
+    w = W.random_small(9000 + seed, n_cand, i_pad, max(n_req, 1), n_slo=n_slo,
+                       pen_kappa=float(rng.choice([0.0, 0.25, 1.5]))).with_requests(0, n_req)
+    if rng.random() < 0.5:
+        w = W.stressed(w, seed=seed, deadline_scale=float(rng.choice([1.0, 0.25, 0.05])))
+    w = W.replace(w, policy=int(rng.integers(0, 2)), tbt_mode=int(rng.integers(0, 2)),
+                  arrival_ticks=W.poisson_arrivals(W.rng_for(seed, 3), float(rng.choice([50.0, 800.0, 20000.0])),
+                                                   n_req))
+    print(f"combo seed={seed} C={n_cand} I={i_pad} R={n_req} K={n_slo} window={window} policy={w.policy} "
+          f"tbt_mode={w.tbt_mode} kappa={float(w.pen_kappa)}", flush=True)
+    check_sweep(w)
+    if window and n_req:
+        check_sweep_windowed(w, window)
+    check_score(w, window if n_req else 0, weights=SCORE_WEIGHTS[:1])
+    c = int(rng.integers(0, n_cand))
+    one = w.with_candidates(c, c + 1)
+    check_assign(one, window=window, window_blocks=int(rng.choice([0, 1, 3, 16, 64])))
+
+
 def largest_tables(n_tp, b_cap, seed):
     """A profile that fills the table limit (n_tp * (b_cap + 1) = 2048 cells), eight instances per
     candidate drawn over all rows and batch sizes, Poisson arrivals."""
