@@ -388,19 +388,41 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(const uint32_t* __
   __shared__ unsigned long long best[16];
   __shared__ unsigned long long esum[16];
   if (threadIdx.x < kMaxSlo) cls_count[threadIdx.x] = 0u;
+  // both loops fetch eight elements per thread at a time: the kernel is one block, so its duration is
+  // the number of dependent trips to memory
+  constexpr uint32_t kBatch = 8;
   {
     unsigned long long e = 0ull;
-    for (uint32_t i = threadIdx.x; i < n_parts; i += blockDim.x) e += eval_parts[i];
+    for (uint32_t i0 = threadIdx.x; i0 < n_parts; i0 += kBatch * blockDim.x) {
+      unsigned long long v[kBatch];
+#pragma unroll
+      for (uint32_t u = 0; u < kBatch; ++u) {
+        const uint32_t i = i0 + u * blockDim.x;
+        v[u] = i < n_parts ? eval_parts[i] : 0ull;
+      }
+#pragma unroll
+      for (uint32_t u = 0; u < kBatch; ++u) e += v[u];
+    }
     for (int d = 32; d >= 1; d >>= 1) e += __shfl_xor(e, d);
     if ((threadIdx.x & 63u) == 0u) esum[threadIdx.x >> 6] = e;
   }
   const float fr = (float)n_req;
   unsigned long long key = 0ull;  // (count << 32) | ~index: max key = max count, then min index
-  for (uint32_t c = threadIdx.x; c < n_cand; c += blockDim.x) {
-    const uint32_t n = sat_count[c];
-    if (sat_ratio) sat_ratio[c] = n_req ? (float)n / fr : 0.0f;
-    const unsigned long long kc = ((unsigned long long)n << 32) | (unsigned long long)(~c);
-    key = kc > key ? kc : key;
+  for (uint32_t c0 = threadIdx.x; c0 < n_cand; c0 += kBatch * blockDim.x) {
+    uint32_t n[kBatch];
+#pragma unroll
+    for (uint32_t u = 0; u < kBatch; ++u) {
+      const uint32_t c = c0 + u * blockDim.x;
+      n[u] = c < n_cand ? sat_count[c] : 0u;
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kBatch; ++u) {
+      const uint32_t c = c0 + u * blockDim.x;
+      if (c >= n_cand) continue;
+      if (sat_ratio) sat_ratio[c] = n_req ? (float)n[u] / fr : 0.0f;
+      const unsigned long long kc = ((unsigned long long)n[u] << 32) | (unsigned long long)(~c);
+      key = kc > key ? kc : key;
+    }
   }
   for (int d = 32; d >= 1; d >>= 1) {
     const unsigned long long o = __shfl_xor(key, d);

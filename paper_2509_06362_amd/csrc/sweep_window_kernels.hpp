@@ -146,22 +146,41 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
         iDe[v] = 1.0f / De[v];
         best[v] = -INFINITY; idx[v] = -1; bpre[v] = 0.0f;
       }
-      for (uint32_t j = 0; j < n; ++j) {
-        const float4 r = recs[j];  // a, p, tbt, wait
+      // one (request v, instance j) triple; r = {a, p, tbt, wait}, s2 = the between-token margin
+      auto score_one = [&](const float4 r, float s2, uint32_t j, int v) {
+        const float pre = fmaf(r.y, L[v], r.x);
+        const float ttft = r.w + pre;
+        const float e2e = fmaf(S[v], r.z, ttft);
+        const float s1 = (Dt[v] - ttft) * iDt[v];
+        const float s3 = (De[v] - e2e) * iDe[v];
+        const float slack = fminf(fminf(s1, s2), s3);
+        const float val = (kSQ && slack >= 0.0f) ? rankv[j] : slack;
+        // one compare, one select, one max: the winner's prefill time is recomputed after the loop
+        idx[v] = (val > best[v]) ? (int32_t)j : idx[v];
+        best[v] = max_no_nan(best[v], val);
+      };
+      // With few requests per lane a wavefront has little to overlap an LDS read with (short windows
+      // leave a SIMD two or three wavefronts), so U records are fetched per trip before any is used.
+      constexpr uint32_t U = (V == 1) ? 4u : (V == 2 ? 2u : 1u);
+      uint32_t j = 0;
+      for (; j + U <= n; j += U) {
+        float4 r[U];
+        float s2[U][V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-          const float pre = fmaf(r.y, L[v], r.x);
-          const float ttft = r.w + pre;
-          const float e2e = fmaf(S[v], r.z, ttft);
-          const float s1 = (Dt[v] - ttft) * iDt[v];
-          const float s2 = s2tab[k[v] * kS2Stride + j];
-          const float s3 = (De[v] - e2e) * iDe[v];
-          const float slack = fminf(fminf(s1, s2), s3);
-          const float val = (kSQ && slack >= 0.0f) ? rankv[j] : slack;
-          // one compare, one select, one max: the winner's prefill time is recomputed after the loop
-          idx[v] = (val > best[v]) ? (int32_t)j : idx[v];
-          best[v] = max_no_nan(best[v], val);
+        for (uint32_t u = 0; u < U; ++u) {
+          r[u] = recs[j + u];
+#pragma unroll
+          for (int v = 0; v < V; ++v) s2[u][v] = s2tab[k[v] * kS2Stride + j + u];
         }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u)
+#pragma unroll
+          for (int v = 0; v < V; ++v) score_one(r[u], s2[u][v], j + u, v);
+      }
+      for (; j < n; ++j) {
+        const float4 r = recs[j];
+#pragma unroll
+        for (int v = 0; v < V; ++v) score_one(r, s2tab[k[v] * kS2Stride + j], j, v);
       }
 #pragma unroll
       for (int v = 0; v < V; ++v)
