@@ -117,14 +117,15 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
       n_blk[tid] = 0u;
       t_blk[tid] = 0ull;
       if (kSQ) occ_s[tid] = occ;
+      // the instance's between-token margins against every class, while its tbt is at hand
+      const float tbt_j = recs[tid].z;
+      for (uint32_t k = 0; k < a.n_slo; ++k) s2tab[k * kS2Stride + tid] = (cls[k].Db - tbt_j) * cls[k].iDb;
     }
     __syncthreads();
-    if (kSQ && tid < n) rankv[tid] = queue_rank_value(occ_s, n, tid);
-    for (uint32_t i = tid; i < a.n_slo * n; i += kAssignThreads) {
-      const uint32_t k = i / n, j = i - k * n;
-      s2tab[k * kS2Stride + j] = (a.d_tbt[k] - recs[j].z) * a.i_tbt[k];
+    if (kSQ) {
+      if (tid < n) rankv[tid] = queue_rank_value(occ_s, n, tid);
+      __syncthreads();
     }
-    __syncthreads();
 
     for (uint64_t b0 = s0; b0 < e0; b0 += (uint64_t)V * kAssignThreads) {
       float L[V], S[V], Dt[V], iDt[V], De[V], iDe[V], best[V], bpre[V];
@@ -222,10 +223,12 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
         occ -= done;
       }
     }
-    // the next stage rewrites recs / n_blk / t_blk: every thread must have finished reading them
-    __syncthreads();
+    // No barrier before the next stage: it rewrites recs and the margin table, which every thread
+    // finished reading before the barrier above, and n_blk / t_blk entries that only their own thread
+    // reads; the next window's atomics on them come after the stage's barrier.
   }
 
+  __syncthreads();  // the last update has read n_blk / t_blk, which are reused below
   for (int d = 32; d >= 1; d >>= 1) sat += __shfl_xor(sat, d);
   if ((tid & 63u) == 0u) wave_sat[tid >> 6] = sat;
   if (kScore) {
