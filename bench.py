@@ -55,8 +55,8 @@ KERNEL_SOURCES = {
     "assign_static_kernel": ("device_model.hpp", "sweep_kernels.hpp", "assign_kernels.hpp"),
 }
 TRAFFIC = {
-    "cfg1_placer_sweep": ("sweep_kernel", 6.710e6, "2df455b4d44e6bfc"),
-    "streaming_i4": ("assign_static_kernel", 1.1410e9, "7cb04cd9ab312e16"),
+    "cfg1_placer_sweep": ("sweep_kernel", 6.710e6, "8098146ad3d29803"),
+    "streaming_i4": ("assign_static_kernel", 1.1410e9, "f80150fc6acd3f3f"),
 }
 
 
