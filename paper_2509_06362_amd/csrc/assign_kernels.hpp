@@ -168,11 +168,19 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
       const float s3 = (De[v] - e2e) * iDe[v];
       const float slack = fminf(fminf(s1, s2), s3);
       const float val = (kSQ && slack >= 0.0f) ? rank : slack;
-      if (val > best[v]) {
-        best[v] = val;
-        idx[v] = (int32_t)j;
-        if (kSQ) b_slack[v] = slack;
-        if (kLat) { b_ttft[v] = ttft; b_tbt[v] = r.z; b_e2e[v] = e2e; }
+      if (NREG || (!kLat && !kSQ)) {  // nothing but (best, idx) to carry, or records in registers
+        if (val > best[v]) {
+          best[v] = val;
+          idx[v] = (int32_t)j;
+          if (kSQ) b_slack[v] = slack;
+          if (kLat) { b_ttft[v] = ttft; b_tbt[v] = r.z; b_e2e[v] = e2e; }
+        }
+      } else {
+        // one compare, one select, one max per triple instead of a select per reported quantity: what
+        // else is reported about the winner is worked out again after the loop from its record (the
+        // same operations, so the same bits)
+        idx[v] = (val > best[v]) ? (int32_t)j : idx[v];
+        best[v] = max_no_nan(best[v], val);
       }
     }
   };
@@ -182,6 +190,23 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
       if ((uint32_t)j < n) score(rreg[j], (uint32_t)j, kSQ ? rrank[j] : 0.0f);
   } else {
     for (uint32_t j = 0; j < n; ++j) score(recs[j], j, kSQ ? rankv[j] : 0.0f);
+    if (kLat || kSQ) {
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        if (idx[v] < 0) continue;
+        const float4 r = recs[idx[v]];
+        const float pre = fmaf(r.y, L[v], r.x);
+        const float ttft = r.w + pre;
+        const float e2e = fmaf(S[v], r.z, ttft);
+        if (kLat) { b_ttft[v] = ttft; b_tbt[v] = r.z; b_e2e[v] = e2e; }
+        if (kSQ) {
+          const float s1 = (Dt[v] - ttft) * iDt[v];
+          const float s2 = s2tab[k[v] * kS2Stride + idx[v]];
+          const float s3 = (De[v] - e2e) * iDe[v];
+          b_slack[v] = fminf(fminf(s1, s2), s3);
+        }
+      }
+    }
   }
   uint32_t sat = 0;
 #pragma unroll
