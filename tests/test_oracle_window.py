@@ -84,3 +84,25 @@ def test_window_state_accounting():
     # the last window is loaded but not drained
     last = np.arange(w.n_req) >= (w.n_req - 512)
     assert (r["occ"] >= np.bincount(r["chosen"][adm & last], minlength=64)).all()
+
+
+def test_hand_worked_drain_rate():
+    """Between windows min(W, B) requests decode side by side, each needing E[L_d] = s_bar * tbt, so
+    floor(min(W, B) * elapsed / E[L_d]) of them complete (never more than are there).
+    One instance, B = 4, E[L_d] = 64 * 2^-6 = 1 s; it starts with W = 2 (below the cap) or W = 6
+    (above it); one request per window, 1.75 s between arrivals, nothing queued.
+      W = 2: window 0 admits -> W = 3; 1.75 s pass: floor(3 * 1.75) = 5 -> all 3 leave, W = 0.
+             With B in place of min(W, B) it would also be 0, so a second start is taken:
+      W = 2, 0.5 s between arrivals: W = 3; floor(3 * 0.5) = 1 leaves -> W = 2   (B = 4 would give 2 -> W = 1)
+             next window admits -> W = 3, last window: nothing drains.          (final W = 3, not 2)
+      W = 6: window 0 admits -> W = 7; floor(min(7, 4) * 0.5) = 2 leave -> W = 5; next admits -> W = 6."""
+    g = read_golden()
+    base = worked_example_workload(g)
+    half = 1 << 19                                                     # 0.5 s in ticks
+    for occ0, gap, want in ((2, half, 3), (6, half, 6), (2, 7 * (1 << 18), 1)):
+        w = W.replace(base.with_requests(0, 2), window=1, occ=np.array([[occ0]], np.int32),
+                      arrival_ticks=np.array([0, gap], np.uint32),
+                      d_ttft=np.array([64.0], np.float32))             # wide deadline: both admitted
+        r = oracle.score_assign(w)
+        assert r["n_satisfied"] == 2
+        assert r["occ"].tolist() == [want], (occ0, gap)
