@@ -293,8 +293,8 @@ def main() -> int:
             dw.sweep(out=sweep_out, stream=stream, window=sweep_window)
 
     if kind == "sweep":
-        # the distributor runs on the winning deployment; its index is fixed by a first sweep so
-        # that the timed steps need no device-to-host copy
+        # the distributor runs on the winning deployment; a first sweep tells the host which one that
+        # is (for the triple count only)
         run_sweep()
         torch.cuda.synchronize()
         best = int(sweep_out[2].item())
@@ -302,8 +302,9 @@ def main() -> int:
         triples_assign = w.n_req * int(w.n_inst[best])
 
         def step():
+            # the distributor reads the sweep's best candidate on the device: no host round trip
             run_sweep()
-            dw.assign(cand=best, window=0, latencies=False, out=assign_out, stream=stream)
+            dw.assign_selected(sweep_out[2], window=0, latencies=False, out=assign_out, stream=stream)
     else:
         best = 0
         triples_sweep = 0

@@ -219,6 +219,16 @@ typedef struct {
 int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                        const maaso_params* prm, const maaso_assign_out* out, void* hip_stream);
 
+/* The same distributor on one row of a multi-candidate placement, the row index being read on the
+ * DEVICE when the kernel starts: cand [1] is typically the best_cand output of maaso_placement_sweep
+ * or maaso_placement_score issued just before on the same stream, so that placing and distributing
+ * need no host round trip in between.  pl may hold any number of candidates; only row *cand is read
+ * (and, with window > 0, written).  *cand >= pl->n_cand raises MAASO_DEV_BAD_INSTANCE and the call
+ * behaves as for a placement without instances.  Errors as maaso_score_assign. */
+int maaso_score_assign_selected(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t* cand,
+                                const maaso_requests* rq, const maaso_params* prm,
+                                const maaso_assign_out* out, void* hip_stream);
+
 /* Placer: SLO-satisfaction count and ratio of every candidate deployment against the whole request
  * set, and the best candidate - the evaluation of Phi_S^n(I', R_x) that Alg. 1 performs for each
  * candidate deployment I' (Eq. 3, Eq. 6).

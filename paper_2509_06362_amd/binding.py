@@ -25,6 +25,7 @@ EXPORTS = (
     "maaso_ctx_kernel_elapsed", "maaso_ctx_sweep_evaluated", "maaso_score_assign",
     "maaso_placement_sweep", "maaso_placement_score", "maaso_split_by_slo",
     "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
+    "maaso_score_assign_selected",
 )
 
 
@@ -99,6 +100,9 @@ def load_library() -> C.CDLL:
         lib.maaso_ctx_sweep_evaluated.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         lib.maaso_score_assign.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                            C.POINTER(Params), C.POINTER(AssignOut), C.c_void_p]
+        lib.maaso_score_assign_selected.argtypes = [C.c_void_p, C.POINTER(Placements), C.c_void_p,
+                                                    C.POINTER(Requests), C.POINTER(Params),
+                                                    C.POINTER(AssignOut), C.c_void_p]
         lib.maaso_placement_sweep.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                               C.POINTER(Params), C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p]
@@ -260,6 +264,24 @@ def maaso_score_assign(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch
     _check(load_library().maaso_score_assign(ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm),
                                              C.byref(out), _stream_handle(stream)),
            "maaso_score_assign")
+
+
+def maaso_score_assign_selected(ctx: Context, *, cand, n_cand, i_pad, n_inst, tp_idx, max_batch, occ,
+                                q_ticks, n_req, prompt_len, out_len, slo_class, arrival_ticks=None,
+                                s_bar, pen_kappa=0.0, tbt_mode=0, window=0, policy=0,
+                                chosen=None, slack=None, ttft=None, tbt=None, e2e=None,
+                                n_satisfied=None, stream=None) -> None:
+    """maaso_score_assign on the row whose index is the device word `cand` (an int32 tensor)."""
+    import torch
+    pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
+    rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window), int(policy))
+    out = AssignOut(_dptr(chosen, torch.int32), _dptr(slack, torch.float32),
+                    _dptr(ttft, torch.float32), _dptr(tbt, torch.float32),
+                    _dptr(e2e, torch.float32), _dptr(n_satisfied, torch.int64))
+    _check(load_library().maaso_score_assign_selected(
+        ctx.handle, C.byref(pl), _dptr(cand, torch.int32), C.byref(rq), C.byref(prm), C.byref(out),
+        _stream_handle(stream)), "maaso_score_assign_selected")
 
 
 def maaso_placement_sweep(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
@@ -508,6 +530,32 @@ class DeviceWorkload:
             tp_idx=self.tp_idx[cand:cand + 1], max_batch=self.max_batch[cand:cand + 1], occ=occ,
             q_ticks=q, **self.request_args(), arrival_ticks=self.arrival_ticks, **prm,
             window=window, stream=stream,
+            **{k: out.get(k) for k in ("chosen", "slack", "ttft", "tbt", "e2e", "n_satisfied")})
+        res = dict(out)
+        res["occ"], res["q_ticks"] = occ, q
+        return res
+
+    def assign_selected(self, cand, window=None, latencies: bool = True, stream=None, out=None):
+        """maaso_score_assign_selected over all resident candidates, the row named by the device
+        word `cand` (int32 tensor [1]).  With window > 0 the whole state is cloned first."""
+        import torch
+        dev = self.prompt_len.device
+        R = self.w.n_req
+        window = self.w.window if window is None else window
+        if out is None:
+            out = dict(chosen=torch.empty(R, dtype=torch.int32, device=dev),
+                       slack=torch.empty(R, dtype=torch.float32, device=dev),
+                       n_satisfied=torch.empty(1, dtype=torch.int64, device=dev))
+            if latencies:
+                for k in ("ttft", "tbt", "e2e"):
+                    out[k] = torch.empty(R, dtype=torch.float32, device=dev)
+        occ, q = self.occ, self.q_ticks
+        if window:
+            occ, q = occ.clone(), q.clone()
+        maaso_score_assign_selected(
+            self.ctx, cand=cand, n_cand=self.w.n_cand, i_pad=self.w.i_pad, n_inst=self.n_inst,
+            tp_idx=self.tp_idx, max_batch=self.max_batch, occ=occ, q_ticks=q, **self.request_args(),
+            arrival_ticks=self.arrival_ticks, **self.param_args(), window=window, stream=stream,
             **{k: out.get(k) for k in ("chosen", "slack", "ttft", "tbt", "e2e", "n_satisfied")})
         res = dict(out)
         res["occ"], res["q_ticks"] = occ, q

@@ -24,7 +24,9 @@ struct AssignArgs {
   uint32_t n_slo;
   float d_ttft[kMaxSlo], d_tbt[kMaxSlo], i_ttft[kMaxSlo], i_tbt[kMaxSlo];
   uint32_t i_pad;
-  const uint32_t* n_inst;  // [1]
+  uint32_t n_cand;           // rows in the placement arrays
+  const uint32_t* cand_sel;  // [1] device word naming the row to distribute over; null = row 0
+  const uint32_t* n_inst;    // [n_cand]
   const uint8_t* tp_idx;
   const uint16_t* max_batch;
   int32_t* occ;
@@ -52,14 +54,41 @@ struct ClassRow {
   float Dt, Db, iDt, iDb;
 };
 
+// The placement row a call works on.  The row index may live on the device (the best candidate of a
+// sweep that ran just before on the same stream), so that no host round trip separates the two.
+struct PlacementRow {
+  uint32_t n;  // valid instances, already clamped to i_pad; 0 when the index is out of range
+  const uint8_t* tp_idx;
+  const uint16_t* max_batch;
+  int32_t* occ;
+  uint64_t* q_ticks;
+};
+__device__ __forceinline__ PlacementRow select_row(const AssignArgs& a) {
+  uint32_t c = a.cand_sel ? *a.cand_sel : 0u;
+  PlacementRow r;
+  if (c >= a.n_cand) {
+    raise_status(a.status, 2u);
+    c = 0u;
+    r.n = 0u;
+  } else {
+    r.n = min(a.n_inst[c], a.i_pad);
+  }
+  const size_t off = (size_t)c * a.i_pad;
+  r.tp_idx = a.tp_idx + off;
+  r.max_batch = a.max_batch + off;
+  r.occ = a.occ + off;
+  r.q_ticks = a.q_ticks + off;
+  return r;
+}
+
 // Stage the placement's instances into LDS records {a, p, tbt, wait}.  An instance outside the
 // tables keeps its slot (dropping it would shift the indices) with a record that can never win:
 // wait = +inf gives slack = -inf, which a strict '>' against -inf never takes.
-__device__ __forceinline__ void stage_placement(const AssignArgs& a, uint32_t n, float4* recs,
-                                                float* svc) {
+__device__ __forceinline__ void stage_placement(const AssignArgs& a, const PlacementRow& row, uint32_t n,
+                                                float4* recs, float* svc) {
   for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) {
     Staged s;
-    if (stage_instance(a.tab, a.cells, a.mp, a.tp_idx[j], a.max_batch[j], a.occ[j], a.q_ticks[j], s)) {
+    if (stage_instance(a.tab, a.cells, a.mp, row.tp_idx[j], row.max_batch[j], row.occ[j], row.q_ticks[j], s)) {
       recs[j] = make_float4(s.a, s.p, s.tbt, s.wait);
       if (svc) svc[j] = s.svc;
     } else {
@@ -269,10 +298,11 @@ __global__ __launch_bounds__(kAssignThreads) void assign_static_kernel(const Ass
   const uint64_t stride = (uint64_t)gridDim.x * kAssignThreads;
   RequestVec cur{}, nxt{};
   if (V == 4 && g0 < n_vec) cur = load_request_vec(a, g0 * V);
-  const uint32_t n = min(min(a.n_inst[0], a.i_pad), NREG ? (uint32_t)NREG : 256u);
-  stage_placement(a, n, recs, nullptr);
+  const PlacementRow row = select_row(a);
+  const uint32_t n = min(row.n, NREG ? (uint32_t)NREG : 256u);
+  stage_placement(a, row, n, recs, nullptr);
   if (kSQ)
-    for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) occ_s[j] = a.occ[j];
+    for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) occ_s[j] = row.occ[j];
   __syncthreads();
   if (kSQ)
     for (uint32_t j = threadIdx.x; j < n; j += blockDim.x) rankv[j] = queue_rank_value(occ_s, n, j);

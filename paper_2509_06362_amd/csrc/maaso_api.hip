@@ -128,6 +128,10 @@ int launch_sweep(const SweepArgs& a, uint32_t blocks, hipStream_t s) {
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
 
+int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t* cand_sel,
+                      const maaso_requests* rq, const maaso_params* prm, const maaso_assign_out* out,
+                      void* hip_stream);
+
 void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placements* pl,
                       const maaso_requests* rq, const maaso_params* prm,
                       const maaso_assign_out* out) {
@@ -140,6 +144,8 @@ void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placement
   std::memcpy(a.i_ttft, ctx->i_ttft, sizeof(a.i_ttft));
   std::memcpy(a.i_tbt, ctx->i_tbt, sizeof(a.i_tbt));
   a.i_pad = pl->i_pad;
+  a.n_cand = pl->n_cand;
+  a.cand_sel = nullptr;
   a.n_inst = pl->n_inst;
   a.tp_idx = pl->tp_idx;
   a.max_batch = pl->max_batch;
@@ -689,9 +695,27 @@ int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t
 
 int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                        const maaso_params* prm, const maaso_assign_out* out, void* hip_stream) {
+  if (pl && pl->n_cand != 1u) return MAASO_E_INVALID_ARG;
+  return score_assign_impl(ctx, pl, nullptr, rq, prm, out, hip_stream);
+}
+
+int maaso_score_assign_selected(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t* cand,
+                                const maaso_requests* rq, const maaso_params* prm,
+                                const maaso_assign_out* out, void* hip_stream) {
+  if (!cand) return MAASO_E_INVALID_ARG;
+  return score_assign_impl(ctx, pl, cand, rq, prm, out, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t* cand_sel,
+                      const maaso_requests* rq, const maaso_params* prm, const maaso_assign_out* out,
+                      void* hip_stream) {
   int rc = check_common(ctx, pl, rq, prm);
   if (rc != MAASO_OK) return rc;
-  if (!out || pl->n_cand != 1u || (!out->chosen && !out->n_satisfied)) return MAASO_E_INVALID_ARG;
+  if (!out || (!out->chosen && !out->n_satisfied)) return MAASO_E_INVALID_ARG;
   const uint32_t R = rq->n_req;
   if (prm->window != 0u && R != 0 && !rq->arrival_ticks) return MAASO_E_INVALID_ARG;
   DeviceGuard guard(ctx->device);
@@ -700,6 +724,7 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
 
   AssignArgs a;
   fill_assign_args(a, ctx, pl, rq, prm, out);
+  a.cand_sel = cand_sel;
   const bool lat = out->ttft || out->tbt || out->e2e;
   if (R == 0) {
     hipLaunchKernelGGL(assign_init_kernel, dim3(1), dim3(64), 0, s, a.n_satisfied);
@@ -788,6 +813,10 @@ int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_r
 #undef MAASO_LAUNCH_WINDOW
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
+
+}  // namespace
+
+extern "C" {
 
 int maaso_ctx_kernel_timing(maaso_ctx* ctx, int enable) {
   if (!ctx) return MAASO_E_INVALID_ARG;

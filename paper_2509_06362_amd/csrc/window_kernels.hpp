@@ -114,12 +114,13 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
   __shared__ float rankv[kSQ ? 256 : 1];
 
   const uint32_t tid = threadIdx.x;
-  const uint32_t n = min(a.n_inst[0], a.i_pad);
+  const PlacementRow row = select_row(a);
+  const uint32_t n = row.n;
   // thread j owns instance j: configuration and live state stay in its registers
   uint32_t tp = 0, B = 1;
   int32_t occ = 0;
   uint64_t q = 0;
-  if (tid < n) { tp = a.tp_idx[tid]; B = a.max_batch[tid]; occ = a.occ[tid]; q = a.q_ticks[tid]; }
+  if (tid < n) { tp = row.tp_idx[tid]; B = row.max_batch[tid]; occ = row.occ[tid]; q = row.q_ticks[tid]; }
   if (tid < a.n_slo) cls[tid] = ClassRow{a.d_ttft[tid], a.d_tbt[tid], a.i_ttft[tid], a.i_tbt[tid]};
   for (uint32_t i = tid; i < 3u * a.cells; i += kWindowThreads) tab[i] = a.tab[i];
   __syncthreads();
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
     }
   }
 
-  if (alive && blockIdx.x == 0 && tid < n) { a.occ[tid] = occ; a.q_ticks[tid] = q; }
+  if (alive && blockIdx.x == 0 && tid < n) { row.occ[tid] = occ; row.q_ticks[tid] = q; }
   for (int dlt = 32; dlt >= 1; dlt >>= 1) sat += __shfl_xor(sat, dlt);
   if ((tid & 63u) == 0u) wave_sat[tid >> 6] = sat;
   __syncthreads();

@@ -768,6 +768,46 @@ def test_sweep_and_score_shortest_queue(seed, n_cand, i_pad, n_req, n_slo, windo
         check_score(v, window, weights=SCORE_WEIGHTS[:2])
 
 
+@pytest.mark.parametrize("window", [0, 300])
+def test_assign_on_a_row_selected_on_the_device(window):
+    """Sweep, then distribute over the sweep's best candidate without the index leaving the GPU; and
+    over every other row in turn; an out-of-range index is flagged and treated as an empty placement."""
+    w = W.stressed(W.random_small(131, 9, 24, 2000, n_slo=3, pen_kappa=0.25), seed=5, deadline_scale=0.25)
+    w = W.replace(w, arrival_ticks=W.poisson_arrivals(W.rng_for(131, 3), 700.0, 2000))
+    dw = binding.DeviceWorkload(w)
+    try:
+        dev = dw.prompt_len.device
+        cnt, _, best = dw.sweep()
+        got = dw.assign_selected(best, window=window)
+        torch.cuda.synchronize()
+        b = int(best.item())
+        assert b == oracle.placement_sweep(w)["best_cand"]
+        rows = [(best, b, got)]
+        for c in range(w.n_cand):
+            sel = torch.tensor([c], dtype=torch.int32, device=dev)
+            rows.append((sel, c, dw.assign_selected(sel, window=window)))
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        for sel, c, g in rows:
+            ref = oracle.score_assign(w, cand=c, window=window)
+            assert np.array_equal(g["chosen"].cpu().numpy(), ref["chosen"]), c
+            assert np.array_equal(g["slack"].cpu().numpy(), ref["slack"])
+            for k in ("ttft", "tbt", "e2e"):
+                assert np.array_equal(g[k].cpu().numpy(), ref[k], equal_nan=True)
+            assert int(g["n_satisfied"].item()) == ref["n_satisfied"]
+            occ = g["occ"].cpu().numpy()
+            assert np.array_equal(occ[c], ref["occ"])
+            assert np.array_equal(np.delete(occ, c, axis=0), np.delete(w.occ, c, axis=0))   # other rows untouched
+            assert np.array_equal(g["q_ticks"].cpu().numpy()[c].view(np.uint64), ref["q_ticks"])
+        bad = torch.tensor([w.n_cand], dtype=torch.int32, device=dev)
+        g = dw.assign_selected(bad, window=window)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 2
+        assert (g["chosen"].cpu().numpy() == -1).all() and int(g["n_satisfied"].item()) == 0
+    finally:
+        dw.close()
+
+
 def test_assign_static_unaligned_arrays_take_the_scalar_path():
     """Request and output arrays offset by one element are only 4-byte aligned."""
     w = W.stressed(W.random_small(26, 1, 20, 3001, n_slo=3), seed=3)
