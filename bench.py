@@ -56,7 +56,7 @@ KERNEL_SOURCES = {
 }
 TRAFFIC = {
     "cfg1_placer_sweep": ("sweep_kernel", 6.710e6, "8098146ad3d29803"),
-    "streaming_i4": ("assign_static_kernel", 1.1410e9, "9d696107b573d9f5"),
+    "streaming_i4": ("assign_static_kernel", 1.1410e9, "76aa51fcf860e5bd"),
 }
 
 
