@@ -70,6 +70,13 @@ __device__ __forceinline__ float min_no_nan(float x, float y) {
   return r;
 }
 
+// min(x, y, z) in one instruction slot.
+__device__ __forceinline__ float min3_no_nan(float x, float y, float z) {
+  float r;
+  asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
+  return r;
+}
+
 __device__ __forceinline__ float max_no_nan(float x, float y) {
   float r;
   asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
@@ -261,7 +268,9 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
   }
   for (uint32_t i = tid; i < 3u * kMaxGroup; i += kSweepThreads) (&lens[0][0])[i] = 0u;
   __syncthreads();
-  uint32_t cur = items[0], nxt = items[1];
+  // uniform by construction; held in scalar registers so that the candidate loop is a scalar loop
+  uint32_t cur = __builtin_amdgcn_readfirstlane(items[0]);
+  uint32_t nxt = __builtin_amdgcn_readfirstlane(items[1]);
   if (cur >= a.n_items) return;
 
   // staging slot(s) of this thread inside a group
@@ -336,7 +345,15 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
 #pragma unroll
             for (int q = 0; q < Q; ++q) m[q] = r.z + fmaf(r.x, L[q], r.y);
           }
-          for (uint32_t i = 1; i < n; ++i) {
+          uint32_t i = 1;
+          for (; i + 1u < n; i += 2u) {  // two records per trip: one three-way minimum serves both
+            const float4 r = lst[i];
+            const float4 s = lst[i + 1u];
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+              m[q] = min3_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y), s.z + fmaf(s.x, L[q], s.y));
+          }
+          if (i < n) {
             const float4 r = lst[i];
 #pragma unroll
             for (int q = 0; q < Q; ++q) m[q] = min_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y));
@@ -357,7 +374,7 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
     prev_c0 = c0;
     prev_n = g_cands;
     cur = nxt;
-    nxt = items[it & 1u];
+    nxt = __builtin_amdgcn_readfirstlane(items[it & 1u]);
     if (cur >= a.n_items) {
       if (tid < prev_n) {
         const uint32_t b = it & 1u;
