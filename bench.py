@@ -146,7 +146,7 @@ ALG2_SCORE_WEIGHTS = (4.0, 0.3, 4096.0, 2.0)
 def bench_alg2(args) -> int:
     """Resource partition (Alg. 2) as one pipeline: split by SLO, every growth-chain deployment of
     Alg. 1 scored against R_t, R_l and R, best per GPU count, partition scan.  A step is the whole
-    pipeline; its triples are those of the three scoring launches."""
+    pipeline; its triples are those of the scoring launch, which carries the three request sets."""
     import numpy as np
     import torch
     from paper_2509_06362_amd import binding, workloads as W
@@ -175,7 +175,7 @@ def bench_alg2(args) -> int:
     torch.cuda.synchronize()
     k_ms, k_n = binding.maaso_ctx_kernel_elapsed(dw.ctx)
     binding.maaso_ctx_kernel_timing(dw.ctx, False)
-    k_total_s = k_ms * 1e-3 / max(n_timed, 1)       # the three scoring launches of one step
+    k_total_s = k_ms * 1e-3 / max(n_timed, 1)       # the scoring launch of one step (three request sets)
     ops = ASSIGN_LANEOPS_PER_TRIPLE * triples_step
     part = res["partition"].cpu().numpy()
     result = {
@@ -187,7 +187,7 @@ def bench_alg2(args) -> int:
         "config": {"workload": "alg2_partition", "n_gpus_partitioned": ALG2_GPUS, "n_cand": cw.n_cand,
                    "i_pad": cw.i_pad, "n_req": cw.n_req, "n_chains": len(tp), "window": int(w.window),
                    "seed": w.seed, "triples_per_step": triples_step,
-                   "step": "split_by_slo + 3 x (placement_score + ins_deploy_select) + resource_partition",
+                   "step": "split_by_slo + placement_score_sets (R_t, R_l, R) + 3 x ins_deploy_select + resource_partition",
                    "partition": {"g_t": int(part[0]), "g_l": int(part[1]),
                                  "heterogeneous": int(part[2]), "phi_opt": float(res["phi_opt"].item())}},
         "roofline": {"kernel": "sweep_window_kernel", "bound": "alu",

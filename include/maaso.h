@@ -48,6 +48,7 @@ typedef enum {
 #define MAASO_MAX_REQUESTS 2147483648u /* R: requests per call                                  */
 #define MAASO_MAX_LEN 16777215u    /* prompt_len / out_len: exactly representable in binary32   */
 #define MAASO_MAX_GPUS 4096u       /* |G|: GPUs of a (sub-)cluster in the placer's outer algorithms */
+#define MAASO_MAX_REQUEST_SETS 4u  /* request sets scored by one maaso_placement_score_sets call   */
 
 /* bits of the device status word (maaso_ctx_device_status) */
 #define MAASO_DEV_BAD_CLASS 1u     /* a request with slo_class >= n_slo was skipped (never satisfied) */
@@ -280,6 +281,18 @@ typedef struct {
 int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, const maaso_score_weights* wts,
                           const maaso_score_out* out, void* hip_stream);
+
+/* maaso_placement_score of the same candidates against n_sets (1..MAASO_MAX_REQUEST_SETS) request
+ * sets at once: rq[k] is scored into out[k], HOST arrays of n_sets elements each, exactly as a call of
+ * maaso_placement_score per set would - every set starts from the state as given in pl.  Alg. 2
+ * (Sec. IV-E) needs the score of every candidate deployment against R_t, against R_l and, for its
+ * homogeneous fallback, against all of R; the runs are independent, so one launch carries them all
+ * and the device stays filled while the longest of them finishes.  No two sets may share an output
+ * array.  Errors: INVALID_ARG, SHAPE, HIP. */
+int maaso_placement_score_sets(maaso_ctx* ctx, const maaso_placements* pl, uint32_t n_sets,
+                               const maaso_requests* rq, const maaso_params* prm,
+                               const maaso_score_weights* wts, const maaso_score_out* out,
+                               void* hip_stream);
 
 /* Alg. 2, first step (Sec. IV-E: the requests are categorised by SLO into a strict set R_t and a
  * relaxed set R_l).  Classes whose bit is set in tight_classes form R_t.  The four request streams

@@ -25,7 +25,7 @@ EXPORTS = (
     "maaso_ctx_kernel_elapsed", "maaso_ctx_sweep_evaluated", "maaso_score_assign",
     "maaso_placement_sweep", "maaso_placement_score", "maaso_split_by_slo",
     "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
-    "maaso_score_assign_selected",
+    "maaso_score_assign_selected", "maaso_placement_score_sets",
 )
 
 
@@ -109,6 +109,10 @@ def load_library() -> C.CDLL:
         lib.maaso_placement_score.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                               C.POINTER(Params), C.POINTER(ScoreWeights),
                                               C.POINTER(ScoreOut), C.c_void_p]
+        lib.maaso_placement_score_sets.argtypes = [C.c_void_p, C.POINTER(Placements), C.c_uint32,
+                                                   C.POINTER(Requests), C.POINTER(Params),
+                                                   C.POINTER(ScoreWeights), C.POINTER(ScoreOut),
+                                                   C.c_void_p]
         lib.maaso_profile_fit.argtypes = [C.c_int, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_uint32, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         lib.maaso_split_by_slo.argtypes = [C.c_void_p, C.POINTER(Requests), C.c_uint32] + [C.c_void_p] * 6
@@ -316,6 +320,30 @@ def maaso_placement_score(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_ba
            "maaso_placement_score")
 
 
+def maaso_placement_score_sets(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
+                               sets, s_bar, pen_kappa=0.0, tbt_mode=0, window=0, policy=0, alpha, beta,
+                               gamma_t, gamma_l, stream=None) -> None:
+    """`sets`: one dict per request set with the request keywords (n_req, prompt_len, out_len,
+    slo_class, arrival_ticks) and the output keywords (sat_count, score, phi_s, phi_t, phi_l,
+    best_cand) of maaso_placement_score."""
+    import torch
+    pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window), int(policy))
+    wts = ScoreWeights(float(alpha), float(beta), float(gamma_t), float(gamma_l))
+    n = len(sets)
+    rqs = (Requests * max(n, 1))()
+    outs = (ScoreOut * max(n, 1))()
+    for k, d in enumerate(sets):
+        rqs[k] = _requests(d["n_req"], d["prompt_len"], d["out_len"], d["slo_class"],
+                           d.get("arrival_ticks"))
+        outs[k] = ScoreOut(_dptr(d["sat_count"], torch.int32), _dptr(d.get("phi_s"), torch.float32),
+                           _dptr(d.get("phi_t"), torch.float32), _dptr(d.get("phi_l"), torch.float32),
+                           _dptr(d["score"], torch.float32), _dptr(d.get("best_cand"), torch.int32))
+    _check(load_library().maaso_placement_score_sets(
+        ctx.handle, C.byref(pl), n, rqs, C.byref(prm), C.byref(wts), outs, _stream_handle(stream)),
+        "maaso_placement_score_sets")
+
+
 def maaso_profile_fit(offsets, level, thr, b_cap: int, eps_lo: float = 2.0 ** -10,
                       eps_hi: float = 2.0 ** 10, device: int = 0):
     """Host numpy samples -> (params [T, 4] float64: T0, delta, eps, sse; tbt [T, b_cap + 1] float32).
@@ -442,6 +470,30 @@ class DeviceWorkload:
             stream=stream, **out)
         return out
 
+    def score_sets(self, ranges, alpha, beta, gamma_t, gamma_l, window=0, stream=None):
+        """maaso_placement_score_sets: the resident candidates against the request ranges
+        [(lo, hi), ...] of the resident requests, one launch; returns one dict of tensors per range."""
+        import torch
+        dev = self.prompt_len.device
+        C_ = self.w.n_cand
+        sets, outs = [], []
+        for lo, hi in ranges:
+            out = dict(sat_count=torch.empty(C_, dtype=torch.int32, device=dev),
+                       best_cand=torch.empty(1, dtype=torch.int32, device=dev))
+            for k in ("phi_s", "phi_t", "phi_l", "score"):
+                out[k] = torch.empty(C_, dtype=torch.float32, device=dev)
+            outs.append(out)
+            sets.append(dict(
+                n_req=hi - lo, prompt_len=self.prompt_len[lo:hi], out_len=self.out_len[lo:hi],
+                slo_class=self.slo_class[lo:hi],
+                arrival_ticks=self.arrival_ticks[lo:hi] if window else None, **out))
+        maaso_placement_score_sets(
+            self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
+            max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, sets=sets, window=window,
+            **self.param_args(), alpha=alpha, beta=beta, gamma_t=gamma_t, gamma_l=gamma_l,
+            stream=stream)
+        return outs
+
     def split_by_slo(self, tight_classes: int, stream=None):
         """maaso_split_by_slo of the resident requests; returns the four reordered streams (arrival
         None when the workload has none) and the device word holding |R_t|."""
@@ -471,29 +523,30 @@ class DeviceWorkload:
         offs = torch.from_numpy(np.ascontiguousarray(chain_offsets).view(np.int32)).to(dev)
         res = dict(n_tight=n_t)
 
-        def deploy(tag, lo, hi, src):
-            sub = dict(n_req=hi - lo, prompt_len=src[0][lo:hi], out_len=src[1][lo:hi],
-                       slo_class=src[2][lo:hi],
-                       arrival_ticks=None if (src[3] is None or not window) else src[3][lo:hi])
-            sat = torch.empty(C_, dtype=torch.int32, device=dev)
-            score = torch.empty(C_, dtype=torch.float32, device=dev)
-            maaso_placement_score(
-                self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
-                max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, **sub, window=window,
-                **self.param_args(), alpha=alpha, beta=beta, gamma_t=gamma_t, gamma_l=gamma_l,
-                sat_count=sat, score=score, stream=stream)
+        split = (sp["prompt_len_out"], sp["out_len_out"], sp["slo_class_out"], sp["arrival_ticks_out"])
+        runs = [("t", 0, n_t, split), ("l", n_t, R, split)]
+        if homogeneous:
+            runs.append(("h", 0, R, (self.prompt_len, self.out_len, self.slo_class, self.arrival_ticks)))
+        sets = []
+        for tag, lo, hi, src in runs:
+            res[f"score_{tag}"] = torch.empty(C_, dtype=torch.float32, device=dev)
+            sets.append(dict(
+                n_req=hi - lo, prompt_len=src[0][lo:hi], out_len=src[1][lo:hi], slo_class=src[2][lo:hi],
+                arrival_ticks=None if (src[3] is None or not window) else src[3][lo:hi],
+                sat_count=torch.empty(C_, dtype=torch.int32, device=dev), score=res[f"score_{tag}"]))
+        # one launch scores every candidate against every set
+        maaso_placement_score_sets(
+            self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
+            max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, sets=sets, window=window,
+            **self.param_args(), alpha=alpha, beta=beta, gamma_t=gamma_t, gamma_l=gamma_l,
+            stream=stream)
+        for tag, _, _, _ in runs:
             phi = torch.empty(n_gpus + 1, dtype=torch.float32, device=dev)
             cand = torch.empty(n_gpus + 1, dtype=torch.int32, device=dev)
             maaso_ins_deploy_select(self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst,
-                                    tp_idx=self.tp_idx, score=score, chain_offsets=offs, n_gpus=n_gpus,
-                                    phi_star=phi, cand_star=cand, stream=stream)
-            res[f"score_{tag}"], res[f"phi_{tag}_star"], res[f"cand_{tag}_star"] = score, phi, cand
-
-        split = (sp["prompt_len_out"], sp["out_len_out"], sp["slo_class_out"], sp["arrival_ticks_out"])
-        deploy("t", 0, n_t, split)
-        deploy("l", n_t, R, split)
-        if homogeneous:
-            deploy("h", 0, R, (self.prompt_len, self.out_len, self.slo_class, self.arrival_ticks))
+                                    tp_idx=self.tp_idx, score=res[f"score_{tag}"], chain_offsets=offs,
+                                    n_gpus=n_gpus, phi_star=phi, cand_star=cand, stream=stream)
+            res[f"phi_{tag}_star"], res[f"cand_{tag}_star"] = phi, cand
         res["partition"] = torch.empty(6, dtype=torch.int32, device=dev)
         res["phi_opt"] = torch.empty(1, dtype=torch.float32, device=dev)
         maaso_resource_partition(

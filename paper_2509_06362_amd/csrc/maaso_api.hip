@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -166,29 +167,36 @@ void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placement
   a.sat_acc = reinterpret_cast<unsigned long long*>(ctx->status + 36);
 }
 
-// One block per candidate; requests per lane chosen so that a window keeps the lanes busy.
+// One block per (request set, candidate); requests per lane chosen so that a window keeps the lanes
+// busy (by the set with the longest windows: the choice never changes a result).
 template <bool kScore, bool kSQ>
-int launch_sweep_window_v(const SweepWindowArgs& a, uint32_t n_cand, size_t lds, hipStream_t s) {
-  const uint64_t per_window = a.window < a.n_req ? a.window : a.n_req;
+int launch_sweep_window_v(const SweepWindowArgs& a, size_t lds, hipStream_t s) {
+  uint64_t per_window = 0;
+  for (uint32_t k = 0; k < a.n_sets; ++k) {
+    const uint64_t pw = a.sets[k].window < a.sets[k].n_req ? a.sets[k].window : a.sets[k].n_req;
+    if (pw > per_window) per_window = pw;
+  }
+  const uint64_t blocks = (uint64_t)a.n_cand * a.n_sets;
+  if (blocks == 0 || blocks > 0x7fffffffull) return MAASO_E_SHAPE;
+  const dim3 grid((uint32_t)blocks);
   if (per_window > 2u * kAssignThreads)
-    hipLaunchKernelGGL((sweep_window_kernel<kScore, 4, kSQ>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 4, kSQ>), grid, dim3(kAssignThreads), lds, s, a);
   else if (per_window > kAssignThreads)
-    hipLaunchKernelGGL((sweep_window_kernel<kScore, 2, kSQ>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 2, kSQ>), grid, dim3(kAssignThreads), lds, s, a);
   else
-    hipLaunchKernelGGL((sweep_window_kernel<kScore, 1, kSQ>), dim3(n_cand), dim3(kAssignThreads), lds, s, a);
+    hipLaunchKernelGGL((sweep_window_kernel<kScore, 1, kSQ>), grid, dim3(kAssignThreads), lds, s, a);
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
 
 template <bool kScore>
-int launch_sweep_window(const SweepWindowArgs& a, uint32_t policy, uint32_t n_cand, size_t lds,
-                        hipStream_t s) {
-  return policy ? launch_sweep_window_v<kScore, true>(a, n_cand, lds, s)
-                : launch_sweep_window_v<kScore, false>(a, n_cand, lds, s);
+int launch_sweep_window(const SweepWindowArgs& a, uint32_t policy, size_t lds, hipStream_t s) {
+  return policy ? launch_sweep_window_v<kScore, true>(a, lds, s)
+                : launch_sweep_window_v<kScore, false>(a, lds, s);
 }
 
+// Everything but the request sets.
 void fill_sweep_window_args(SweepWindowArgs& a, const maaso_ctx* ctx, const maaso_placements* pl,
-                            const maaso_requests* rq, const maaso_params* prm, uint32_t window,
-                            uint32_t* sat_count) {
+                            const maaso_params* prm) {
   a.tab = ctx->tab;
   a.cells = ctx->cells;
   a.mp = model_params(ctx, prm);
@@ -204,17 +212,34 @@ void fill_sweep_window_args(SweepWindowArgs& a, const maaso_ctx* ctx, const maas
   a.max_batch = pl->max_batch;
   a.occ = pl->occ;
   a.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
-  a.n_req = rq->n_req;
-  a.prompt_len = rq->prompt_len;
-  a.out_len = rq->out_len;
-  a.slo_class = rq->slo_class;
-  a.arrival_ticks = rq->arrival_ticks;
-  a.window = window;
-  a.sat_count = sat_count;
+  a.n_sets = 0;
+  std::memset(a.sets, 0, sizeof(a.sets));
   a.status = ctx->status;
   a.alpha = a.beta = 0.0f;
   a.gamma_t = a.gamma_l = 1.0f;
-  a.phi_s = a.phi_t = a.phi_l = a.score = nullptr;
+}
+
+// Appends a request set.  prm->window == 0 (static) = one window over everything: the state update is
+// never reached.
+void add_sweep_window_set(SweepWindowArgs& a, const maaso_requests* rq, const maaso_params* prm,
+                          uint32_t* sat_count, const maaso_score_out* out) {
+  SweepWindowSet& t = a.sets[a.n_sets++];
+  t.n_req = rq->n_req;
+  t.window = prm->window ? prm->window : (rq->n_req ? rq->n_req : 1u);
+  t.prompt_len = rq->prompt_len;
+  t.out_len = rq->out_len;
+  t.slo_class = rq->slo_class;
+  t.arrival_ticks = rq->arrival_ticks;
+  t.sat_count = sat_count;
+  t.phi_s = out ? out->phi_s : nullptr;
+  t.phi_t = out ? out->phi_t : nullptr;
+  t.phi_l = out ? out->phi_l : nullptr;
+  t.score = out ? out->score : nullptr;
+}
+
+bool score_weights_ok(const maaso_score_weights* wts) {
+  return wts && std::isfinite(wts->alpha) && std::isfinite(wts->beta) && wts->gamma_t > 0.0f &&
+         wts->gamma_l > 0.0f && std::isfinite(wts->gamma_t) && std::isfinite(wts->gamma_l);
 }
 
 }  // namespace
@@ -375,11 +400,12 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   if (prm->window != 0u && R != 0) {
     // Capacity-aware form: one block per candidate walks the request windows on its own state copy.
     SweepWindowArgs a;
-    fill_sweep_window_args(a, ctx, pl, rq, prm, prm->window, sat_count);
+    fill_sweep_window_args(a, ctx, pl, prm);
+    add_sweep_window_set(a, rq, prm, sat_count, nullptr);
     {
       TimedRegion timed(ctx, s);
-      if (launch_sweep_window<false>(a, prm->policy, C, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
-        return MAASO_E_HIP;
+      rc = launch_sweep_window<false>(a, prm->policy, (size_t)3 * ctx->cells * sizeof(float), s);
+      if (rc != MAASO_OK) return rc;
     }
     unsigned long long* eval_total = reinterpret_cast<unsigned long long*>(ctx->status + 32);
     hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
@@ -511,38 +537,48 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
 int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, const maaso_score_weights* wts,
                           const maaso_score_out* out, void* hip_stream) {
-  int rc = check_common(ctx, pl, rq, prm);
-  if (rc != MAASO_OK) return rc;
-  if (!wts || !out || !out->sat_count || !out->score) return MAASO_E_INVALID_ARG;
-  if (!std::isfinite(wts->alpha) || !std::isfinite(wts->beta) || !(wts->gamma_t > 0.0f) ||
-      !(wts->gamma_l > 0.0f) || !std::isfinite(wts->gamma_t) || !std::isfinite(wts->gamma_l))
-    return MAASO_E_INVALID_ARG;
-  if (prm->window != 0u && rq->n_req != 0 && !rq->arrival_ticks) return MAASO_E_INVALID_ARG;
+  return maaso_placement_score_sets(ctx, pl, 1u, rq, prm, wts, out, hip_stream);
+}
+
+int maaso_placement_score_sets(maaso_ctx* ctx, const maaso_placements* pl, uint32_t n_sets,
+                               const maaso_requests* rq, const maaso_params* prm,
+                               const maaso_score_weights* wts, const maaso_score_out* out,
+                               void* hip_stream) {
+  if (!rq || !out || n_sets == 0u || n_sets > MAASO_MAX_REQUEST_SETS) return MAASO_E_INVALID_ARG;
+  for (uint32_t k = 0; k < n_sets; ++k) {
+    const int rc = check_common(ctx, pl, &rq[k], prm);
+    if (rc != MAASO_OK) return rc;
+    if (!out[k].sat_count || !out[k].score) return MAASO_E_INVALID_ARG;
+    if (prm->window != 0u && rq[k].n_req != 0 && !rq[k].arrival_ticks) return MAASO_E_INVALID_ARG;
+  }
+  if (!score_weights_ok(wts)) return MAASO_E_INVALID_ARG;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   SweepWindowArgs a;
-  // static = one window over everything: the state update is never reached
-  const uint32_t window = prm->window ? prm->window : (rq->n_req ? rq->n_req : 1u);
-  fill_sweep_window_args(a, ctx, pl, rq, prm, window, out->sat_count);
+  fill_sweep_window_args(a, ctx, pl, prm);
+  // longest set first: its blocks run longest, so they should start first
+  uint32_t order[MAASO_MAX_REQUEST_SETS];
+  for (uint32_t k = 0; k < n_sets; ++k) order[k] = k;
+  std::stable_sort(order, order + n_sets,
+                   [&](uint32_t x, uint32_t y) { return rq[x].n_req > rq[y].n_req; });
+  for (uint32_t k = 0; k < n_sets; ++k)
+    add_sweep_window_set(a, &rq[order[k]], prm, out[order[k]].sat_count, &out[order[k]]);
   a.alpha = wts->alpha;
   a.beta = wts->beta;
   a.gamma_t = wts->gamma_t;
   a.gamma_l = wts->gamma_l;
-  a.phi_s = out->phi_s;
-  a.phi_t = out->phi_t;
-  a.phi_l = out->phi_l;
-  a.score = out->score;
   {
     TimedRegion timed(ctx, s);
-    if (launch_sweep_window<true>(a, prm->policy, pl->n_cand, (size_t)3 * ctx->cells * sizeof(float), s) != MAASO_OK)
-      return MAASO_E_HIP;
+    const int rc = launch_sweep_window<true>(a, prm->policy, (size_t)3 * ctx->cells * sizeof(float), s);
+    if (rc != MAASO_OK) return rc;
   }
-  if (out->best_cand) {
-    hipLaunchKernelGGL(score_argmax_kernel, dim3(1), dim3(1024), 0, s, out->score, pl->n_cand,
-                       out->best_cand);
-    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-  }
+  for (uint32_t k = 0; k < n_sets; ++k)
+    if (out[k].best_cand) {
+      hipLaunchKernelGGL(score_argmax_kernel, dim3(1), dim3(1024), 0, s, out[k].score, pl->n_cand,
+                         out[k].best_cand);
+      if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+    }
   return MAASO_OK;
 }
 

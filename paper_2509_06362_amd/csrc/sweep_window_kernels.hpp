@@ -18,6 +18,24 @@
 
 namespace maaso {
 
+// One request set and the outputs of scoring every candidate against it.
+struct SweepWindowSet {
+  uint32_t n_req;
+  uint32_t window;  // requests per window (>= 1)
+  const uint32_t* prompt_len;
+  const uint32_t* out_len;
+  const uint8_t* slo_class;
+  const uint32_t* arrival_ticks;
+  uint32_t* sat_count;
+  // composite serving score (kScore kernels only); every output may be null
+  float* phi_s;
+  float* phi_t;
+  float* phi_l;
+  float* score;
+};
+
+constexpr int kMaxSweepSets = 4;
+
 struct SweepWindowArgs {
   const float* tab;
   uint32_t cells;
@@ -30,20 +48,13 @@ struct SweepWindowArgs {
   const uint16_t* max_batch;
   const int32_t* occ;
   const uint64_t* q_ticks;
-  uint32_t n_req;
-  const uint32_t* prompt_len;
-  const uint32_t* out_len;
-  const uint8_t* slo_class;
-  const uint32_t* arrival_ticks;
-  uint32_t window;
-  uint32_t* sat_count;
+  // Block b scores candidate b % n_cand against set b / n_cand: the sets are independent runs over
+  // the same candidates (Alg. 2 scores every deployment against R_t, R_l and all of R), listed
+  // longest first so that the blocks that run longest start first.
+  uint32_t n_sets;
+  SweepWindowSet sets[kMaxSweepSets];
   uint32_t* status;
-  // composite serving score (kScore kernels only); every output may be null
   float alpha, beta, gamma_t, gamma_l;
-  float* phi_s;
-  float* phi_t;
-  float* phi_l;
-  float* score;
 };
 
 __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
@@ -73,7 +84,9 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   __shared__ float rankv[kSQ ? 256 : 1];
 
   const uint32_t tid = threadIdx.x;
-  const uint32_t c = blockIdx.x;
+  const uint32_t set = blockIdx.x / a.n_cand;
+  const uint32_t c = blockIdx.x - set * a.n_cand;
+  const SweepWindowSet& rs = a.sets[set];
   const size_t base = (size_t)c * a.i_pad;
   const uint32_t n = min(a.n_inst[c], a.i_pad);
   uint32_t tp = 0, B = 1;
@@ -87,8 +100,8 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   for (uint32_t i = tid; i < 3u * a.cells; i += kAssignThreads) tab[i] = a.tab[i];
   __syncthreads();
 
-  const uint64_t R = a.n_req;
-  const uint64_t n_windows = (R + a.window - 1) / a.window;
+  const uint64_t R = rs.n_req;
+  const uint64_t n_windows = (R + rs.window - 1) / rs.window;
   uint32_t sat = 0;
   uint32_t served = 0;                // requests admitted to instance tid over all windows
   unsigned long long wait_sum = 0ull; // their queue waits at admission, in ticks
@@ -96,10 +109,10 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   float inv_tbt_first = 0.0f;
 
   for (uint64_t w = 0; w < n_windows; ++w) {
-    const uint64_t s0 = w * a.window;
-    const uint64_t e0 = (s0 + a.window < R) ? s0 + a.window : R;
+    const uint64_t s0 = w * rs.window;
+    const uint64_t e0 = (s0 + rs.window < R) ? s0 + rs.window : R;
     uint32_t delta = 0;
-    if (tid < n && e0 < R) delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
+    if (tid < n && e0 < R) delta = rs.arrival_ticks[e0] - rs.arrival_ticks[s0];
     float svc = 1.0f;
     if (tid < n) {
       Staged st;
@@ -138,7 +151,7 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
         live[v] = r < e0;
         uint32_t pl = 0, ol = 0;
         k[v] = 0;
-        if (live[v]) { pl = a.prompt_len[r]; ol = a.out_len[r]; k[v] = a.slo_class[r]; }
+        if (live[v]) { pl = rs.prompt_len[r]; ol = rs.out_len[r]; k[v] = rs.slo_class[r]; }
         if (k[v] >= a.n_slo) { raise_status(a.status, 1u); live[v] = false; k[v] = 0; }
         L[v] = (float)pl; S[v] = (float)ol;
         const ClassRow cr = cls[k[v]];
@@ -242,11 +255,11 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   if (tid == 0) {
     uint32_t t = 0;
     for (int wv = 0; wv < kAssignThreads / 64; ++wv) t += wave_sat[wv];
-    a.sat_count[c] = t;
+    rs.sat_count[c] = t;
     if (kScore) {
       unsigned long long ticks = 0ull;
       for (int wv = 0; wv < kAssignThreads / 64; ++wv) ticks += t_blk[wv];
-      const float ps = (a.n_req == 0u) ? 0.0f : (float)t / (float)a.n_req;
+      const float ps = (rs.n_req == 0u) ? 0.0f : (float)t / (float)rs.n_req;
       float pt = 0.0f;
       for (uint32_t j = 0; j < n; ++j) {
         const float inv = s2tab[j];
@@ -256,10 +269,10 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
       const float ptn = fminf(pt, a.gamma_t) / a.gamma_t;
       const float pln = fmaxf(a.gamma_l - pl, 0.0f) / a.gamma_l;
       const float sc = fmaf(a.alpha, ps, fmaf(a.beta, ptn, (1.0f - a.beta) * pln));
-      if (a.phi_s) a.phi_s[c] = ps;
-      if (a.phi_t) a.phi_t[c] = pt;
-      if (a.phi_l) a.phi_l[c] = pl;
-      if (a.score) a.score[c] = sc;
+      if (rs.phi_s) rs.phi_s[c] = ps;
+      if (rs.phi_t) rs.phi_t[c] = pt;
+      if (rs.phi_l) rs.phi_l[c] = pl;
+      if (rs.score) rs.score[c] = sc;
     }
   }
 }

@@ -87,6 +87,8 @@ def test_null_context_is_rejected(lib):
     assert lib.maaso_score_assign(None, None, None, None, None, None) == -1
     assert lib.maaso_placement_sweep(None, None, None, None, None, None, None, None) == -1
     assert lib.maaso_placement_score(None, None, None, None, None, None, None) == -1
+    assert lib.maaso_placement_score_sets(None, None, 1, None, None, None, None, None) == -1
+    assert lib.maaso_placement_score_sets(None, None, 0, None, None, None, None, None) == -1
     assert lib.maaso_score_assign_selected(None, None, None, None, None, None, None) == -1
     assert lib.maaso_profile_fit(0, 1, None, None, None, 8, 1.0, 2.0, None, None) == -1
     assert lib.maaso_split_by_slo(None, None, 0, None, None, None, None, None, None) == -1

@@ -344,6 +344,51 @@ def test_score_config_shapes():
     check_score(full, window=0, weights=SCORE_WEIGHTS[1:2], sampled=picks[:2])
 
 
+@pytest.mark.parametrize("seed,n_cand,i_pad,n_req,window,cuts", [
+    (81, 14, 24, 3000, 128, (0, 1100, 3000)),       # R_t, R_l and all of R, as Alg. 2 asks
+    (82, 9, 64, 2600, 0, (0, 700, 2600)),           # static: the sets' single windows differ in size
+    (83, 5, 8, 1500, 700, (0, 0, 1500)),            # an empty set among them
+    (84, 21, 3, 900, 40, (0, 450, 900)),
+])
+def test_score_request_sets(seed, n_cand, i_pad, n_req, window, cuts):
+    """One launch over several request sets (Alg. 2 scores every deployment against R_t, R_l and R)
+    gives, set by set, the oracle's result for that set alone."""
+    w = W.stressed(W.random_small(seed, n_cand, i_pad, n_req, n_slo=3, pen_kappa=0.5), seed=seed,
+                   deadline_scale=0.2)
+    a, m, b = cuts
+    ranges = [(a, m), (m, b), (a, b), (m, m + (b - m) // 3)]
+    alpha, beta, gt, gl = SCORE_WEIGHTS[0]
+    dw = binding.DeviceWorkload(w)
+    try:
+        for n_sets in (4, 3, 1):
+            print(f"score sets {w.name} C={n_cand} I={i_pad} R={n_req} window={window} "
+                  f"ranges={ranges[:n_sets]}", flush=True)
+            outs = dw.score_sets(ranges[:n_sets], alpha, beta, gt, gl, window=window)
+            torch.cuda.synchronize()
+            assert binding.maaso_ctx_device_status(dw.ctx) == 0
+            for (lo, hi), out in zip(ranges, outs):
+                ref = oracle.placement_score(w.with_requests(lo, hi), alpha, beta, gt, gl, window=window)
+                for k in ("sat_count", "phi_s", "phi_t", "phi_l", "score"):
+                    got = u32(out[k]) if out[k].dtype == torch.int32 else out[k].cpu().numpy()
+                    assert np.array_equal(got, ref[k]), (k, lo, hi)
+                assert int(u32(out["best_cand"])[0]) == ref["best_cand"]
+        assert np.array_equal(dw.occ.cpu().numpy(), w.occ)
+    finally:
+        dw.close()
+
+
+def test_score_request_sets_rejects_bad_arguments():
+    w = W.random_small(85, 3, 4, 200, n_slo=2)
+    dw = binding.DeviceWorkload(w)
+    try:
+        with pytest.raises(binding.MaasoError):
+            dw.score_sets([], 4.0, 0.3, 512.0, 0.5)
+        with pytest.raises(binding.MaasoError):
+            dw.score_sets([(0, 10)] * 5, 4.0, 0.3, 512.0, 0.5)
+    finally:
+        dw.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # profiler: least-squares fit of the throughput-decay function (Sec. IV-B, Eq. 1)
 # ------------------------------------------------------------------------------------------------
