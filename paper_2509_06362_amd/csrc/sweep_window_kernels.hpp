@@ -173,9 +173,12 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
         idx[v] = (val > best[v]) ? (int32_t)j : idx[v];
         best[v] = max_no_nan(best[v], val);
       };
-      // With few requests per lane a wavefront has little to overlap an LDS read with (short windows
-      // leave a SIMD two or three wavefronts), so U records are fetched per trip before any is used.
-      constexpr uint32_t U = (V == 1) ? 4u : (V == 2 ? 2u : 1u);
+      // U records are fetched per trip before any is used.  With one request per lane a wavefront has
+      // little else to overlap an LDS read with (short windows leave a SIMD a few wavefronts);
+      // with four, a longer trip also spreads the address bookkeeping of the per-class margin reads
+      // over more triples.  Measured: V = 1: U = 4 beats 1 and 8; V = 4: U = 4 beats 1 and 2
+      // (128 registers, still four wavefronts per SIMD).
+      constexpr uint32_t U = (V == 2) ? 2u : 4u;
       uint32_t j = 0;
       for (; j + U <= n; j += U) {
         float4 r[U];
