@@ -35,12 +35,16 @@ HBM_PEAK_GBS = 8000.0
 
 # Sweep, per (request, instance) pair that reaches the latency loop: prefill fma, queue-wait add, and
 # half of a three-input minimum (one v_min3_f32 folds two pairs into the running minimum): 2.5
-# instruction slots per pair is the least this instruction set needs, so that is the algorithmic
-# figure the roofline fraction uses.  Counted as operations (fma, add, min) a pair is 3; that figure
-# is reported beside it and can exceed the slot fraction by 3 / 2.5.
-SWEEP_LANEOPS_PER_PAIR = 2.5
+# instruction slots per pair is the least this instruction set needs.  Where an instance's queue wait
+# is exactly zero (fresh instances, the placer's usual candidates) the add changes nothing and the
+# kernel leaves it out: 1.5 slots.  The roofline fraction uses these figures with the kernel's own
+# counts of both kinds of pair.  Counted as operations of the model (fma, add, min) a pair is 3; that
+# figure is reported beside it and exceeds the slot fraction.
+SWEEP_SLOTS_PER_PAIR = 2.5
+SWEEP_SLOTS_PER_PAIR_NO_WAIT = 1.5
 SWEEP_OPERATIONS_PER_PAIR = 3
-SWEEP_FLOP_PER_PAIR = 4
+SWEEP_FLOP_PER_PAIR = 4          # fma = 2
+SWEEP_FLOP_PER_PAIR_NO_WAIT = 3
 # Distributor, per triple: 2 fma, 1 add, 2 sub, 2 mul, 2 min, 1 compare, 2 selects (the between-token
 # margin comes from a per-(class, instance) table).
 ASSIGN_LANEOPS_PER_TRIPLE = 12
@@ -60,8 +64,8 @@ KERNEL_SOURCES = {
     "assign_static_kernel": ("device_model.hpp", "sweep_kernels.hpp", "assign_kernels.hpp"),
 }
 TRAFFIC = {
-    "cfg1_placer_sweep": ("sweep_kernel", 6.714e6, "7ec14cf42107bd43"),
-    "streaming_i4": ("assign_static_kernel", 1.1410e9, "ee1665c679e49c7a"),
+    "cfg1_placer_sweep": ("sweep_kernel", 5.711e6, "e216885261b4244c"),
+    "streaming_i4": ("assign_static_kernel", 1.1410e9, "1217bb17183f7cc8"),
 }
 
 
@@ -353,22 +357,27 @@ def main() -> int:
             "kernel_triples_per_s": triples_sweep / k_avg_s,
         }
     elif kind == "sweep":
-        pairs = binding.maaso_ctx_sweep_evaluated(dw.ctx)  # pairs that reached the latency loop
-        ops = SWEEP_LANEOPS_PER_PAIR * pairs
+        # pairs that reached the latency loop, and those of them on an instance without a wait
+        pairs, pairs_nowait = binding.maaso_ctx_sweep_evaluated(dw.ctx, split=True)
+        ops = (SWEEP_SLOTS_PER_PAIR * (pairs - pairs_nowait)
+               + SWEEP_SLOTS_PER_PAIR_NO_WAIT * pairs_nowait)
+        flop = (SWEEP_FLOP_PER_PAIR * (pairs - pairs_nowait)
+                + SWEEP_FLOP_PER_PAIR_NO_WAIT * pairs_nowait)
         roofline = {
             "kernel": "sweep_kernel", "bound": "alu",
             "achieved": ops / k_avg_s / 1e12, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
             "frac": ops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS, "traffic": measured_traffic(w.name),
             "kernel_ms": k_avg_s * 1e3, "launches_timed": k_n,
-            "laneops_per_pair": SWEEP_LANEOPS_PER_PAIR,
+            "slots_per_pair": SWEEP_SLOTS_PER_PAIR,
+            "slots_per_pair_without_wait": SWEEP_SLOTS_PER_PAIR_NO_WAIT,
             "operations_per_pair": SWEEP_OPERATIONS_PER_PAIR,
             "frac_counting_operations": SWEEP_OPERATIONS_PER_PAIR * pairs / k_avg_s / 1e12
             / VALU_PEAK_TLANEOPS,
-            "pairs_evaluated": pairs, "valid_triples": triples_sweep,
+            "pairs_evaluated": pairs, "pairs_without_wait": pairs_nowait,
+            "valid_triples": triples_sweep,
             "settled_per_class_instance": triples_sweep - pairs,
-            "tflops": SWEEP_FLOP_PER_PAIR * pairs / k_avg_s / 1e12,
-            "frac_of_fp32_vector_peak": SWEEP_FLOP_PER_PAIR * pairs / k_avg_s / 1e12
-            / FP32_VECTOR_PEAK_TFLOPS,
+            "tflops": flop / k_avg_s / 1e12,
+            "frac_of_fp32_vector_peak": flop / k_avg_s / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
             "kernel_triples_per_s": triples_sweep / k_avg_s,
         }
         # the metric also asks for the fraction of the HBM roofline: each request record (9 B), each

@@ -145,8 +145,11 @@ int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches
 /* Synchronises the device and returns how many (request, instance) pairs the context's most recent
  * maaso_placement_sweep evaluated in its latency loop, i.e. the valid triples minus those whose
  * instance already fails the between-token deadline of the request's class (they are settled per
- * (class, instance) and never reach the loop).  0 if no sweep has run.  Errors: INVALID_ARG, HIP. */
-int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs);
+ * (class, instance) and never reach the loop).  *pairs_without_wait (may be NULL) receives how many
+ * of them belong to an instance whose queue wait is exactly zero: for those the sweep leaves the
+ * addition of the wait out (0 + x = x), so they cost it less.  Both 0 if no sweep has run.
+ * Errors: INVALID_ARG, HIP. */
+int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs, uint64_t* pairs_without_wait);
 
 /* Requests as structure-of-arrays streams (Sec. IV-C: a request r decodes S_r tokens before its
  * deadline; Sec. V-A: arrivals over time).  DEVICE pointers, read only. */

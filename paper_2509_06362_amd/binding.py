@@ -97,7 +97,8 @@ def load_library() -> C.CDLL:
         lib.maaso_ctx_kernel_timing.argtypes = [C.c_void_p, C.c_int]
         lib.maaso_ctx_kernel_elapsed.argtypes = [C.c_void_p, C.POINTER(C.c_float),
                                                  C.POINTER(C.c_uint32)]
-        lib.maaso_ctx_sweep_evaluated.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
+        lib.maaso_ctx_sweep_evaluated.argtypes = [C.c_void_p, C.POINTER(C.c_uint64),
+                                                  C.POINTER(C.c_uint64)]
         lib.maaso_score_assign.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                            C.POINTER(Params), C.POINTER(AssignOut), C.c_void_p]
         lib.maaso_score_assign_selected.argtypes = [C.c_void_p, C.POINTER(Placements), C.c_void_p,
@@ -230,12 +231,13 @@ def maaso_ctx_kernel_elapsed(ctx: Context):
     return float(ms.value), int(n.value)
 
 
-def maaso_ctx_sweep_evaluated(ctx: Context) -> int:
-    """(request, instance) pairs the last sweep evaluated in its latency loop (synchronises)."""
-    v = C.c_uint64(0)
-    _check(load_library().maaso_ctx_sweep_evaluated(ctx.handle, C.byref(v)),
+def maaso_ctx_sweep_evaluated(ctx: Context, split: bool = False):
+    """(request, instance) pairs the last sweep evaluated in its latency loop (synchronises); with
+    `split` also how many of them belong to an instance without a queue wait."""
+    v, z = C.c_uint64(0), C.c_uint64(0)
+    _check(load_library().maaso_ctx_sweep_evaluated(ctx.handle, C.byref(v), C.byref(z)),
            "maaso_ctx_sweep_evaluated")
-    return int(v.value)
+    return (int(v.value), int(z.value)) if split else int(v.value)
 
 
 def _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks) -> Requests:

@@ -318,9 +318,9 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
     rc = MAASO_E_NOMEM;
   if (rc == MAASO_OK && !hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->status), kSmallBytes))) rc = MAASO_E_NOMEM;
   if (rc == MAASO_OK) {
-    // one small allocation, in 32-bit words: [0] status, [16..31] class counts, [32..33] evaluated
-    // pairs of the last sweep, [34] delivered-blocks counter and [36..37] admitted-count
-    // accumulator of the static distributor
+    // one small allocation, in 32-bit words: [0] status, [16..31] class counts, [32..35] evaluated
+    // pairs of the last sweep (all; those without a wait), [36..37] admitted-count accumulator and
+    // delivered-blocks ticket of the static distributor
     ctx->cls_count = ctx->status + 16;
     if (!hip_ok(hipMemcpy(ctx->tab, host, (size_t)3 * cells * 4, hipMemcpyHostToDevice)) ||
         !hip_ok(hipMemset(ctx->status, 0, kSmallBytes)))
@@ -424,8 +424,10 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   if (Q == 0) Q = R >= (1u << 17) ? 16u : (R >= (1u << 14) ? 8u : (R >= (1u << 12) ? 4u : 2u));
   uint32_t G = (uint32_t)kGroupSlots / I;
   if (G > (uint32_t)kMaxGroup) G = kMaxGroup;
-  // measured: items of about 128 instance slots balance best across the persistent blocks
-  uint32_t g_want = ctx->sweep_group ? ctx->sweep_group : (128u / I ? 128u / I : 1u);
+  // measured: items of about 256 instance slots (8 candidates of 32 slots a third full: 105 us against
+  // 110 with 4 or 16; full slots: 4 and 8 equal; 128 slots: 1, 2 equal) balance the per-item
+  // barrier against the tail of the dynamic queues
+  uint32_t g_want = ctx->sweep_group ? ctx->sweep_group : (256u / I ? 256u / I : 1u);
   if (g_want < G) G = g_want;
   const uint32_t n_items = (C + G - 1) / G;
   const uint32_t tile = (uint32_t)kSweepThreads * Q;
@@ -446,8 +448,8 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   auto up256 = [](size_t x) { return (x + 255) & ~size_t(255); };
   const size_t lbuf_bytes = up256((size_t)K * (R ? R : 1u) * sizeof(float));
   const size_t recs_bytes = up256((size_t)C * I * sizeof(float4));
-  // queue heads, then one 8-byte evaluated-pairs word per sweep block
-  const size_t queue_words = (size_t)nrb_max * 8u + 2u * (size_t)blocks64;
+  // queue heads, then two 8-byte evaluated-pairs words per sweep block
+  const size_t queue_words = (size_t)nrb_max * 8u + 4u * (size_t)blocks64;
   const size_t queue_bytes = up256(queue_words * sizeof(uint32_t));
   rc = ensure_workspace(ctx, lbuf_bytes + recs_bytes + queue_bytes);
   if (rc != MAASO_OK) return rc;
@@ -888,16 +890,18 @@ int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches
   return MAASO_OK;
 }
 
-int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs) {
+int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs, uint64_t* pairs_without_wait) {
   if (!ctx || !pairs) return MAASO_E_INVALID_ARG;
   *pairs = 0;
+  if (pairs_without_wait) *pairs_without_wait = 0;
   if (!ctx->last_evaluated) return MAASO_OK;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
-  unsigned long long v = 0;
+  unsigned long long v[2] = {0, 0};
   if (!hip_ok(hipDeviceSynchronize())) return MAASO_E_HIP;
-  if (!hip_ok(hipMemcpy(&v, ctx->last_evaluated, sizeof(v), hipMemcpyDeviceToHost))) return MAASO_E_HIP;
-  *pairs = v;
+  if (!hip_ok(hipMemcpy(v, ctx->last_evaluated, sizeof(v), hipMemcpyDeviceToHost))) return MAASO_E_HIP;
+  *pairs = v[0];
+  if (pairs_without_wait) *pairs_without_wait = v[1];
   return MAASO_OK;
 }
 

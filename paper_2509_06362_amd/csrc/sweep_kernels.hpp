@@ -212,14 +212,14 @@ struct SweepArgs {
   uint32_t nrb_max;  // request-tile slots of the grid (>= tiles that exist)
   uint32_t* queues;  // [nrb_max][8] next position of each (request tile, XCD) queue
   uint32_t* sat_count;
-  unsigned long long* evaluated;  // [gridDim.x] per block: (request, instance) pairs that reached
+  unsigned long long* evaluated;  // [2][gridDim.x] per block: (request, instance) pairs that reached
                                   // the latency loop (zero on entry; summed by the finalize kernel)
 };
 
 template <int Q>
-__global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a) {
+__device__ __forceinline__ void sweep_body(const SweepArgs& a) {
   __shared__ float4 lists[2][kGroupSlots];
-  __shared__ uint32_t lens[3][kMaxGroup];
+  __shared__ uint32_t lens[3][2][kMaxGroup];  // [buffer][0: records without a wait, 1: with][candidate]
   __shared__ uint32_t blk_cnt[2][kSweepWaves][kMaxGroup];
   __shared__ uint32_t items[2];
 
@@ -249,24 +249,25 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
   const float Dt = a.d_ttft[k_b];
   const float Db = a.d_tbt[k_b];
 
+  // A lane without a request carries an infinite prompt length: its latency on every instance is
+  // +inf (the per-token prefill cost is positive), so it never counts and needs no mask.
   float L[Q];
-  uint64_t vmask[Q];
-  bool any_req = false;
+  uint32_t wave_reqs = 0;  // valid requests held by this wavefront
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     const uint32_t idx = off + wave * (kWave * Q) + q * kWave + lane;
     const bool ok = idx < n_k;
-    L[q] = ok ? a.lbuf[(size_t)k_b * a.n_req + idx] : 0.0f;
-    vmask[q] = __ballot(ok);
-    any_req = any_req || vmask[q] != 0ull;
+    L[q] = ok ? a.lbuf[(size_t)k_b * a.n_req + idx] : INFINITY;
+    wave_reqs += (uint32_t)__popcll(__ballot(ok));
   }
+  const bool any_req = wave_reqs != 0u;
 
   uint32_t* queue = a.queues + (size_t)rb * 8u + xcd;
   if (tid == 0u) {
     items[0] = xcd + 8u * atomicAdd(queue, 1u);
     items[1] = xcd + 8u * atomicAdd(queue, 1u);
   }
-  for (uint32_t i = tid; i < 3u * kMaxGroup; i += kSweepThreads) (&lens[0][0])[i] = 0u;
+  for (uint32_t i = tid; i < 6u * kMaxGroup; i += kSweepThreads) (&lens[0][0][0])[i] = 0u;
   __syncthreads();
   // uniform by construction; held in scalar registers so that the candidate loop is a scalar loop
   uint32_t cur = __builtin_amdgcn_readfirstlane(items[0]);
@@ -293,8 +294,11 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
 #pragma unroll
     for (int u = 0; u < kSlotsPerThread; ++u)
       if (rec[u].w <= Db) {  // between-token deadline of the block's class
-        const uint32_t pos = atomicAdd(&lens[it % 3u][s_cl[u]], 1u);
-        lists[it & 1u][s_cl[u] * I + pos] = rec[u];
+        // records whose queue wait is exactly zero (fresh instances: the placer's usual candidates)
+        // fill the candidate's segment from the front, the others from the back
+        const bool nowait = rec[u].z == 0.0f;
+        const uint32_t pos = atomicAdd(&lens[it % 3u][nowait ? 0 : 1][s_cl[u]], 1u);
+        lists[it & 1u][s_cl[u] * I + (nowait ? pos : I - 1u - pos)] = rec[u];
       }
   };
 
@@ -305,10 +309,7 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
   }
   __syncthreads();
 
-  uint32_t wave_reqs = 0;  // valid requests held by this wavefront
-#pragma unroll
-  for (int q = 0; q < Q; ++q) wave_reqs += (uint32_t)__popcll(vmask[q]);
-  unsigned long long evaluated = 0ull;
+  unsigned long long evaluated = 0ull, evaluated_nowait = 0ull;
 
   uint32_t prev_c0 = 0, prev_n = 0;
   for (uint32_t it = 0;; ++it) {
@@ -329,46 +330,74 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
     uint32_t acc = 0;  // lane g holds this wavefront's count for candidate c0 + g
     if (any_req) {
       const float4* gl = lists[it & 1u];
-      const uint32_t* glen = lens[it % 3u];
-      uint32_t n_ahead = glen[0];
-      uint32_t n_sum = 0;  // records this wavefront walks in this group
+      const uint32_t* glen0 = lens[it % 3u][0];
+      const uint32_t* glen1 = lens[it % 3u][1];
+      uint32_t n0_ahead = glen0[0], n1_ahead = glen1[0];
+      uint32_t n_sum = 0, n0_sum = 0;  // records this wavefront walks in this group
       for (uint32_t g = 0; g < g_cands; ++g) {
-        const uint32_t n = __builtin_amdgcn_readfirstlane(n_ahead);
-        n_ahead = glen[min(g + 1u, G - 1u)];
-        n_sum += n;
+        const uint32_t n0 = __builtin_amdgcn_readfirstlane(n0_ahead);
+        const uint32_t n1 = __builtin_amdgcn_readfirstlane(n1_ahead);
+        n0_ahead = glen0[min(g + 1u, G - 1u)];
+        n1_ahead = glen1[min(g + 1u, G - 1u)];
+        n_sum += n0 + n1;
+        n0_sum += n0;
         const float4* lst = gl + g * I;
+        const float4* wlst = lst + (I - n1);  // the records with a wait sit at the segment's end
         uint32_t cnt = 0;
-        if (n != 0u) {
+        if (n0 + n1 != 0u) {
           float m[Q];  // smallest first-token latency so far; the first record initialises it
-          {
-            const float4 r = lst[0];
+          const float4* p0 = lst;   // next record without a wait
+          const float4* p1 = wlst;  // next record with one
+          uint32_t left0 = n0, left1 = n1;
+          if (n0 != 0u) {
+            const float4 r = *p0++;
+            --left0;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) m[q] = fmaf(r.x, L[q], r.y);
+          } else {
+            const float4 r = *p1++;
+            --left1;
 #pragma unroll
             for (int q = 0; q < Q; ++q) m[q] = r.z + fmaf(r.x, L[q], r.y);
           }
-          uint32_t i = 1;
-          for (; i + 1u < n; i += 2u) {  // two records per trip: one three-way minimum serves both
-            const float4 r = lst[i];
-            const float4 s = lst[i + 1u];
+          // wait == +0: ttft = 0 + prefill = prefill exactly (the prefill time is positive), so the
+          // add is left out - two fma and one three-way minimum per two records
+          for (uint32_t t = left0 >> 1; t != 0u; --t, p0 += 2) {
+            const float4 r = p0[0];
+            const float4 u = p0[1];
 #pragma unroll
             for (int q = 0; q < Q; ++q)
-              m[q] = min3_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y), s.z + fmaf(s.x, L[q], s.y));
+              m[q] = min3_no_nan(m[q], fmaf(r.x, L[q], r.y), fmaf(u.x, L[q], u.y));
           }
-          if (i < n) {
-            const float4 r = lst[i];
+          if (left0 & 1u) {
+            const float4 r = p0[0];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) m[q] = min_no_nan(m[q], fmaf(r.x, L[q], r.y));
+          }
+          for (uint32_t t = left1 >> 1; t != 0u; --t, p1 += 2) {  // one three-way minimum serves two records
+            const float4 r = p1[0];
+            const float4 u = p1[1];
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+              m[q] = min3_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y), u.z + fmaf(u.x, L[q], u.y));
+          }
+          if (left1 & 1u) {
+            const float4 r = p1[0];
 #pragma unroll
             for (int q = 0; q < Q; ++q) m[q] = min_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y));
           }
 #pragma unroll
-          for (int q = 0; q < Q; ++q) cnt += (uint32_t)__popcll(__ballot(m[q] <= Dt) & vmask[q]);
+          for (int q = 0; q < Q; ++q) cnt += (uint32_t)__popcll(__ballot(m[q] <= Dt));
         }
         acc = (lane == g) ? cnt : acc;
       }
       evaluated += (unsigned long long)n_sum * wave_reqs;
+      evaluated_nowait += (unsigned long long)n0_sum * wave_reqs;
     }
     blk_cnt[it & 1u][wave][lane] = acc;
 
     file_group(rec, it + 1u);
-    if (tid < kMaxGroup) lens[(it + 2u) % 3u][tid] = 0u;  // last read while scoring group it-1
+    if (tid < 2u * kMaxGroup) (&lens[(it + 2u) % 3u][0][0])[tid] = 0u;  // last read while scoring group it-1
     if (tid == 0u) items[it & 1u] = after_next;
     __syncthreads();
     prev_c0 = c0;
@@ -385,10 +414,25 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
     }
   }
   // one word per block, no atomics: thousands of same-address atomics at the kernel's end are slow
-  __shared__ unsigned long long wave_eval[kSweepWaves];
-  if (lane == 0u) wave_eval[wave] = evaluated;
+  __shared__ unsigned long long wave_eval[2][kSweepWaves];
+  if (lane == 0u) { wave_eval[0][wave] = evaluated; wave_eval[1][wave] = evaluated_nowait; }
   __syncthreads();
-  if (tid == 0u) a.evaluated[blockIdx.x] = wave_eval[0] + wave_eval[1] + wave_eval[2] + wave_eval[3];
+  if (tid < 2u)  // all pairs, then those of them whose instance has no wait
+    a.evaluated[(size_t)tid * gridDim.x + blockIdx.x] =
+        wave_eval[tid][0] + wave_eval[tid][1] + wave_eval[tid][2] + wave_eval[tid][3];
+}
+
+template <int Q>
+__global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a) {
+  sweep_body<Q>(a);
+}
+
+// 16 requests per lane: held to 96 registers, i.e. five wavefronts per SIMD - left alone the
+// compiler takes 99, only four fit, and the variant loses what it gains.
+template <>
+__global__ __launch_bounds__(kSweepThreads) __attribute__((amdgpu_num_vgpr(96)))
+void sweep_kernel<16>(const SweepArgs a) {
+  sweep_body<16>(a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -403,25 +447,26 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(const uint32_t* __
                                                               uint32_t n_parts,
                                                               unsigned long long* __restrict__ eval_total) {
   __shared__ unsigned long long best[16];
-  __shared__ unsigned long long esum[16];
+  __shared__ unsigned long long esum[2][16];
   if (threadIdx.x < kMaxSlo) cls_count[threadIdx.x] = 0u;
   // both loops fetch eight elements per thread at a time: the kernel is one block, so its duration is
   // the number of dependent trips to memory
   constexpr uint32_t kBatch = 8;
-  {
+  for (uint32_t half = 0; half < 2u; ++half) {  // all pairs, then the pairs without a wait
+    const unsigned long long* parts = eval_parts + (size_t)half * n_parts;
     unsigned long long e = 0ull;
     for (uint32_t i0 = threadIdx.x; i0 < n_parts; i0 += kBatch * blockDim.x) {
       unsigned long long v[kBatch];
 #pragma unroll
       for (uint32_t u = 0; u < kBatch; ++u) {
         const uint32_t i = i0 + u * blockDim.x;
-        v[u] = i < n_parts ? eval_parts[i] : 0ull;
+        v[u] = i < n_parts ? parts[i] : 0ull;
       }
 #pragma unroll
       for (uint32_t u = 0; u < kBatch; ++u) e += v[u];
     }
     for (int d = 32; d >= 1; d >>= 1) e += __shfl_xor(e, d);
-    if ((threadIdx.x & 63u) == 0u) esum[threadIdx.x >> 6] = e;
+    if ((threadIdx.x & 63u) == 0u) esum[half][threadIdx.x >> 6] = e;
   }
   const float fr = (float)n_req;
   unsigned long long key = 0ull;  // (count << 32) | ~index: max key = max count, then min index
@@ -451,10 +496,10 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(const uint32_t* __
     for (uint32_t w = 1; w < (blockDim.x >> 6); ++w) key = best[w] > key ? best[w] : key;
     *best_cand = ~(uint32_t)(key & 0xffffffffull);
   }
-  if (threadIdx.x == 0) {
+  if (threadIdx.x < 2u) {
     unsigned long long e = 0ull;
-    for (uint32_t w = 0; w < (blockDim.x >> 6); ++w) e += esum[w];
-    *eval_total = e;
+    for (uint32_t w = 0; w < (blockDim.x >> 6); ++w) e += esum[threadIdx.x][w];
+    eval_total[threadIdx.x] = e;
   }
 }
 

@@ -100,7 +100,7 @@ def test_null_context_is_rejected(lib):
     assert lib.maaso_ctx_set_wait_limit(None, 1) == -1
     assert lib.maaso_ctx_kernel_timing(None, 1) == -1
     assert lib.maaso_ctx_kernel_elapsed(None, None, None) == -1
-    assert lib.maaso_ctx_sweep_evaluated(None, None) == -1
+    assert lib.maaso_ctx_sweep_evaluated(None, None, None) == -1
     lib.maaso_ctx_destroy(None)
 
 

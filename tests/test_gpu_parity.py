@@ -878,19 +878,27 @@ def test_assign_static_unaligned_arrays_take_the_scalar_path():
 
 def test_sweep_reports_the_pairs_it_evaluated():
     """Pairs that reach the latency loop = sum over (candidate, class) of the instances whose
-    between-token latency meets the class deadline, times the requests of that class."""
+    between-token latency meets the class deadline, times the requests of that class; those of an
+    instance without a queue wait are reported separately (the sweep skips their addition)."""
     w = W.stressed(W.config4(n_cand=40, n_req=5000), seed=2)
+    # every third instance slot fresh (no queued prefill, nothing running): a mix of both kinds
+    fresh = (np.arange(w.i_pad)[None, :] + np.arange(w.n_cand)[:, None]) % 3 == 0
+    w = W.replace(w, occ=np.where(fresh, 0, w.occ).astype(w.occ.dtype),
+                  q_ticks=np.where(fresh, 0, w.q_ticks).astype(w.q_ticks.dtype))
     dw = binding.DeviceWorkload(w)
-    dw.sweep()
-    got = binding.maaso_ctx_sweep_evaluated(dw.ctx)
+    cnt, _, _ = dw.sweep()
+    got, got_nowait = binding.maaso_ctx_sweep_evaluated(dw.ctx, split=True)
     per_class = np.bincount(w.slo_class, minlength=w.n_slo).astype(np.int64)
-    want = 0
+    want = want_nowait = 0
     for c in range(w.n_cand):
-        tbt = oracle.stage(w, c)["tbt"]
+        st = oracle.stage(w, c)
         for k in range(w.n_slo):
-            want += int((tbt <= w.d_tbt[k]).sum()) * int(per_class[k])
-    assert got == want
-    assert 0 < got < w.valid_triples()
+            ok = st["tbt"] <= w.d_tbt[k]
+            want += int(ok.sum()) * int(per_class[k])
+            want_nowait += int((ok & (st["wait"] == 0)).sum()) * int(per_class[k])
+    assert (got, got_nowait) == (want, want_nowait)
+    assert 0 < got_nowait < got < w.valid_triples()
+    assert np.array_equal(u32(cnt), oracle.placement_sweep(w)["sat_count"])
     dw.close()
 
 
