@@ -876,6 +876,30 @@ def test_assign_static_unaligned_arrays_take_the_scalar_path():
     dw.close()
 
 
+@pytest.mark.parametrize("seed,n_cand,i_pad,n_req,fresh_share", [
+    (91, 40, 32, 5000, 0.5), (92, 25, 7, 3000, 0.3), (93, 12, 128, 2500, 0.8),
+    (94, 6, 256, 1200, 0.1), (95, 60, 1, 900, 0.5), (96, 33, 48, 20000, 0.97),
+])
+def test_sweep_with_fresh_and_loaded_instances_mixed(seed, n_cand, i_pad, n_req, fresh_share):
+    """Instances without a queue wait and instances with one inside the same candidates, in every
+    proportion and with odd and even numbers of each: the sweep walks them in two loops."""
+    base = W.stressed(W.random_small(seed, n_cand, i_pad, n_req, n_slo=3, pen_kappa=0.5), seed=seed,
+                      deadline_scale=0.04)   # tight: a fresh instance serves short prompts only
+    rng = np.random.default_rng(seed)
+    fresh = rng.random((n_cand, i_pad)) < fresh_share
+    w = W.replace(base, occ=np.where(fresh, 0, base.occ).astype(base.occ.dtype),
+                  q_ticks=np.where(fresh, 0, base.q_ticks).astype(base.q_ticks.dtype))
+    cnt = check_sweep(w, shapes=((0, 0, 0), (2, 1, 1), (16, 3, 2)), threshold=True)
+    assert (cnt > 0).any() and (cnt < n_req).any()   # neither everything nor nothing is served
+    dw = binding.DeviceWorkload(w)
+    try:
+        dw.sweep()
+        pairs, nowait = binding.maaso_ctx_sweep_evaluated(dw.ctx, split=True)
+        assert 0 < nowait < pairs
+    finally:
+        dw.close()
+
+
 def test_sweep_reports_the_pairs_it_evaluated():
     """Pairs that reach the latency loop = sum over (candidate, class) of the instances whose
     between-token latency meets the class deadline, times the requests of that class; those of an
