@@ -155,8 +155,10 @@ __global__ __launch_bounds__(256) void sweep_prep_kernel(const PrepArgs a) {
   float* tab = reinterpret_cast<float*>(smem);
   for (uint32_t i = tid; i < 3u * a.cells; i += 256u) tab[i] = a.tab[i];
   const uint32_t sb = blockIdx.x - a.n_bucket_blocks;
-  if (sb == 0u)  // queue heads, then the per-block words that count evaluated pairs
-    for (uint32_t i = tid; i < a.n_queues; i += 256u) a.queues[i] = 0u;
+  {  // queue heads, then the per-block words that count evaluated pairs: every stage block clears a slice
+    const uint32_t n_stage = gridDim.x - a.n_bucket_blocks;
+    for (uint32_t i = sb * 256u + tid; i < a.n_queues; i += n_stage * 256u) a.queues[i] = 0u;
+  }
   __syncthreads();
   const uint64_t n_slots = (uint64_t)a.n_cand * a.i_pad;
   const uint64_t base = (uint64_t)sb * kStageSlotsPerBlock;
@@ -332,13 +334,12 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a) {
       const float4* gl = lists[it & 1u];
       const uint32_t* glen0 = lens[it % 3u][0];
       const uint32_t* glen1 = lens[it % 3u][1];
-      uint32_t n0_ahead = glen0[0], n1_ahead = glen1[0];
+      // lane g fetches the list lengths of candidate g once; the loop reads them lane by lane
+      const uint32_t len0 = glen0[lane], len1 = glen1[lane];
       uint32_t n_sum = 0, n0_sum = 0;  // records this wavefront walks in this group
       for (uint32_t g = 0; g < g_cands; ++g) {
-        const uint32_t n0 = __builtin_amdgcn_readfirstlane(n0_ahead);
-        const uint32_t n1 = __builtin_amdgcn_readfirstlane(n1_ahead);
-        n0_ahead = glen0[min(g + 1u, G - 1u)];
-        n1_ahead = glen1[min(g + 1u, G - 1u)];
+        const uint32_t n0 = (uint32_t)__builtin_amdgcn_readlane((int)len0, (int)g);
+        const uint32_t n1 = (uint32_t)__builtin_amdgcn_readlane((int)len1, (int)g);
         n_sum += n0 + n1;
         n0_sum += n0;
         const float4* lst = gl + g * I;
@@ -449,13 +450,25 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(const uint32_t* __
   __shared__ unsigned long long best[16];
   __shared__ unsigned long long esum[2][16];
   if (threadIdx.x < kMaxSlo) cls_count[threadIdx.x] = 0u;
-  // both loops fetch eight elements per thread at a time: the kernel is one block, so its duration is
-  // the number of dependent trips to memory
+  // The kernel is one block, so its duration is the number of dependent trips to memory: the first
+  // batch of every array (eight elements per thread each) is requested before anything is used.
   constexpr uint32_t kBatch = 8;
+  const uint32_t stride = kBatch * blockDim.x;
+  unsigned long long v0[kBatch], v1[kBatch];
+  uint32_t n[kBatch];
+#pragma unroll
+  for (uint32_t u = 0; u < kBatch; ++u) {
+    const uint32_t i = threadIdx.x + u * blockDim.x;
+    v0[u] = i < n_parts ? eval_parts[i] : 0ull;
+    v1[u] = i < n_parts ? eval_parts[(size_t)n_parts + i] : 0ull;
+    n[u] = i < n_cand ? sat_count[i] : 0u;
+  }
   for (uint32_t half = 0; half < 2u; ++half) {  // all pairs, then the pairs without a wait
     const unsigned long long* parts = eval_parts + (size_t)half * n_parts;
     unsigned long long e = 0ull;
-    for (uint32_t i0 = threadIdx.x; i0 < n_parts; i0 += kBatch * blockDim.x) {
+#pragma unroll
+    for (uint32_t u = 0; u < kBatch; ++u) e += half ? v1[u] : v0[u];
+    for (uint32_t i0 = threadIdx.x + stride; i0 < n_parts; i0 += stride) {
       unsigned long long v[kBatch];
 #pragma unroll
       for (uint32_t u = 0; u < kBatch; ++u) {
@@ -470,12 +483,13 @@ __global__ __launch_bounds__(1024) void sweep_finalize_kernel(const uint32_t* __
   }
   const float fr = (float)n_req;
   unsigned long long key = 0ull;  // (count << 32) | ~index: max key = max count, then min index
-  for (uint32_t c0 = threadIdx.x; c0 < n_cand; c0 += kBatch * blockDim.x) {
-    uint32_t n[kBatch];
+  for (uint32_t c0 = threadIdx.x; c0 < n_cand; c0 += stride) {
+    if (c0 != threadIdx.x) {
 #pragma unroll
-    for (uint32_t u = 0; u < kBatch; ++u) {
-      const uint32_t c = c0 + u * blockDim.x;
-      n[u] = c < n_cand ? sat_count[c] : 0u;
+      for (uint32_t u = 0; u < kBatch; ++u) {
+        const uint32_t c = c0 + u * blockDim.x;
+        n[u] = c < n_cand ? sat_count[c] : 0u;
+      }
     }
 #pragma unroll
     for (uint32_t u = 0; u < kBatch; ++u) {
