@@ -64,8 +64,8 @@ KERNEL_SOURCES = {
     "assign_static_kernel": ("device_model.hpp", "sweep_kernels.hpp", "assign_kernels.hpp"),
 }
 TRAFFIC = {
-    "cfg1_placer_sweep": ("sweep_kernel", 5.695e6, "20e70b188d19de9c"),
-    "streaming_i4": ("assign_static_kernel", 1.1410e9, "c502c73315f99fc1"),
+    "cfg1_placer_sweep": ("sweep_kernel", 5.695e6, "4224fb415c88948b"),
+    "streaming_i4": ("assign_static_kernel", 1.1410e9, "4cf95a22c442d8f7"),
 }
 
 

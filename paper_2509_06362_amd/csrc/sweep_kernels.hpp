@@ -12,8 +12,9 @@
 //      queue.  For each group the block filters the records on the between-token deadline of its
 //      class into compact per-candidate lists in LDS (double-buffered, loads for the next group are
 //      issued before the current group is scored, one barrier per group), then every wavefront
-//      streams the lists with broadcast LDS reads: per (request, instance) one fused multiply-add
-//      (prefill), one add (queue wait), one min.
+//      streams the lists with broadcast LDS reads, two records per trip: per (request, instance) one
+//      fused multiply-add (prefill), one add (queue wait) and half of a three-input min.  Records
+//      whose queue wait is exactly zero are listed apart and walked without the add (0 + x = x).
 //   3. sweep_finalize_kernel - ratio = count / R and the best candidate (lowest index on ties).
 //
 // A request is satisfied iff min_j ttft_j <= D_ttft over the listed instances.  This is the same
