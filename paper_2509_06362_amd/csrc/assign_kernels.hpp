@@ -186,14 +186,15 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
     idx[v] = -1;
     b_ttft[v] = b_tbt[v] = b_e2e[v] = __builtin_nanf("");
   }
-  auto score = [&](const float4 r, uint32_t j, float rank) {  // r = {a, p, tbt, wait}
+  // r = {a, p, tbt, wait}; m2 = the between-token margins of the V requests when they come from the table
+  auto score = [&](const float4 r, const float (&m2)[V], uint32_t j, float rank) {
 #pragma unroll
     for (int v = 0; v < V; ++v) {
       const float pre = fmaf(r.y, L[v], r.x);
       const float ttft = r.w + pre;
       const float e2e = fmaf(S[v], r.z, ttft);
       const float s1 = (Dt[v] - ttft) * iDt[v];
-      const float s2 = NREG ? (Db[v] - r.z) * iDb[v] : s2tab[k[v] * kS2Stride + j];
+      const float s2 = NREG ? (Db[v] - r.z) * iDb[v] : m2[v];
       const float s3 = (De[v] - e2e) * iDe[v];
       const float slack = fminf(fminf(s1, s2), s3);
       const float val = (kSQ && slack >= 0.0f) ? rank : slack;
@@ -214,11 +215,34 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
     }
   };
   if (NREG) {
+    const float none[V] = {};
 #pragma unroll
     for (int j = 0; j < (NREG ? NREG : 1); ++j)
-      if ((uint32_t)j < n) score(rreg[j], (uint32_t)j, kSQ ? rrank[j] : 0.0f);
+      if ((uint32_t)j < n) score(rreg[j], none, (uint32_t)j, kSQ ? rrank[j] : 0.0f);
   } else {
-    for (uint32_t j = 0; j < n; ++j) score(recs[j], j, kSQ ? rankv[j] : 0.0f);
+    // four records and their margins are fetched per trip before any is used: one LDS wait and one
+    // round of address arithmetic for sixteen triples
+    constexpr uint32_t U = 4;
+    uint32_t j = 0;
+    for (; j + U <= n; j += U) {
+      float4 r[U];
+      float m2[U][V], rk[U];
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) {
+        r[u] = recs[j + u];
+        rk[u] = kSQ ? rankv[j + u] : 0.0f;
+#pragma unroll
+        for (int v = 0; v < V; ++v) m2[u][v] = s2tab[k[v] * kS2Stride + j + u];
+      }
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) score(r[u], m2[u], j + u, rk[u]);
+    }
+    for (; j < n; ++j) {
+      float m2[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) m2[v] = s2tab[k[v] * kS2Stride + j];
+      score(recs[j], m2, j, kSQ ? rankv[j] : 0.0f);
+    }
     if (kLat || kSQ) {
 #pragma unroll
       for (int v = 0; v < V; ++v) {
