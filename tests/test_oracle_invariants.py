@@ -129,3 +129,22 @@ def test_subrange_sweep_matches_full_sweep():
     assert np.array_equal(part["sat_count"][5:17], full["sat_count"][5:17])
     assert (part["sat_count"][:5] == 0).all()
     assert part["best_cand"] == 5 + int(np.argmax(full["sat_count"][5:17]))
+
+
+def test_a_fresh_instance_adds_no_wait_to_the_first_token_latency():
+    """An instance with nothing queued and a free slot has a queue wait of exactly +0, and the
+    first-token latency on it is the prefill time bit for bit (L_r = L_q + L_d with L_q = 0, Eq. 2):
+    what allows a fast path that leaves the addition out for such instances."""
+    w = W.config1(n_cand=6, n_req=64)
+    rng = np.random.default_rng(7)
+    for c in range(w.n_cand):
+        st = oracle.stage(w, c)
+        assert np.all(st["wait"] == 0.0) and not np.any(np.signbit(st["wait"]))
+        for j in rng.choice(len(st["a"]), 3):
+            for L in (0, 1, 17, 8192, 16777215):
+                t = oracle.triple(st["a"][j], st["p"][j], st["tbt"][j], st["wait"][j], L, 100, 0.5, 0.05)
+                pre = np.float32(np.float64(st["p"][j]) * np.float64(L) + np.float64(st["a"][j]))  # one rounding
+                assert t["pre"] == pre and t["ttft"] == t["pre"] and t["pre"] > 0
+    # with load it is not: queued prefill shows up in the wait
+    loaded = W.stressed(w, seed=3)
+    assert np.all(oracle.stage(loaded, 0)["wait"] > 0.0)
