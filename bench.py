@@ -65,7 +65,7 @@ KERNEL_SOURCES = {
 }
 TRAFFIC = {
     "cfg1_placer_sweep": ("sweep_kernel", 5.695e6, "4224fb415c88948b"),
-    "streaming_i4": ("assign_static_kernel", 1.1410e9, "199ee8dc19364bd5"),
+    "streaming_i4": ("assign_static_kernel", 1.1410e9, "ed231e5bfe0493fc"),
 }
 
 

