@@ -117,3 +117,33 @@ def test_product_package_does_not_touch_the_oracle():
         text = f.read_text()
         assert "import oracle" not in text and "from oracle" not in text, f
         assert "maaso_oracle" not in text, f
+
+
+def test_header_is_plain_c_and_layouts_agree_with_the_binding(lib, tmp_path):
+    """maaso.h compiles as C99 with nothing but <stdint.h>, a C program links against the library,
+    and the C compiler's struct sizes are the ones the ctypes binding marshals."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "abi_check.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "maaso.h"\n'
+        "int main(void) {\n"
+        '  printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(maaso_profile_desc), sizeof(maaso_requests),\n'
+        "         sizeof(maaso_placements), sizeof(maaso_params), sizeof(maaso_assign_out),\n"
+        "         sizeof(maaso_score_weights), sizeof(maaso_score_out));\n"
+        '  printf("%s\\n", maaso_strerror(MAASO_OK));\n'
+        '  printf("%d\\n", maaso_score_assign(NULL, NULL, NULL, NULL, NULL, NULL));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "abi_check"
+    pkg = binding.LIB_PATH.parent
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", f"-I{HEADER.parent}",
+                    str(src), "-o", str(exe), f"-L{pkg}", "-lmaaso", f"-Wl,-rpath,{pkg}",
+                    "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    sizes = [int(x) for x in out[0].split()]
+    assert sizes == [C.sizeof(t) for t in (binding.ProfileDesc, binding.Requests, binding.Placements,
+                                           binding.Params, binding.AssignOut, binding.ScoreWeights,
+                                           binding.ScoreOut)]
+    assert out[1] == "ok" and int(out[2]) == -1
