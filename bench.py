@@ -64,8 +64,8 @@ KERNEL_SOURCES = {
     "assign_static_kernel": ("device_model.hpp", "sweep_kernels.hpp", "assign_kernels.hpp"),
 }
 TRAFFIC = {
-    "cfg1_placer_sweep": ("sweep_kernel", 5.695e6, "4224fb415c88948b"),
-    "streaming_i4": ("assign_static_kernel", 1.1410e9, "ed231e5bfe0493fc"),
+    "cfg1_placer_sweep": ("sweep_kernel", 5.695e6, "90eec800b4caf031"),
+    "streaming_i4": ("assign_static_kernel", 1.1410e9, "c0e11e1f486a50b7"),
 }
 
 

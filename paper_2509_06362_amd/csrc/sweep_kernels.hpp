@@ -429,14 +429,6 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a)
   sweep_body<Q>(a);
 }
 
-// 16 requests per lane: held to 96 registers, i.e. five wavefronts per SIMD - left alone the
-// compiler takes 99, only four fit, and the variant loses what it gains.
-template <>
-__global__ __launch_bounds__(kSweepThreads) __attribute__((amdgpu_num_vgpr(96)))
-void sweep_kernel<16>(const SweepArgs a) {
-  sweep_body<16>(a);
-}
-
 // ---------------------------------------------------------------------------------------------
 // ratio[c] = count[c] / R and the best candidate: largest count, lowest index on ties (Alg. 1 keeps
 // the best-scoring deployment).  One block.  Also clears the class counters for the next call.
