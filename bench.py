@@ -102,6 +102,10 @@ def make_workload(name: str):
         from dataclasses import replace
         w = W.config4()
         return replace(w, name=w.name + "_windowed", window=4096)
+    if name == "cfg4w1":  # config 4 request by request: every request meets the state left by all earlier ones
+        from dataclasses import replace
+        w = W.config4()
+        return replace(w, name=w.name + "_request_by_request", window=1)
     if name == "cfg4score":  # the same, every candidate scored with the composite serving score
         from dataclasses import replace
         w = W.config4()
@@ -242,7 +246,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="cfg1",
-                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "cfg4score", "alg2", "stream"])
+                    choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "cfg4w1", "cfg4score", "alg2", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-triples", type=float, default=3.0e9,
                     help="size of the oracle's timed sample, in triples")
@@ -349,7 +353,7 @@ def main() -> int:
     if kind == "sweep" and sweep_window:
         ops = ASSIGN_LANEOPS_PER_TRIPLE * triples_sweep
         roofline = {
-            "kernel": "sweep_window_kernel", "bound": "alu",
+            "kernel": "sweep_seq_kernel" if sweep_window == 1 else "sweep_window_kernel", "bound": "alu",
             "achieved": ops / k_avg_s / 1e12, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
             "frac": ops / k_avg_s / 1e12 / VALU_PEAK_TLANEOPS, "traffic": measured_traffic(w.name),
             "kernel_ms": k_avg_s * 1e3, "launches_timed": k_n,

@@ -16,6 +16,7 @@
 #include "partition_kernels.hpp"
 #include "profile_fit_kernels.hpp"
 #include "sweep_window_kernels.hpp"
+#include "sweep_seq_kernels.hpp"
 #include "window_kernels.hpp"
 
 using namespace maaso;
@@ -178,6 +179,25 @@ int launch_sweep_window_v(const SweepWindowArgs& a, size_t lds, hipStream_t s) {
   }
   const uint64_t blocks = (uint64_t)a.n_cand * a.n_sets;
   if (blocks == 0 || blocks > 0x7fffffffull) return MAASO_E_SHAPE;
+  // Short windows go to the kernel that gives a wavefront to each (set, candidate) and its lanes to
+  // the instances.  Measured crossover with the lanes-are-requests kernel (2048-8192 candidates): up to
+  // 32 slots a window of 4 (6.2 against 7.6 ms; 8: 5.7 against 3.8), 128 slots 16 (6.6 against 9.4; 32:
+  // 6.4 against 4.8), 256 slots 32 (7.7 against 8.9; 64: 7.6 against 4.5).
+  const uint32_t short_window = a.i_pad / 8u > 4u ? a.i_pad / 8u : 4u;
+  bool one_by_one = !kSQ;
+  for (uint32_t k = 0; k < a.n_sets; ++k) one_by_one = one_by_one && a.sets[k].window <= short_window;
+  if (one_by_one) {
+    const dim3 g((uint32_t)((blocks + kSeqThreads / 64 - 1) / (kSeqThreads / 64)));
+    if (!kSQ) {
+      if (a.i_pad <= 64u)
+        hipLaunchKernelGGL((sweep_seq_kernel<kScore, 1>), g, dim3(kSeqThreads), lds, s, a);
+      else if (a.i_pad <= 128u)
+        hipLaunchKernelGGL((sweep_seq_kernel<kScore, 2>), g, dim3(kSeqThreads), lds, s, a);
+      else
+        hipLaunchKernelGGL((sweep_seq_kernel<kScore, 4>), g, dim3(kSeqThreads), lds, s, a);
+    }
+    return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+  }
   const dim3 grid((uint32_t)blocks);
   if (per_window > 2u * kAssignThreads)
     hipLaunchKernelGGL((sweep_window_kernel<kScore, 4, kSQ>), grid, dim3(kAssignThreads), lds, s, a);

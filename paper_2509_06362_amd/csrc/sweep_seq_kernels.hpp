@@ -1,0 +1,213 @@
+// Capacity-aware evaluation of candidate deployments with SHORT windows, down to one request per
+// window - where every request meets the state left by all earlier ones, the paper's simulator taken
+// literally (Sec. V-A: requests are mapped to slots one after the other and instance clocks advance
+// in between).
+//
+// With a handful of requests per window the lanes of sweep_window_kernel (lanes = requests) are
+// mostly idle and its block-wide barriers per window dominate.  Here a candidate belongs to ONE
+// wavefront and the lanes are its INSTANCES (S slots per lane, instance j = s * 64 + lane): state,
+// profile evaluation, triple, and the drain between two windows all stay in the lane's registers,
+// the best instance of a request is a DPP arg-max over the wavefront, and nothing crosses a barrier.
+// Requests are fetched 64 at a time (one per lane) and handed out lane by lane with v_readlane.
+//
+// The arithmetic is the windowed kernel's, operation by operation, so the two agree bit for bit and
+// with the oracle's windowed distributor.  The shortest-queue rule is not offered here (its ranks
+// need every instance's queue length); the windowed kernel serves it.
+#pragma once
+
+#include "sweep_window_kernels.hpp"
+#include "window_kernels.hpp"
+
+#pragma clang fp contract(off)
+
+namespace maaso {
+
+constexpr int kSeqThreads = 256;  // four wavefronts = four (request set, candidate) units per block
+
+__device__ __forceinline__ float lane_value(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+
+// Arg-max of (slack, index) over the whole wavefront, lowest index among equals; every lane ends
+// with the winner.  Four DPP steps settle each row of 16 lanes; the four row winners are then read
+// with v_readlane and compared as uniform values - no trip through LDS on the per-request chain.
+__device__ __forceinline__ void argmax_wave(float& s, int32_t& i) {
+  argmax_lanes<16>(s, i);
+  float s0 = lane_value(s, 0), s1 = lane_value(s, 16), s2 = lane_value(s, 32), s3 = lane_value(s, 48);
+  int32_t i0 = __builtin_amdgcn_readlane(i, 0), i1 = __builtin_amdgcn_readlane(i, 16);
+  int32_t i2 = __builtin_amdgcn_readlane(i, 32), i3 = __builtin_amdgcn_readlane(i, 48);
+  take_better(s0, i0, s1, i1);
+  take_better(s2, i2, s3, i3);
+  take_better(s0, i0, s2, i2);
+  s = s0;
+  i = i0;
+}
+
+template <bool kScore, int S>
+__global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindowArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* tab = reinterpret_cast<float*>(smem);
+  __shared__ ClassRow cls[kMaxSlo];
+
+  const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid & 63u;
+  if (tid < a.n_slo) cls[tid] = ClassRow{a.d_ttft[tid], a.d_tbt[tid], a.i_ttft[tid], a.i_tbt[tid]};
+  for (uint32_t i = tid; i < 3u * a.cells; i += kSeqThreads) tab[i] = a.tab[i];
+  __syncthreads();  // the only barrier: from here on a wavefront works alone
+
+  const uint64_t unit = (uint64_t)blockIdx.x * (kSeqThreads / 64) + (tid >> 6);
+  if (unit >= (uint64_t)a.n_sets * a.n_cand) return;
+  const uint32_t set = (uint32_t)(unit / a.n_cand);
+  const uint32_t c = (uint32_t)(unit - (uint64_t)set * a.n_cand);
+  const SweepWindowSet& rs = a.sets[set];
+  const size_t base = (size_t)c * a.i_pad;
+  const uint32_t n = min(a.n_inst[c], a.i_pad);
+
+  // instance state, S slots per lane
+  uint32_t tp[S], B[S], served[S];
+  int32_t occ[S];
+  uint64_t q[S];
+  float inv_tbt_first[S];
+  bool valid[S];
+#pragma unroll
+  for (int s = 0; s < S; ++s) {
+    const uint32_t j = (uint32_t)s * 64u + lane;
+    valid[s] = j < n;
+    tp[s] = 0; B[s] = 1; occ[s] = 0; q[s] = 0; served[s] = 0; inv_tbt_first[s] = 0.0f;
+    if (valid[s]) {
+      tp[s] = a.tp_idx[base + j]; B[s] = a.max_batch[base + j];
+      occ[s] = a.occ[base + j]; q[s] = a.q_ticks[base + j];
+    }
+  }
+  unsigned long long wait_sum = 0ull;  // queue waits of the requests this lane's instances admitted, ticks
+  uint32_t sat = 0;                    // uniform
+
+  const uint64_t R = rs.n_req;
+  const uint64_t W = rs.window;
+  // requests are fetched 64 at a time, one per lane, and handed out with v_readlane
+  // what depends on the request alone (its deadlines, the reciprocal of the end-to-end one) is
+  // worked out for the 64 requests of a batch at once, off the per-request chain
+  uint64_t batch0 = ~0ull;  // first request of the batch held in the vectors below
+  float Lv = 0.0f, Sv = 0.0f, Dtv = 1.0f, iDtv = 1.0f, Dbv = 1.0f, iDbv = 1.0f, Dev = 1.0f, iDev = 1.0f;
+  uint32_t livev = 0;
+  for (uint64_t s0 = 0; s0 < R; s0 += W) {
+    const uint64_t e0 = (s0 + W < R) ? s0 + W : R;
+    // stage this lane's instances against the state the window starts with
+    float ra[S], rp[S], rt[S], rw[S], svc[S];
+    unsigned long long wait_ticks[S];
+    uint32_t n_add[S];
+    unsigned long long t_add[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      ra[s] = 1.0f; rp[s] = 1.0f; rt[s] = 1.0f; rw[s] = INFINITY; svc[s] = 1.0f;
+      wait_ticks[s] = 0ull; n_add[s] = 0u; t_add[s] = 0ull;
+      if (!valid[s]) continue;
+      Staged st;
+      if (stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st)) {
+        ra[s] = st.a; rp[s] = st.p; rt[s] = st.tbt; rw[s] = st.wait;
+        svc[s] = st.svc;
+        if (kScore) {
+          wait_ticks[s] = (unsigned long long)__float2ll_rn(st.wait * 1048576.0f);
+          if (s0 == 0u) inv_tbt_first[s] = 1.0f / st.tbt;
+        }
+      } else {
+        raise_status(a.status, 2u);
+      }
+    }
+    for (uint64_t r = s0; r < e0; ++r) {
+      if ((r & ~63ull) != batch0) {
+        batch0 = r & ~63ull;
+        const uint64_t mine = batch0 + lane;
+        uint32_t pl = 0, ol = 0, kk = 0;
+        if (mine < R) { pl = rs.prompt_len[mine]; ol = rs.out_len[mine]; kk = rs.slo_class[mine]; }
+        livev = 1u;
+        if (kk >= a.n_slo) { raise_status(a.status, 1u); livev = 0u; kk = 0; }
+        Lv = (float)pl; Sv = (float)ol;
+        const ClassRow cr = cls[kk];
+        Dtv = cr.Dt; iDtv = cr.iDt; Dbv = cr.Db; iDbv = cr.iDb;
+        Dev = fmaf(Sv, cr.Db, cr.Dt);
+        iDev = 1.0f / Dev;
+      }
+      const int i = (int)(r & 63ull);
+      const float L = lane_value(Lv, i), So = lane_value(Sv, i);
+      const bool live = __builtin_amdgcn_readlane((int)livev, i) != 0;
+      Deadlines d;
+      d.Dt = lane_value(Dtv, i); d.iDt = lane_value(iDtv, i);
+      d.Db = lane_value(Dbv, i); d.iDb = lane_value(iDbv, i);
+      d.De = lane_value(Dev, i); d.iDe = lane_value(iDev, i);
+      float best = -INFINITY, bpre = 0.0f;
+      int32_t idx = -1;
+#pragma unroll
+      for (int s = 0; s < S; ++s) {
+        if (!valid[s]) continue;
+        const Margins m = score_triple(ra[s], rp[s], rt[s], rw[s], L, So, d);
+        if (m.slack > best) { best = m.slack; idx = (int32_t)((uint32_t)s * 64u + lane); bpre = m.pre; }
+      }
+      if (!live) { best = -INFINITY; idx = -1; }
+      float wbest = best;
+      int32_t widx = idx;
+      argmax_wave(wbest, widx);       // every lane ends with the wavefront's winner
+      if (live && wbest >= 0.0f) {    // admitted: the chosen instance takes the load at the window's end
+        sat += 1u;
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+          if (widx == (int32_t)((uint32_t)s * 64u + lane)) {
+            n_add[s] += 1u;
+            t_add[s] += (unsigned long long)__float2ll_rn(bpre * 1048576.0f);
+          }
+      }
+    }
+    // the window's load, then the time that passes until the next window opens
+    uint32_t delta = 0;
+    if (e0 < R) delta = rs.arrival_ticks[e0] - rs.arrival_ticks[s0];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      if (!valid[s]) continue;
+      if (kScore) {
+        served[s] += n_add[s];
+        wait_sum += (unsigned long long)n_add[s] * wait_ticks[s];
+      }
+      occ[s] += (int32_t)n_add[s];
+      q[s] += t_add[s];
+      if (e0 < R) {
+        q[s] -= (q[s] < (uint64_t)delta) ? q[s] : (uint64_t)delta;
+        const int32_t run = min(occ[s], (int32_t)B[s]);
+        const float x = ((float)run * ((float)delta * 0x1p-20f)) / svc[s];
+        const int32_t done = min(occ[s], (int32_t)floorf(fminf(x, 2147483520.0f)));
+        occ[s] -= done;
+      }
+    }
+  }
+
+  // results of this (set, candidate): lane 0 writes them
+  if (kScore) wait_sum = wave_sum_u64(wait_sum);
+  float pt = 0.0f;
+  if (kScore) {
+    // Phi_T: 1 / tbt of the serving instances, added in index order
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      const float inv = (valid[s] && served[s] != 0u) ? inv_tbt_first[s] : -1.0f;
+      const uint32_t upto = n > (uint32_t)s * 64u ? min(n - (uint32_t)s * 64u, 64u) : 0u;
+      for (uint32_t l = 0; l < upto; ++l) {
+        const float v = lane_value(inv, (int)l);
+        if (v >= 0.0f) pt = pt + v;
+      }
+    }
+  }
+  if (lane == 0u) {
+    rs.sat_count[c] = sat;
+    if (kScore) {
+      const float ps = (rs.n_req == 0u) ? 0.0f : (float)sat / (float)rs.n_req;
+      const float plat = (sat == 0u) ? 0.0f : ((float)wait_sum * 0x1p-20f) / (float)sat;
+      const float ptn = fminf(pt, a.gamma_t) / a.gamma_t;
+      const float pln = fmaxf(a.gamma_l - plat, 0.0f) / a.gamma_l;
+      const float sc = fmaf(a.alpha, ps, fmaf(a.beta, ptn, (1.0f - a.beta) * pln));
+      if (rs.phi_s) rs.phi_s[c] = ps;
+      if (rs.phi_t) rs.phi_t[c] = pt;
+      if (rs.phi_l) rs.phi_l[c] = plat;
+      if (rs.score) rs.score[c] = sc;
+    }
+  }
+}
+
+}  // namespace maaso

@@ -218,6 +218,63 @@ def test_windowed_sweep_small_irregular(seed, n_cand, i_pad, n_req, n_slo, windo
     assert spread > 1
 
 
+@pytest.mark.parametrize("seed,n_cand,i_pad,n_req,n_slo", [
+    (161, 9, 1, 65, 1), (162, 7, 64, 1000, 3), (163, 5, 65, 63, 2), (164, 6, 128, 700, 8),
+    (165, 3, 200, 64, 16), (166, 5, 256, 513, 3), (167, 13, 20, 1, 2), (168, 4, 31, 2, 3),
+])
+def test_sweep_request_by_request(seed, n_cand, i_pad, n_req, n_slo):
+    """Windows of one request (every request meets the state left by all earlier ones) run in a
+    kernel of their own - one wavefront per candidate, lanes = instances: counts, scores, request
+    sets and the flags for out-of-range elements against the oracle's distributor at window 1."""
+    w = W.random_small(seed, n_cand, i_pad, n_req, n_slo=n_slo, pen_kappa=0.5 if seed % 2 else 0.0)
+    w = W.replace(w, arrival_ticks=W.poisson_arrivals(W.rng_for(seed, 3), 300.0, n_req))
+    seen = set()
+    for v in (w, W.stressed(w, seed=seed, deadline_scale=0.25), W.replace(w, tbt_mode=1)):
+        seen.update(check_sweep_windowed(v, 1).tolist())
+        check_score(v, 1, weights=SCORE_WEIGHTS[:2])
+    assert len(seen) > 1 or n_req <= 2
+    if n_req >= 64:
+        v = W.stressed(w, seed=seed, deadline_scale=0.25)
+        m = n_req // 3
+        dw = binding.DeviceWorkload(v)
+        try:
+            alpha, beta, gt, gl = SCORE_WEIGHTS[0]
+            outs = dw.score_sets([(0, m), (m, n_req), (0, n_req)], alpha, beta, gt, gl, window=1)
+            torch.cuda.synchronize()
+            for (lo, hi), out in zip([(0, m), (m, n_req), (0, n_req)], outs):
+                ref = oracle.placement_score(v.with_requests(lo, hi), alpha, beta, gt, gl, window=1)
+                for k in ("sat_count", "phi_s", "phi_t", "phi_l", "score"):
+                    got = u32(out[k]) if out[k].dtype == torch.int32 else out[k].cpu().numpy()
+                    assert np.array_equal(got, ref[k]), (k, lo, hi)
+            assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        finally:
+            dw.close()
+
+
+def test_sweep_request_by_request_flags_out_of_range_elements():
+    """A request of an unknown class is never admitted (time still passes after it) and an instance
+    outside the tables is absent: the counts are those of the oracle on a stream where these requests
+    are hopeless ones of a valid class and that instance is one nobody can use."""
+    w = W.random_small(169, 4, 8, 300)
+    w = W.replace(w, n_inst=np.full(4, 8, np.uint32),
+                  arrival_ticks=W.poisson_arrivals(W.rng_for(169, 3), 300.0, 300))
+    rows = [3, 77, 299]
+    bad_cls = w.slo_class.copy(); bad_cls[rows] = 9
+    bad_tp = w.tp_idx.copy(); bad_tp[1, 2] = 200
+    dw = binding.DeviceWorkload(W.replace(w, slo_class=bad_cls, tp_idx=bad_tp))
+    try:
+        cnt, _, _ = dw.sweep(window=1)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 3
+    finally:
+        dw.close()
+    hopeless = w.prompt_len.copy(); hopeless[rows] = 16777215        # minutes of prefill: never admitted
+    unusable = w.q_ticks.copy(); unusable[1, 2] = 1 << 45            # a year of queued prefill
+    ref = oracle.placement_sweep_windowed(W.replace(w, prompt_len=hopeless, q_ticks=unusable), window=1)
+    assert np.array_equal(u32(cnt), ref["sat_count"])
+    assert 0 < int(ref["sat_count"].min()) and int(ref["sat_count"].max()) < 300
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_windowed_sweep_repeats_exactly(policy):
     """Short windows, many of them, repeated on fresh contexts: every call must give the oracle's
@@ -254,6 +311,9 @@ def test_windowed_sweep_config4_shape():
     full = W.config4()
     rng = np.random.default_rng(44)
     check_sweep_windowed(full, 4096, sampled=sorted(rng.choice(full.n_cand, 6, replace=False).tolist()))
+    # request by request (the short-window kernel), and at its longest window for 128 instance slots
+    check_sweep_windowed(full, 1, sampled=sorted(rng.choice(full.n_cand, 3, replace=False).tolist()))
+    check_sweep_windowed(full, 16, sampled=sorted(rng.choice(full.n_cand, 3, replace=False).tolist()))
 
 
 # ------------------------------------------------------------------------------------------------
