@@ -123,7 +123,9 @@ const char* maaso_strerror(int status);
  *   sweep_group: candidates per work item of the sweep kernel (clamped to what fits its LDS lists);
  *   sweep_blocks_per_queue: persistent blocks serving each (request tile, XCD) work queue;
  *   window_blocks: blocks of the windowed distributor's persistent kernel (at most one per compute
- *   unit is used).  Errors: INVALID_ARG. */
+ *   unit is used).  Left at 0, windows of up to four requests are distributed by a single wavefront
+ *   instead (no device-wide barrier per window); a value keeps the persistent kernel for them too.
+ * Errors: INVALID_ARG. */
 int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane, uint32_t sweep_group,
                                uint32_t sweep_blocks_per_queue, uint32_t window_blocks);
 

@@ -210,4 +210,149 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
   }
 }
 
+// The distributor itself on short windows (one placement, requests in arrival order, down to one
+// request per window - the online distributor of Sec. IV-F taken literally): the same wavefront
+// scheme, plus the per-request outputs.  One wavefront does all the work - the method is sequential
+// here - so this is about latency: no device-wide barrier per window.  The outputs of 64 requests are
+// collected one lane each and stored together.
+template <bool kLat, int S>
+__global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint32_t window) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* tab = reinterpret_cast<float*>(smem);
+  __shared__ ClassRow cls[kMaxSlo];
+  const uint32_t lane = threadIdx.x;
+  if (lane < a.n_slo) cls[lane] = ClassRow{a.d_ttft[lane], a.d_tbt[lane], a.i_ttft[lane], a.i_tbt[lane]};
+  for (uint32_t i = lane; i < 3u * a.cells; i += 64u) tab[i] = a.tab[i];
+  __syncthreads();
+
+  const PlacementRow row = select_row(a);
+  const uint32_t n = row.n;
+  uint32_t tp[S], B[S];
+  int32_t occ[S];
+  uint64_t q[S];
+  bool valid[S];
+#pragma unroll
+  for (int s = 0; s < S; ++s) {
+    const uint32_t j = (uint32_t)s * 64u + lane;
+    valid[s] = j < n;
+    tp[s] = 0; B[s] = 1; occ[s] = 0; q[s] = 0;
+    if (valid[s]) { tp[s] = row.tp_idx[j]; B[s] = row.max_batch[j]; occ[s] = row.occ[j]; q[s] = row.q_ticks[j]; }
+  }
+  unsigned long long sat = 0ull;  // uniform
+
+  const uint64_t R = a.n_req;
+  const uint64_t W = window;
+  uint64_t batch0 = ~0ull;
+  float Lv = 0.0f, Sv = 0.0f, Dtv = 1.0f, iDtv = 1.0f, Dbv = 1.0f, iDbv = 1.0f, Dev = 1.0f, iDev = 1.0f;
+  uint32_t livev = 0;
+  // outputs of the batch, request batch0 + lane in this lane
+  int32_t o_idx = -1;
+  float o_slack = -INFINITY, o_ttft = 0.0f, o_tbt = 0.0f, o_e2e = 0.0f;
+  auto flush = [&]() {
+    const uint64_t mine = batch0 + lane;
+    if (batch0 == ~0ull || mine >= R) return;
+    if (a.chosen) a.chosen[mine] = o_idx;
+    if (a.slack) a.slack[mine] = o_slack;
+    if (kLat) {
+      if (a.ttft) a.ttft[mine] = o_ttft;
+      if (a.tbt) a.tbt[mine] = o_tbt;
+      if (a.e2e) a.e2e[mine] = o_e2e;
+    }
+  };
+  for (uint64_t s0 = 0; s0 < R; s0 += W) {
+    const uint64_t e0 = (s0 + W < R) ? s0 + W : R;
+    float ra[S], rp[S], rt[S], rw[S], svc[S];
+    uint32_t n_add[S];
+    unsigned long long t_add[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      ra[s] = 1.0f; rp[s] = 1.0f; rt[s] = 1.0f; rw[s] = INFINITY; svc[s] = 1.0f;
+      n_add[s] = 0u; t_add[s] = 0ull;
+      if (!valid[s]) continue;
+      Staged st;
+      if (stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st)) {
+        ra[s] = st.a; rp[s] = st.p; rt[s] = st.tbt; rw[s] = st.wait;
+        svc[s] = st.svc;
+      } else {
+        raise_status(a.status, 2u);
+      }
+    }
+    for (uint64_t r = s0; r < e0; ++r) {
+      if ((r & ~63ull) != batch0) {
+        flush();
+        batch0 = r & ~63ull;
+        const uint64_t mine = batch0 + lane;
+        uint32_t pl = 0, ol = 0, kk = 0;
+        if (mine < R) { pl = a.prompt_len[mine]; ol = a.out_len[mine]; kk = a.slo_class[mine]; }
+        livev = 1u;
+        if (kk >= a.n_slo) { raise_status(a.status, 1u); livev = 0u; kk = 0; }
+        Lv = (float)pl; Sv = (float)ol;
+        const ClassRow cr = cls[kk];
+        Dtv = cr.Dt; iDtv = cr.iDt; Dbv = cr.Db; iDbv = cr.iDb;
+        Dev = fmaf(Sv, cr.Db, cr.Dt);
+        iDev = 1.0f / Dev;
+      }
+      const int i = (int)(r & 63ull);
+      const float L = lane_value(Lv, i), So = lane_value(Sv, i);
+      const bool live = __builtin_amdgcn_readlane((int)livev, i) != 0;
+      Deadlines d;
+      d.Dt = lane_value(Dtv, i); d.iDt = lane_value(iDtv, i);
+      d.Db = lane_value(Dbv, i); d.iDb = lane_value(iDbv, i);
+      d.De = lane_value(Dev, i); d.iDe = lane_value(iDev, i);
+      float best = -INFINITY, bpre = 0.0f, bttft = 0.0f, btbt = 0.0f, be2e = 0.0f;
+      int32_t idx = -1;
+#pragma unroll
+      for (int s = 0; s < S; ++s) {
+        if (!valid[s]) continue;
+        const Margins m = score_triple(ra[s], rp[s], rt[s], rw[s], L, So, d);
+        if (m.slack > best) {
+          best = m.slack; idx = (int32_t)((uint32_t)s * 64u + lane); bpre = m.pre;
+          bttft = m.ttft; btbt = rt[s]; be2e = m.e2e;
+        }
+      }
+      if (!live) { best = -INFINITY; idx = -1; }
+      float wbest = best;
+      int32_t widx = idx;
+      argmax_wave(wbest, widx);
+      // what is reported about the chosen instance comes from the lane that holds it
+      const float nanv = __builtin_nanf("");
+      float w_ttft = nanv, w_tbt = nanv, w_e2e = nanv;
+      if (widx >= 0) {
+        const int owner = widx & 63;
+        if (kLat) { w_ttft = lane_value(bttft, owner); w_tbt = lane_value(btbt, owner); w_e2e = lane_value(be2e, owner); }
+        if (wbest >= 0.0f) {  // admitted: it loads the instance; a blocked request does not
+          sat += 1ull;
+#pragma unroll
+          for (int s = 0; s < S; ++s)
+            if (widx == (int32_t)((uint32_t)s * 64u + lane)) {
+              n_add[s] += 1u;
+              t_add[s] += (unsigned long long)__float2ll_rn(bpre * 1048576.0f);
+            }
+        }
+      }
+      if ((int)lane == i) { o_idx = widx; o_slack = wbest; o_ttft = w_ttft; o_tbt = w_tbt; o_e2e = w_e2e; }
+    }
+    uint32_t delta = 0;
+    if (e0 < R) delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      if (!valid[s]) continue;
+      occ[s] += (int32_t)n_add[s];
+      q[s] += t_add[s];
+      if (e0 < R) {  // time passes until the next window opens
+        q[s] -= (q[s] < (uint64_t)delta) ? q[s] : (uint64_t)delta;
+        const int32_t run = min(occ[s], (int32_t)B[s]);
+        const float x = ((float)run * ((float)delta * 0x1p-20f)) / svc[s];
+        const int32_t done = min(occ[s], (int32_t)floorf(fminf(x, 2147483520.0f)));
+        occ[s] -= done;
+      }
+    }
+  }
+  flush();
+#pragma unroll
+  for (int s = 0; s < S; ++s)
+    if (valid[s]) { row.occ[(uint32_t)s * 64u + lane] = occ[s]; row.q_ticks[(uint32_t)s * 64u + lane] = q[s]; }
+  if (lane == 0u && a.n_satisfied) *a.n_satisfied = sat;
+}
+
 }  // namespace maaso

@@ -1013,6 +1013,52 @@ def test_assign_windowed_irregular(seed, i_pad, n_inst, window, blocks):
     check_assign(w, window=window, window_blocks=blocks)
 
 
+@pytest.mark.parametrize("seed,i_pad,n_inst,n_req,window", [
+    (141, 1, 1, 130, 1), (142, 64, 64, 1000, 1), (143, 65, 65, 63, 2), (144, 128, 100, 700, 3),
+    (145, 200, 200, 64, 4), (146, 256, 256, 513, 1), (147, 20, 0, 70, 1), (148, 31, 31, 1, 1),
+    (149, 8, 5, 4097, 4),
+])
+def test_assign_request_by_request(seed, i_pad, n_inst, n_req, window):
+    """Windows of 1 to 4 requests - the online distributor taken literally - run on one wavefront with
+    the instances in its lanes: every output and the final state against the oracle, with and without
+    the latency outputs, at the state as generated and under load; the persistent kernel, asked for
+    through its blocks knob, must give the same."""
+    w = W.random_small(seed, 1, i_pad, n_req, n_slo=4, pen_kappa=0.25)
+    w = W.replace(w, n_inst=np.array([n_inst], np.uint32),
+                  arrival_ticks=W.poisson_arrivals(W.rng_for(seed, 3), 200.0, n_req))
+    for v in (w, W.stressed(w, seed=seed, deadline_scale=0.25), W.replace(w, tbt_mode=1)):
+        ref = oracle.score_assign(v, window=window)
+        check_assign(v, window=window, ref=ref)
+        check_assign(v, window=window, latencies=False, ref=ref)
+        check_assign(v, window=window, window_blocks=2, ref=ref)
+
+
+def test_assign_request_by_request_flags_out_of_range_elements():
+    w = W.random_small(150, 1, 8, 300)
+    w = W.replace(w, n_inst=np.array([8], np.uint32),
+                  arrival_ticks=W.poisson_arrivals(W.rng_for(150, 3), 300.0, 300))
+    rows = [3, 77, 299]
+    bad_cls = w.slo_class.copy(); bad_cls[rows] = 9
+    bad_tp = w.tp_idx.copy(); bad_tp[0, 2] = 200
+    dw = binding.DeviceWorkload(W.replace(w, slo_class=bad_cls, tp_idx=bad_tp))
+    try:
+        got = dw.assign(window=1)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 3
+        ch = got["chosen"].cpu().numpy()
+        assert (ch[rows] == -1).all() and (ch != 2).all()
+        assert np.isneginf(got["slack"].cpu().numpy()[rows]).all()
+        assert np.isnan(got["ttft"].cpu().numpy()[rows]).all()
+    finally:
+        dw.close()
+    hopeless = w.prompt_len.copy(); hopeless[rows] = 16777215
+    unusable = w.q_ticks.copy(); unusable[0, 2] = 1 << 45
+    ref = oracle.score_assign(W.replace(w, prompt_len=hopeless, q_ticks=unusable), window=1)
+    keep = np.ones(300, bool); keep[rows] = False
+    assert np.array_equal(ch[keep], ref["chosen"][keep])
+    assert int(got["n_satisfied"].item()) == ref["n_satisfied"]
+
+
 def test_windowed_with_one_window_matches_static_outputs():
     w = W.config2(n_req=4096, window=4096)
     a = check_assign(w, window=0)
