@@ -138,8 +138,7 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
       float best = -INFINITY, bpre = 0.0f;
       int32_t idx = -1;
 #pragma unroll
-      for (int s = 0; s < S; ++s) {
-        if (!valid[s]) continue;
+      for (int s = 0; s < S; ++s) {  // an absent slot holds a record with an infinite wait: never the best
         const Margins m = score_triple(ra[s], rp[s], rt[s], rw[s], L, So, d);
         if (m.slack > best) { best = m.slack; idx = (int32_t)((uint32_t)s * 64u + lane); bpre = m.pre; }
       }
@@ -161,8 +160,7 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
     uint32_t delta = 0;
     if (e0 < R) delta = rs.arrival_ticks[e0] - rs.arrival_ticks[s0];
 #pragma unroll
-    for (int s = 0; s < S; ++s) {
-      if (!valid[s]) continue;
+    for (int s = 0; s < S; ++s) {  // an absent slot is empty and stays so
       if (kScore) {
         served[s] += n_add[s];
         wait_sum += (unsigned long long)n_add[s] * wait_ticks[s];
@@ -302,8 +300,7 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
       float best = -INFINITY, bpre = 0.0f, bttft = 0.0f, btbt = 0.0f, be2e = 0.0f;
       int32_t idx = -1;
 #pragma unroll
-      for (int s = 0; s < S; ++s) {
-        if (!valid[s]) continue;
+      for (int s = 0; s < S; ++s) {  // an absent slot holds a record with an infinite wait: never the best
         const Margins m = score_triple(ra[s], rp[s], rt[s], rw[s], L, So, d);
         if (m.slack > best) {
           best = m.slack; idx = (int32_t)((uint32_t)s * 64u + lane); bpre = m.pre;
@@ -335,8 +332,7 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
     uint32_t delta = 0;
     if (e0 < R) delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
 #pragma unroll
-    for (int s = 0; s < S; ++s) {
-      if (!valid[s]) continue;
+    for (int s = 0; s < S; ++s) {  // an absent slot is empty and stays so
       occ[s] += (int32_t)n_add[s];
       q[s] += t_add[s];
       if (e0 < R) {  // time passes until the next window opens

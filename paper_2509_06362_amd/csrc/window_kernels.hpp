@@ -40,7 +40,7 @@ __global__ void window_init_kernel(WindowWs* ws, unsigned long long* n_satisfied
 
 // (slack, index) of the better of two candidates: larger slack, lower index among equals.
 __device__ __forceinline__ void take_better(float& s, int32_t& i, float os, int32_t oi) {
-  const bool take = (os > s) || (os == s && oi < i);
+  const bool take = (os > s) | ((os == s) & (oi < i));  // no short circuit: three compares, no branches
   s = take ? os : s;
   i = take ? oi : i;
 }
