@@ -873,7 +873,7 @@ def test_sweep_and_score_shortest_queue(seed, n_cand, i_pad, n_req, n_slo, windo
         check_score(v, window, weights=SCORE_WEIGHTS[:2])
 
 
-@pytest.mark.parametrize("window", [0, 300])
+@pytest.mark.parametrize("window", [0, 300, 1])
 def test_assign_on_a_row_selected_on_the_device(window):
     """Sweep, then distribute over the sweep's best candidate without the index leaving the GPU; and
     over every other row in turn; an out-of-range index is flagged and treated as an empty placement."""
