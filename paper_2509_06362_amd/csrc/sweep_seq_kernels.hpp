@@ -99,19 +99,20 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
     unsigned long long t_add[S];
 #pragma unroll
     for (int s = 0; s < S; ++s) {
-      ra[s] = 1.0f; rp[s] = 1.0f; rt[s] = 1.0f; rw[s] = INFINITY; svc[s] = 1.0f;
-      wait_ticks[s] = 0ull; n_add[s] = 0u; t_add[s] = 0ull;
-      if (!valid[s]) continue;
-      Staged st;
-      if (stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st)) {
-        ra[s] = st.a; rp[s] = st.p; rt[s] = st.tbt; rw[s] = st.wait;
-        svc[s] = st.svc;
-        if (kScore) {
-          wait_ticks[s] = (unsigned long long)__float2ll_rn(st.wait * 1048576.0f);
-          if (s0 == 0u) inv_tbt_first[s] = 1.0f / st.tbt;
-        }
-      } else {
-        raise_status(a.status, 2u);
+      // every lane stages (an absent slot holds a harmless configuration) and the result is selected:
+      // no divergent branch on the per-window chain
+      n_add[s] = 0u; t_add[s] = 0ull;
+      Staged st{1.0f, 1.0f, 1.0f, 1.0f, INFINITY};
+      const bool ok = stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st);
+      const bool use = valid[s] & ok;
+      if (valid[s] & !ok) raise_status(a.status, 2u);
+      ra[s] = use ? st.a : 1.0f; rp[s] = use ? st.p : 1.0f; rt[s] = use ? st.tbt : 1.0f;
+      rw[s] = use ? st.wait : INFINITY;
+      svc[s] = use ? st.svc : 1.0f;
+      wait_ticks[s] = 0ull;
+      if (kScore) {
+        wait_ticks[s] = use ? (unsigned long long)__float2ll_rn(st.wait * 1048576.0f) : 0ull;
+        if (s0 == 0u) inv_tbt_first[s] = use ? 1.0f / st.tbt : inv_tbt_first[s];
       }
     }
     for (uint64_t r = s0; r < e0; ++r) {
