@@ -425,6 +425,8 @@ def test_score_request_sets(seed, n_cand, i_pad, n_req, window, cuts):
                   f"ranges={ranges[:n_sets]}", flush=True)
             outs = dw.score_sets(ranges[:n_sets], alpha, beta, gt, gl, window=window)
             torch.cuda.synchronize()
+            if n_sets == 4:
+                outs4 = outs
             assert binding.maaso_ctx_device_status(dw.ctx) == 0
             for (lo, hi), out in zip(ranges, outs):
                 ref = oracle.placement_score(w.with_requests(lo, hi), alpha, beta, gt, gl, window=window)
@@ -432,6 +434,13 @@ def test_score_request_sets(seed, n_cand, i_pad, n_req, window, cuts):
                     got = u32(out[k]) if out[k].dtype == torch.int32 else out[k].cpu().numpy()
                     assert np.array_equal(got, ref[k]), (k, lo, hi)
                 assert int(u32(out["best_cand"])[0]) == ref["best_cand"]
+        # the order in which the sets are given does not matter (the library runs the longest first)
+        perm = [2, 0, 3, 1]
+        outs_p = dw.score_sets([ranges[i] for i in perm], alpha, beta, gt, gl, window=window)
+        torch.cuda.synchronize()
+        for pos, i in enumerate(perm):
+            for k in ("sat_count", "phi_s", "phi_t", "phi_l", "score", "best_cand"):
+                assert torch.equal(outs_p[pos][k], outs4[i][k]), (k, i)
         assert np.array_equal(dw.occ.cpu().numpy(), w.occ)
     finally:
         dw.close()
