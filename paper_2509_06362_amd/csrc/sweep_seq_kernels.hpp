@@ -264,17 +264,15 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
     uint32_t n_add[S];
     unsigned long long t_add[S];
 #pragma unroll
-    for (int s = 0; s < S; ++s) {
-      ra[s] = 1.0f; rp[s] = 1.0f; rt[s] = 1.0f; rw[s] = INFINITY; svc[s] = 1.0f;
+    for (int s = 0; s < S; ++s) {  // every lane stages and the result is selected: no divergent branch
       n_add[s] = 0u; t_add[s] = 0ull;
-      if (!valid[s]) continue;
-      Staged st;
-      if (stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st)) {
-        ra[s] = st.a; rp[s] = st.p; rt[s] = st.tbt; rw[s] = st.wait;
-        svc[s] = st.svc;
-      } else {
-        raise_status(a.status, 2u);
-      }
+      Staged st{1.0f, 1.0f, 1.0f, 1.0f, INFINITY};
+      const bool ok = stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st);
+      const bool use = valid[s] & ok;
+      if (valid[s] & !ok) raise_status(a.status, 2u);
+      ra[s] = use ? st.a : 1.0f; rp[s] = use ? st.p : 1.0f; rt[s] = use ? st.tbt : 1.0f;
+      rw[s] = use ? st.wait : INFINITY;
+      svc[s] = use ? st.svc : 1.0f;
     }
     for (uint64_t r = s0; r < e0; ++r) {
       if ((r & ~63ull) != batch0) {
