@@ -257,6 +257,149 @@ void add_sweep_window_set(SweepWindowArgs& a, const maaso_requests* rq, const ma
   t.score = out ? out->score : nullptr;
 }
 
+// Launch shape and workspace layout of the static sweep.
+struct SweepPlan {
+  uint32_t Q;         // requests per lane: a block owns 256*Q requests of one class
+  uint32_t G;         // candidates per work item
+  uint32_t n_items;   // ceil(C / G)
+  uint32_t nrb_max;   // request-tile slots of the grid (>= tiles that exist)
+  uint32_t blocks;    // 8 * nrb_max * blocks per (request tile, XCD) queue
+  size_t lbuf_bytes, recs_bytes, queue_words;
+  size_t bytes;       // class-bucketed prompt lengths | staged records | queue heads and pair counts
+};
+
+inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int plan_static_sweep(const maaso_ctx* ctx, uint32_t C, uint32_t I, uint32_t R, SweepPlan& p) {
+  const uint32_t K = ctx->n_slo;
+  uint32_t Q = ctx->sweep_q;
+  // measured: 16 pays from 2^17 requests on (fewer trips to LDS per request; below that the lower
+  // occupancy of its 102 registers costs more than it saves)
+  if (Q == 0) Q = R >= (1u << 17) ? 16u : (R >= (1u << 14) ? 8u : (R >= (1u << 12) ? 4u : 2u));
+  uint32_t G = (uint32_t)kGroupSlots / I;
+  if (G > (uint32_t)kMaxGroup) G = kMaxGroup;
+  // measured: items of about 256 instance slots (8 candidates of 32 slots a third full: 105 us against
+  // 110 with 4 or 16; full slots: 4 and 8 equal; 128 slots: 1, 2 equal) balance the per-item
+  // barrier against the tail of the dynamic queues
+  uint32_t g_want = ctx->sweep_group ? ctx->sweep_group : (256u / I ? 256u / I : 1u);
+  if (g_want < G) G = g_want;
+  const uint32_t n_items = (C + G - 1) / G;
+  const uint32_t tile = (uint32_t)kSweepThreads * Q;
+  const uint32_t nrb_max = (uint32_t)(((uint64_t)R + tile - 1) / tile) + K;  // >= tiles that exist
+  uint32_t bq = ctx->sweep_blocks_per_queue;
+  if (bq == 0) {
+    // measured: about twice as many blocks as can be resident (8 per compute unit) - the late
+    // starters fill the tail of the dynamic queues
+    bq = ((uint32_t)ctx->n_cu * 18u + 4u * nrb_max) / (8u * nrb_max);
+    if (bq == 0) bq = 1;
+  }
+  const uint32_t per_queue = (n_items + 7u) / 8u;
+  if (bq > per_queue) bq = per_queue ? per_queue : 1u;
+  const uint64_t blocks64 = (uint64_t)8 * nrb_max * bq;
+  if (blocks64 > 0x7fffffffull) return MAASO_E_SHAPE;
+  p.Q = Q;
+  p.G = G;
+  p.n_items = n_items;
+  p.nrb_max = nrb_max;
+  p.blocks = (uint32_t)blocks64;
+  p.lbuf_bytes = up256((size_t)K * (R ? R : 1u) * sizeof(float));
+  p.recs_bytes = up256((size_t)C * I * sizeof(float4));
+  // queue heads, then two 8-byte evaluated-pairs words per sweep block
+  p.queue_words = (size_t)nrb_max * 8u + 4u * (size_t)blocks64;
+  p.bytes = p.lbuf_bytes + p.recs_bytes + up256(p.queue_words * sizeof(uint32_t));
+  return MAASO_OK;
+}
+
+// The three launches of the static sweep on workspace `ws` (at least plan.bytes, 256-byte aligned).
+// Everything in the workspace that must start at zero is cleared by the first launch.
+int launch_static_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                        const maaso_params* prm, const SweepPlan& plan, void* ws, uint32_t* sat_count,
+                        float* sat_ratio, uint32_t* best_cand, hipStream_t s) {
+  const uint32_t C = pl->n_cand, I = pl->i_pad, K = ctx->n_slo, R = rq->n_req;
+  unsigned char* wsb = static_cast<unsigned char*>(ws);
+  float* lbuf = reinterpret_cast<float*>(wsb);
+  float4* recs = reinterpret_cast<float4*>(wsb + plan.lbuf_bytes);
+  uint32_t* queues = reinterpret_cast<uint32_t*>(wsb + plan.lbuf_bytes + plan.recs_bytes);
+  int rc = MAASO_OK;
+
+  if (ctx->counters_dirty) {  // an earlier call failed between its launches
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, ctx->cls_count, (uint32_t)kMaxSlo, 0u);
+    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+    ctx->counters_dirty = false;
+  }
+  ctx->counters_dirty = true;
+  {
+    PrepArgs p;
+    p.prompt_len = rq->prompt_len;
+    p.slo_class = rq->slo_class;
+    p.n_req = R;
+    p.n_slo = K;
+    p.lbuf = lbuf;
+    p.cls_count = ctx->cls_count;
+    p.n_bucket_blocks = (uint32_t)(((uint64_t)R + kBucketPerBlock - 1) / kBucketPerBlock);
+    p.tab = ctx->tab;
+    p.cells = ctx->cells;
+    p.mp = model_params(ctx, prm);
+    p.n_cand = C;
+    p.i_pad = I;
+    p.n_inst = pl->n_inst;
+    p.tp_idx = pl->tp_idx;
+    p.max_batch = pl->max_batch;
+    p.occ = pl->occ;
+    p.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
+    p.recs = recs;
+    p.sat_count = sat_count;
+    p.queues = queues;
+    p.n_queues = (uint32_t)plan.queue_words;
+    p.status = ctx->status;
+    const uint64_t n_stage = ((uint64_t)C * I + kStageSlotsPerBlock - 1) / kStageSlotsPerBlock;
+    const uint64_t n_prep = (uint64_t)p.n_bucket_blocks + n_stage;
+    if (n_prep > 0x7fffffffull) return MAASO_E_SHAPE;
+    size_t lds = (size_t)3 * ctx->cells * sizeof(float);
+    if (lds < 2 * kMaxSlo * sizeof(uint32_t)) lds = 2 * kMaxSlo * sizeof(uint32_t);
+    hipLaunchKernelGGL(sweep_prep_kernel, dim3((uint32_t)n_prep), dim3(256), lds, s, p);
+    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+  }
+  if (R != 0) {
+    SweepArgs a;
+    a.n_slo = K;
+    std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
+    std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
+    a.n_cand = C;
+    a.i_pad = I;
+    a.recs = recs;
+    a.lbuf = lbuf;
+    a.cls_count = ctx->cls_count;
+    a.n_req = R;
+    a.group = plan.G;
+    a.n_items = plan.n_items;
+    a.nrb_max = plan.nrb_max;
+    a.queues = queues;
+    a.sat_count = sat_count;
+    a.evaluated = reinterpret_cast<unsigned long long*>(queues + (size_t)plan.nrb_max * 8u);
+    {
+      TimedRegion timed(ctx, s);
+      switch (plan.Q) {
+        case 2: rc = launch_sweep<2>(a, plan.blocks, s); break;
+        case 4: rc = launch_sweep<4>(a, plan.blocks, s); break;
+        case 8: rc = launch_sweep<8>(a, plan.blocks, s); break;
+        default: rc = launch_sweep<16>(a, plan.blocks, s); break;
+      }
+    }
+    if (rc != MAASO_OK) return rc;
+  }
+  // evaluated-pairs total lands in the context's small device block, next to the class counters
+  unsigned long long* eval_total = reinterpret_cast<unsigned long long*>(ctx->status + 32);
+  hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
+                     best_cand, ctx->cls_count,
+                     reinterpret_cast<const unsigned long long*>(queues + (size_t)plan.nrb_max * 8u),
+                     R != 0 ? plan.blocks : 0u, eval_total);
+  ctx->last_evaluated = eval_total;
+  if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+  ctx->counters_dirty = false;
+  return MAASO_OK;
+}
+
 bool score_weights_ok(const maaso_score_weights* wts) {
   return wts && std::isfinite(wts->alpha) && std::isfinite(wts->beta) && wts->gamma_t > 0.0f &&
          wts->gamma_l > 0.0f && std::isfinite(wts->gamma_t) && std::isfinite(wts->gamma_l);
@@ -415,7 +558,7 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-  const uint32_t C = pl->n_cand, I = pl->i_pad, K = ctx->n_slo, R = rq->n_req;
+  const uint32_t C = pl->n_cand, I = pl->i_pad, R = rq->n_req;
 
   if (prm->window != 0u && R != 0) {
     // Capacity-aware form: one block per candidate walks the request windows on its own state copy.
@@ -436,124 +579,12 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
     return MAASO_OK;
   }
 
-  // Launch shape.  Q requests per lane (a block owns 256*Q requests of one class); G candidates per
-  // work item; bq persistent blocks per (request tile, XCD) queue.
-  uint32_t Q = ctx->sweep_q;
-  // measured: 16 pays from 2^17 requests on (fewer trips to LDS per request; below that the lower
-  // occupancy of its 102 registers costs more than it saves)
-  if (Q == 0) Q = R >= (1u << 17) ? 16u : (R >= (1u << 14) ? 8u : (R >= (1u << 12) ? 4u : 2u));
-  uint32_t G = (uint32_t)kGroupSlots / I;
-  if (G > (uint32_t)kMaxGroup) G = kMaxGroup;
-  // measured: items of about 256 instance slots (8 candidates of 32 slots a third full: 105 us against
-  // 110 with 4 or 16; full slots: 4 and 8 equal; 128 slots: 1, 2 equal) balance the per-item
-  // barrier against the tail of the dynamic queues
-  uint32_t g_want = ctx->sweep_group ? ctx->sweep_group : (256u / I ? 256u / I : 1u);
-  if (g_want < G) G = g_want;
-  const uint32_t n_items = (C + G - 1) / G;
-  const uint32_t tile = (uint32_t)kSweepThreads * Q;
-  const uint32_t nrb_max = (uint32_t)(((uint64_t)R + tile - 1) / tile) + K;  // >= tiles that exist
-  uint32_t bq = ctx->sweep_blocks_per_queue;
-  if (bq == 0) {
-    // measured: about twice as many blocks as can be resident (8 per compute unit) - the late
-    // starters fill the tail of the dynamic queues
-    bq = ((uint32_t)ctx->n_cu * 18u + 4u * nrb_max) / (8u * nrb_max);
-    if (bq == 0) bq = 1;
-  }
-  const uint32_t per_queue = (n_items + 7u) / 8u;
-  if (bq > per_queue) bq = per_queue ? per_queue : 1u;
-  const uint64_t blocks64 = (uint64_t)8 * nrb_max * bq;
-  if (blocks64 > 0x7fffffffull) return MAASO_E_SHAPE;
-
-  // workspace: class-bucketed prompt lengths | staged records | queue heads
-  auto up256 = [](size_t x) { return (x + 255) & ~size_t(255); };
-  const size_t lbuf_bytes = up256((size_t)K * (R ? R : 1u) * sizeof(float));
-  const size_t recs_bytes = up256((size_t)C * I * sizeof(float4));
-  // queue heads, then two 8-byte evaluated-pairs words per sweep block
-  const size_t queue_words = (size_t)nrb_max * 8u + 4u * (size_t)blocks64;
-  const size_t queue_bytes = up256(queue_words * sizeof(uint32_t));
-  rc = ensure_workspace(ctx, lbuf_bytes + recs_bytes + queue_bytes);
+  SweepPlan plan;
+  rc = plan_static_sweep(ctx, C, I, R, plan);
   if (rc != MAASO_OK) return rc;
-  unsigned char* wsb = static_cast<unsigned char*>(ctx->ws);
-  float* lbuf = reinterpret_cast<float*>(wsb);
-  float4* recs = reinterpret_cast<float4*>(wsb + lbuf_bytes);
-  uint32_t* queues = reinterpret_cast<uint32_t*>(wsb + lbuf_bytes + recs_bytes);
-
-  if (ctx->counters_dirty) {  // an earlier call failed between its launches
-    if (!hip_ok(hipMemsetAsync(ctx->cls_count, 0, kMaxSlo * sizeof(uint32_t), s))) return MAASO_E_HIP;
-    ctx->counters_dirty = false;
-  }
-  ctx->counters_dirty = true;
-  {
-    PrepArgs p;
-    p.prompt_len = rq->prompt_len;
-    p.slo_class = rq->slo_class;
-    p.n_req = R;
-    p.n_slo = K;
-    p.lbuf = lbuf;
-    p.cls_count = ctx->cls_count;
-    p.n_bucket_blocks = (uint32_t)(((uint64_t)R + kBucketPerBlock - 1) / kBucketPerBlock);
-    p.tab = ctx->tab;
-    p.cells = ctx->cells;
-    p.mp = model_params(ctx, prm);
-    p.n_cand = C;
-    p.i_pad = I;
-    p.n_inst = pl->n_inst;
-    p.tp_idx = pl->tp_idx;
-    p.max_batch = pl->max_batch;
-    p.occ = pl->occ;
-    p.q_ticks = reinterpret_cast<const uint64_t*>(pl->q_ticks);
-    p.recs = recs;
-    p.sat_count = sat_count;
-    p.queues = queues;
-    p.n_queues = (uint32_t)queue_words;
-    p.status = ctx->status;
-    const uint64_t n_stage = ((uint64_t)C * I + kStageSlotsPerBlock - 1) / kStageSlotsPerBlock;
-    const uint64_t n_prep = (uint64_t)p.n_bucket_blocks + n_stage;
-    if (n_prep > 0x7fffffffull) return MAASO_E_SHAPE;
-    size_t lds = (size_t)3 * ctx->cells * sizeof(float);
-    if (lds < 2 * kMaxSlo * sizeof(uint32_t)) lds = 2 * kMaxSlo * sizeof(uint32_t);
-    hipLaunchKernelGGL(sweep_prep_kernel, dim3((uint32_t)n_prep), dim3(256), lds, s, p);
-    if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-  }
-  if (R != 0) {
-    SweepArgs a;
-    a.n_slo = K;
-    std::memcpy(a.d_ttft, ctx->d_ttft, sizeof(a.d_ttft));
-    std::memcpy(a.d_tbt, ctx->d_tbt, sizeof(a.d_tbt));
-    a.n_cand = C;
-    a.i_pad = I;
-    a.recs = recs;
-    a.lbuf = lbuf;
-    a.cls_count = ctx->cls_count;
-    a.n_req = R;
-    a.group = G;
-    a.n_items = n_items;
-    a.nrb_max = nrb_max;
-    a.queues = queues;
-    a.sat_count = sat_count;
-    a.evaluated = reinterpret_cast<unsigned long long*>(queues + (size_t)nrb_max * 8u);
-    const uint32_t blocks = (uint32_t)blocks64;
-    {
-      TimedRegion timed(ctx, s);
-      switch (Q) {
-        case 2: rc = launch_sweep<2>(a, blocks, s); break;
-        case 4: rc = launch_sweep<4>(a, blocks, s); break;
-        case 8: rc = launch_sweep<8>(a, blocks, s); break;
-        default: rc = launch_sweep<16>(a, blocks, s); break;
-      }
-    }
-    if (rc != MAASO_OK) return rc;
-  }
-  // evaluated-pairs total lands in the context's small device block, next to the class counters
-  unsigned long long* eval_total = reinterpret_cast<unsigned long long*>(ctx->status + 32);
-  hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(1024), 0, s, sat_count, C, R, sat_ratio,
-                     best_cand, ctx->cls_count,
-                     reinterpret_cast<const unsigned long long*>(queues + (size_t)nrb_max * 8u),
-                     R != 0 ? (uint32_t)blocks64 : 0u, eval_total);
-  ctx->last_evaluated = eval_total;
-  if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-  ctx->counters_dirty = false;
-  return MAASO_OK;
+  rc = ensure_workspace(ctx, plan.bytes);
+  if (rc != MAASO_OK) return rc;
+  return launch_static_sweep(ctx, pl, rq, prm, plan, ctx->ws, sat_count, sat_ratio, best_cand, s);
 }
 
 int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,

@@ -64,6 +64,12 @@ __device__ __forceinline__ void raise_status(uint32_t* status, uint32_t bit) {
     atomicOr(status, bit);
 }
 
+// Fill of a few 32-bit words (a kernel, not a memset node, so that a caller may capture the call in a
+// HIP graph).
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t n, uint32_t v) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = v;
+}
+
 // v_min_f32 on values that are never NaN (the compiler's fminf adds a canonicalising v_max first).
 __device__ __forceinline__ float min_no_nan(float x, float y) {
   float r;
