@@ -252,6 +252,23 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
                           const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
                           uint32_t* best_cand, void* hip_stream);
 
+/* For callers that cannot allocate device memory while they call (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): maaso_placement_sweep with the same arguments, results
+ * and errors, whose static form (prm->window == 0) keeps its intermediate data - the class-bucketed
+ * prompt lengths, one staged 16-byte record per instance slot, the work-queue heads - in a device
+ * array of MAASO_NOALLOC_SCRATCH_BYTES that is part of the library image (every GPU the library runs
+ * on holds its own copy until the process ends).  The call contains no hipMalloc, hipFree or other
+ * allocating routine and no host synchronisation.  A shape that needs more - about
+ * 4*K*R + 16*C*i_pad bytes plus 20 bytes per launched block - is refused with MAASO_E_SHAPE before
+ * anything is launched.  (The capacity-aware form, window > 0, uses no scratch and is passed through.)
+ * All calls on one GPU share that GPU's array, whatever the context: calls that overlap in time on
+ * one GPU race on it - order them on one stream or with events.  Everything in the array that must
+ * start at zero is cleared by the call's own first launch. */
+#define MAASO_NOALLOC_SCRATCH_BYTES (8u << 20)
+int maaso_placement_sweep_noalloc(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                                  const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
+                                  uint32_t* best_cand, void* hip_stream);
+
 /* Weights and thresholds of the composite serving score (Sec. IV-D, Eq. 6): alpha prioritises SLO
  * satisfaction (the paper uses 4, and 10 in its ablation), beta in [0,1] balances throughput against
  * latency (0.3), gamma_t > 0 is the throughput that normalises to 1 (tokens/s), gamma_l > 0 the

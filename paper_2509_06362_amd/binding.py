@@ -18,6 +18,7 @@ LIB_PATH = Path(__file__).resolve().parent / "libmaaso.so"
 MAASO_MAX_INSTANCES = 256
 MAASO_MAX_SLO = 16
 MAASO_MAX_TABLE_CELLS = 2048
+MAASO_NOALLOC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = (
     "maaso_profile_tables_load", "maaso_ctx_destroy", "maaso_ctx_device_status", "maaso_strerror",
@@ -25,7 +26,7 @@ EXPORTS = (
     "maaso_ctx_kernel_elapsed", "maaso_ctx_sweep_evaluated", "maaso_score_assign",
     "maaso_placement_sweep", "maaso_placement_score", "maaso_split_by_slo",
     "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
-    "maaso_score_assign_selected", "maaso_placement_score_sets",
+    "maaso_score_assign_selected", "maaso_placement_score_sets", "maaso_placement_sweep_noalloc",
 )
 
 
@@ -107,6 +108,7 @@ def load_library() -> C.CDLL:
         lib.maaso_placement_sweep.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                               C.POINTER(Params), C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p]
+        lib.maaso_placement_sweep_noalloc.argtypes = lib.maaso_placement_sweep.argtypes
         lib.maaso_placement_score.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
                                               C.POINTER(Params), C.POINTER(ScoreWeights),
                                               C.POINTER(ScoreOut), C.c_void_p]
@@ -304,6 +306,20 @@ def maaso_placement_sweep(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_ba
         "maaso_placement_sweep")
 
 
+def maaso_placement_sweep_noalloc(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
+                                  n_req, prompt_len, out_len, slo_class, arrival_ticks=None, s_bar,
+                                  pen_kappa=0.0, tbt_mode=0, window=0, policy=0, sat_count,
+                                  sat_ratio=None, best_cand=None, stream=None) -> None:
+    import torch
+    pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
+    rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window), int(policy))
+    _check(load_library().maaso_placement_sweep_noalloc(
+        ctx.handle, C.byref(pl), C.byref(rq), C.byref(prm), _dptr(sat_count, torch.int32),
+        _dptr(sat_ratio, torch.float32), _dptr(best_cand, torch.int32), _stream_handle(stream)),
+        "maaso_placement_sweep_noalloc")
+
+
 def maaso_placement_score(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks,
                           n_req, prompt_len, out_len, slo_class, arrival_ticks=None, s_bar,
                           pen_kappa=0.0, tbt_mode=0, window=0, policy=0, alpha, beta, gamma_t, gamma_l,
@@ -438,9 +454,10 @@ class DeviceWorkload:
         return dict(s_bar=float(self.w.s_bar), pen_kappa=float(self.w.pen_kappa),
                     tbt_mode=int(self.w.tbt_mode), policy=int(self.w.policy))
 
-    def sweep(self, stream=None, out=None, window=0):
+    def sweep(self, stream=None, out=None, window=0, noalloc=False):
         """maaso_placement_sweep over all candidates; returns (sat_count, sat_ratio, best_cand).
-        window > 0 selects the capacity-aware form."""
+        window > 0 selects the capacity-aware form; noalloc the entry point that works in the
+        library's static scratch array."""
         import torch
         dev = self.prompt_len.device
         C_ = self.w.n_cand
@@ -448,7 +465,7 @@ class DeviceWorkload:
             out = (torch.empty(C_, dtype=torch.int32, device=dev),
                    torch.empty(C_, dtype=torch.float32, device=dev),
                    torch.empty(1, dtype=torch.int32, device=dev))
-        maaso_placement_sweep(
+        (maaso_placement_sweep_noalloc if noalloc else maaso_placement_sweep)(
             self.ctx, n_cand=C_, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
             max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, **self.request_args(),
             arrival_ticks=self.arrival_ticks if window else None, window=window,

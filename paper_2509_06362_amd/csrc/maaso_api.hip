@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -26,6 +27,13 @@ static_assert(MAASO_MAX_SLO == kMaxSlo, "header and kernels disagree on the clas
 constexpr uint32_t kMaxTimed = 256;
 constexpr size_t kSmallBytes = 256;
 
+// Workspace of maaso_placement_sweep_noalloc: device memory that exists from the moment the library
+// is loaded, one copy per GPU, so that the call has nothing to allocate.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; kernels are given the address resolved per device.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[MAASO_NOALLOC_SCRATCH_BYTES];
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
 struct maaso_ctx {
   int device;
   uint32_t n_tp, b_cap, cells, n_slo;
@@ -34,6 +42,7 @@ struct maaso_ctx {
   bool has_degree;      // the profile came with GPUs-per-instance figures
   uint32_t* status;     // device status word
   uint32_t* cls_count;  // device [kMaxSlo]
+  void* scratch_ptr;    // this device's copy of the static scratch array
   void* ws;             // device workspace, grow-only
   size_t ws_bytes;
   uint32_t sweep_q;      // 0 = automatic
@@ -133,6 +142,10 @@ int launch_sweep(const SweepArgs& a, uint32_t blocks, hipStream_t s) {
 int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t* cand_sel,
                       const maaso_requests* rq, const maaso_params* prm, const maaso_assign_out* out,
                       void* hip_stream);
+
+int placement_sweep_impl(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                         const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
+                         uint32_t* best_cand, void* hip_stream, bool static_scratch);
 
 void fill_assign_args(AssignArgs& a, const maaso_ctx* ctx, const maaso_placements* pl,
                       const maaso_requests* rq, const maaso_params* prm,
@@ -468,6 +481,16 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   }
   hipDeviceProp_t prop;
   if (!hip_ok(hipGetDeviceProperties(&prop, device))) { delete ctx; return MAASO_E_HIP; }
+  // address of this device's copy of the static scratch array (resolved once per device, with that
+  // device current)
+  if (device < kMaxDevices) {
+    void* sp = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!sp) {
+      if (!hip_ok(hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch))) || !sp) { delete ctx; return MAASO_E_HIP; }
+      g_scratch_ptr[device].store(sp, std::memory_order_release);
+    }
+    ctx->scratch_ptr = sp;
+  }
   ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   ctx->lds_per_block = prop.sharedMemPerBlock;
 
@@ -550,6 +573,24 @@ int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane,
 int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
                           uint32_t* best_cand, void* hip_stream) {
+  return placement_sweep_impl(ctx, pl, rq, prm, sat_count, sat_ratio, best_cand, hip_stream, false);
+}
+
+int maaso_placement_sweep_noalloc(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                                  const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
+                                  uint32_t* best_cand, void* hip_stream) {
+  return placement_sweep_impl(ctx, pl, rq, prm, sat_count, sat_ratio, best_cand, hip_stream, true);
+}
+
+}  // extern "C"
+
+namespace {
+
+// static_scratch: the static sweep works in the library's static device array instead of the
+// context's workspace and refuses what does not fit; nothing is allocated on that path.
+int placement_sweep_impl(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
+                         const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
+                         uint32_t* best_cand, void* hip_stream, bool static_scratch) {
   int rc = check_common(ctx, pl, rq, prm);
   if (rc != MAASO_OK) return rc;
   if (!sat_count) return MAASO_E_INVALID_ARG;
@@ -582,10 +623,20 @@ int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maas
   SweepPlan plan;
   rc = plan_static_sweep(ctx, C, I, R, plan);
   if (rc != MAASO_OK) return rc;
+  if (static_scratch) {
+    if (!ctx->scratch_ptr) return MAASO_E_HIP;
+    if (plan.bytes > (size_t)MAASO_NOALLOC_SCRATCH_BYTES) return MAASO_E_SHAPE;
+    return launch_static_sweep(ctx, pl, rq, prm, plan, ctx->scratch_ptr, sat_count, sat_ratio,
+                               best_cand, s);
+  }
   rc = ensure_workspace(ctx, plan.bytes);
   if (rc != MAASO_OK) return rc;
   return launch_static_sweep(ctx, pl, rq, prm, plan, ctx->ws, sat_count, sat_ratio, best_cand, s);
 }
+
+}  // namespace
+
+extern "C" {
 
 int maaso_placement_score(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, const maaso_score_weights* wts,

@@ -147,3 +147,26 @@ def test_header_is_plain_c_and_layouts_agree_with_the_binding(lib, tmp_path):
                                            binding.Params, binding.AssignOut, binding.ScoreWeights,
                                            binding.ScoreOut)]
     assert out[1] == "ok" and int(out[2]) == -1
+
+
+def test_static_scratch_array_is_visible_to_the_runtime(lib, tmp_path):
+    """hipGetSymbolAddress finds a device variable by name in the code object, so the static scratch
+    array of maaso_placement_sweep_noalloc must be a GLOBAL symbol there (a file-local one makes the
+    runtime abort at load).  Checked on the code object embedded in the built library."""
+    import shutil
+    import subprocess
+    llvm = Path("/opt/rocm/lib/llvm/bin")
+    bundler, readelf = llvm / "clang-offload-bundler", llvm / "llvm-readelf"
+    if not (bundler.exists() and readelf.exists() and shutil.which("objcopy")):
+        pytest.skip("llvm binutils not available")
+    fat = tmp_path / "fatbin"
+    subprocess.run(["objcopy", "-O", "binary", "--only-section=.hip_fatbin", str(binding.LIB_PATH),
+                    str(fat)], check=True)
+    co = tmp_path / "gfx950.co"
+    subprocess.run([str(bundler), "--unbundle", "--type=o", f"--input={fat}",
+                    "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={co}"], check=True)
+    syms = subprocess.run([str(readelf), "-s", str(co)], check=True, capture_output=True, text=True).stdout
+    rows = [l.split() for l in syms.splitlines() if l.strip().endswith("scratch") and "OBJECT" in l]
+    assert rows, "no scratch object in the device code object"
+    assert all(r[4] == "GLOBAL" for r in rows), rows
+    assert int(rows[0][2]) == binding.MAASO_NOALLOC_SCRATCH_BYTES
