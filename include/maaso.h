@@ -12,13 +12,25 @@
  *   - "HOST" pointers are read during the call and may be freed afterwards.  "DEVICE" pointers are
  *     caller-owned device memory (for example torch tensors) on the context's device; the library
  *     never frees or reallocates them.  The only memory the library owns is the context (device
- *     copies of the tables, a scratch workspace, a status word).
- *   - Compute calls are asynchronous on the given HIP stream (NULL = the default stream) and do no
- *     host synchronisation, except that a call needing a larger workspace than any call before it
- *     on that context grows the workspace first (one hipMalloc).  Outputs are valid once the stream
- *     has been synchronised.
- *   - A context may be used from one thread at a time; calls on one context that overlap in time
- *     (different streams) race on its workspace.  Use one context per concurrent stream.
+ *     copies of the tables, a workspace, a status word).
+ *   - Compute calls (maaso_score_assign, maaso_score_assign_selected, maaso_placement_sweep,
+ *     maaso_placement_sweep_noalloc, maaso_placement_score, maaso_placement_score_sets,
+ *     maaso_split_by_slo, maaso_ins_deploy_select, maaso_resource_partition) are asynchronous on the
+ *     given HIP stream (NULL = the default stream).  They allocate nothing, free nothing and do no
+ *     host synchronisation: the context's workspace is sized at maaso_profile_tables_load
+ *     (MAASO_DEFAULT_WORKSPACE_BYTES, enough for 65,536 candidates of 32 instance slots) and
+ *     changed only by maaso_ctx_reserve; a call whose shape needs more is refused with
+ *     MAASO_E_WORKSPACE before anything is launched.  Outputs are valid once the stream has been
+ *     synchronised.  The calls that do synchronise are the set-up and read-back calls:
+ *     maaso_profile_tables_load, maaso_profile_fit, maaso_ctx_reserve, maaso_ctx_destroy,
+ *     maaso_ctx_device_status, maaso_ctx_kernel_elapsed, maaso_ctx_sweep_evaluated.
+ *   - A context serves one call at a time.  Its workspace and accumulators are shared by its calls:
+ *     calls issued on one stream are ordered by that stream; a call issued on another stream than
+ *     the context's previous call is ordered behind it by the library (an event recorded on the
+ *     previous stream, awaited by the new one - no host wait; if the previous stream has been
+ *     destroyed meanwhile the device is synchronised instead).  A second thread entering while a
+ *     call's host part is running gets MAASO_E_BUSY.  For calls that should overlap on the GPU use
+ *     one context per stream.
  *   - Time is counted in ticks of 2^-20 s where integers are used (arrival_ticks, q_ticks).
  *   - Arithmetic is IEEE-754 binary32, round to nearest even, one rounding per operation (fused
  *     multiply-add where the model has one), so results do not depend on the launch configuration.
@@ -39,7 +51,10 @@ typedef enum {
   MAASO_E_TABLE = -3,       /* non-finite or non-positive table entry / deadline outside [2^-20,2^20] */
   MAASO_E_HIP = -4,         /* a HIP runtime call failed (no device, launch failure, ...)             */
   MAASO_E_NOMEM = -5,       /* host or device allocation failed                                       */
-  MAASO_E_TIMEOUT = -6      /* reported by maaso_ctx_device_status: an inter-window wait gave up      */
+  MAASO_E_TIMEOUT = -6,     /* reported by maaso_ctx_device_status: an inter-window wait gave up      */
+  MAASO_E_WORKSPACE = -7,   /* the call's shape needs a larger workspace: maaso_ctx_reserve first     */
+  MAASO_E_BUSY = -8,        /* another thread is inside a call on this context                        */
+  MAASO_E_RESIDENCY = -9    /* the windowed distributor's blocks cannot all be resident at once        */
 } maaso_status;
 
 #define MAASO_MAX_INSTANCES 256u   /* i_pad: instance slots per candidate                      */
@@ -49,13 +64,18 @@ typedef enum {
 #define MAASO_MAX_LEN 16777215u    /* prompt_len / out_len: exactly representable in binary32   */
 #define MAASO_MAX_GPUS 4096u       /* |G|: GPUs of a (sub-)cluster in the placer's outer algorithms */
 #define MAASO_MAX_REQUEST_SETS 4u  /* request sets scored by one maaso_placement_score_sets call   */
+#define MAASO_DEFAULT_WORKSPACE_BYTES (64u << 20) /* workspace a context is loaded with            */
+#define MAASO_COUNT_INCOMPLETE (1ull << 63) /* set in n_satisfied by a windowed call that gave up  */
 
 /* bits of the device status word (maaso_ctx_device_status) */
 #define MAASO_DEV_BAD_CLASS 1u     /* a request with slo_class >= n_slo was skipped (never satisfied) */
 #define MAASO_DEV_BAD_INSTANCE 2u  /* an instance with tp_idx >= n_tp or max_batch outside 1..b_cap was
                                       treated as absent */
 #define MAASO_DEV_WAIT_TIMEOUT 4u  /* the windowed distributor's inter-window wait exceeded its spin
-                                      limit; outputs of that call are incomplete */
+                                      limit.  Of that call: chosen / slack / latencies are written
+                                      for the windows scored before it gave up and untouched after,
+                                      n_satisfied has MAASO_COUNT_INCOMPLETE set, occ and q_ticks are
+                                      left as they were given */
 
 #define MAASO_DEV_BAD_CHAIN 8u     /* chain_offsets of maaso_ins_deploy_select not non-decreasing
                                       within [0, n_cand]; that chain was ignored */
@@ -109,6 +129,21 @@ int maaso_profile_tables_load(const maaso_profile_desc* desc, int device, maaso_
 
 /* Frees the context and everything it owns.  NULL is allowed.  Synchronises the device. */
 void maaso_ctx_destroy(maaso_ctx* ctx);
+
+/* Sizes the context's workspace so that no later compute call with at most max_cand candidates of
+ * i_pad instance slots and max_req requests is refused with MAASO_E_WORKSPACE, whatever launch shape
+ * it takes (set the launch-shape knobs before reserving: more blocks per queue need more).  The
+ * workspace holds, for the static sweep, the prompt lengths bucketed by class (4*K*R bytes), one
+ * 16-byte record per instance slot and the work-queue heads; 12 KiB for the windowed distributor;
+ * 4 bytes per 1024 requests for maaso_split_by_slo.  The windowed sweep, the scores and the static
+ * distributor use none.  Never shrinks.  A set-up call: it synchronises the device and reallocates
+ * when the workspace has to grow.  Errors: INVALID_ARG, SHAPE, HIP, NOMEM, BUSY. */
+int maaso_ctx_reserve(maaso_ctx* ctx, uint32_t max_cand, uint32_t i_pad, uint32_t max_req);
+
+/* Bytes of workspace the context holds and how many times it has been allocated since (and
+ * including) maaso_profile_tables_load - a compute call never changes either.  Either pointer may be
+ * NULL.  Errors: INVALID_ARG. */
+int maaso_ctx_workspace(maaso_ctx* ctx, uint64_t* bytes, uint32_t* allocations);
 
 /* Synchronises the context's device, returns the MAASO_DEV_* bits raised by kernels since the last
  * call in *bits (may be NULL) and clears them.  Returns MAASO_E_TIMEOUT if MAASO_DEV_WAIT_TIMEOUT is
@@ -221,7 +256,10 @@ typedef struct {
  * requests: occupancy and queued prefill ticks are added, the queue drains by the arrival time that
  * passed, and min(W,B) * elapsed / (s_bar * tbt_j) requests complete; blocked requests add no load.
  * After the last window the load is added and nothing drains.  window >= R behaves as one window.
- * Errors: INVALID_ARG, SHAPE, HIP, NOMEM - all detected on the host before any launch. */
+ * Windows of more than four requests run in one persistent kernel whose blocks meet at a device-wide
+ * barrier after every window, so all of them must be resident together: the kernel is launched
+ * cooperatively, which the runtime either guarantees or refuses (MAASO_E_RESIDENCY, nothing ran).
+ * Errors: INVALID_ARG, SHAPE, WORKSPACE, RESIDENCY, BUSY, HIP - all detected on the host. */
 int maaso_score_assign(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                        const maaso_params* prm, const maaso_assign_out* out, void* hip_stream);
 
@@ -247,7 +285,7 @@ int maaso_score_assign_selected(maaso_ctx* ctx, const maaso_placements* pl, cons
  * Outputs, DEVICE pointers: sat_count [C] (required), sat_ratio [C] = count / R (0 when R == 0; may
  * be NULL), best_cand [1] = lowest index among the largest counts (may be NULL).
  * The placements are not written in either form.
- * Errors: INVALID_ARG, SHAPE, HIP, NOMEM. */
+ * Errors: INVALID_ARG, SHAPE, WORKSPACE (static form), BUSY, HIP. */
 int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
                           uint32_t* best_cand, void* hip_stream);
@@ -322,7 +360,7 @@ int maaso_placement_score_sets(maaso_ctx* ctx, const maaso_placements* pl, uint3
  * in their original (arrival) order; *n_tight (DEVICE, [1]) receives |R_t|.  arrival_ticks_out is
  * required when rq->arrival_ticks is given and ignored otherwise.  Outputs must not alias inputs.
  * A request with slo_class >= n_slo raises MAASO_DEV_BAD_CLASS and stays with R_l.
- * Errors: INVALID_ARG, SHAPE, NOMEM, HIP. */
+ * Errors: INVALID_ARG, SHAPE, WORKSPACE, BUSY, HIP. */
 int maaso_split_by_slo(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_classes,
                        uint32_t* prompt_len_out, uint32_t* out_len_out, uint8_t* slo_class_out,
                        uint32_t* arrival_ticks_out, uint32_t* n_tight, void* hip_stream);

@@ -27,6 +27,7 @@ EXPORTS = (
     "maaso_placement_sweep", "maaso_placement_score", "maaso_split_by_slo",
     "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
     "maaso_score_assign_selected", "maaso_placement_score_sets", "maaso_placement_sweep_noalloc",
+    "maaso_ctx_reserve", "maaso_ctx_workspace",
 )
 
 
@@ -95,6 +96,8 @@ def load_library() -> C.CDLL:
         lib.maaso_ctx_set_launch_shape.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
                                                    C.c_uint32]
         lib.maaso_ctx_set_wait_limit.argtypes = [C.c_void_p, C.c_uint32]
+        lib.maaso_ctx_reserve.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32]
+        lib.maaso_ctx_workspace.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
         lib.maaso_ctx_kernel_timing.argtypes = [C.c_void_p, C.c_int]
         lib.maaso_ctx_kernel_elapsed.argtypes = [C.c_void_p, C.POINTER(C.c_float),
                                                  C.POINTER(C.c_uint32)]
@@ -218,6 +221,18 @@ def maaso_ctx_set_launch_shape(ctx: Context, sweep_requests_per_lane=0, sweep_gr
 
 def maaso_ctx_set_wait_limit(ctx: Context, polls: int) -> None:
     _check(load_library().maaso_ctx_set_wait_limit(ctx.handle, polls), "maaso_ctx_set_wait_limit")
+
+
+def maaso_ctx_reserve(ctx: Context, max_cand: int, i_pad: int, max_req: int) -> None:
+    _check(load_library().maaso_ctx_reserve(ctx.handle, int(max_cand), int(i_pad), int(max_req)),
+           "maaso_ctx_reserve")
+
+
+def maaso_ctx_workspace(ctx: Context):
+    """(bytes of workspace held, times it has been allocated)."""
+    b, n = C.c_uint64(0), C.c_uint32(0)
+    _check(load_library().maaso_ctx_workspace(ctx.handle, C.byref(b), C.byref(n)), "maaso_ctx_workspace")
+    return int(b.value), int(n.value)
 
 
 def maaso_ctx_kernel_timing(ctx: Context, enable: bool) -> None:

@@ -43,8 +43,15 @@ struct maaso_ctx {
   uint32_t* status;     // device status word
   uint32_t* cls_count;  // device [kMaxSlo]
   void* scratch_ptr;    // this device's copy of the static scratch array
-  void* ws;             // device workspace, grow-only
+  void* ws;             // device workspace: sized at load, resized only by maaso_ctx_reserve
   size_t ws_bytes;
+  uint32_t ws_allocations;  // how often the workspace has been allocated (load counts as one)
+  // one call at a time: the host part of a call is exclusive, and a call on another stream than the
+  // context's previous call is ordered behind it with an event
+  std::atomic<int> in_call;
+  hipEvent_t order_ev;
+  hipStream_t last_stream;
+  bool has_last;
   uint32_t sweep_q;      // 0 = automatic
   uint32_t sweep_group;  // 0 = automatic
   uint32_t sweep_blocks_per_queue;  // 0 = automatic
@@ -53,6 +60,7 @@ struct maaso_ctx {
   uint32_t window_blocks;  // 0 = automatic
   uint32_t spin_limit;     // polls of the inter-window barrier before a block gives up
   int n_cu;
+  int cooperative;      // the device launches cooperative grids (all blocks resident, or refused)
   size_t lds_per_block;
   // optional timing of the dominant kernel of each call (HIP events on the call's stream)
   bool timing;
@@ -94,7 +102,13 @@ struct TimedRegion {
   }
 };
 
-int ensure_workspace(maaso_ctx* ctx, size_t bytes) {
+// Compute calls never allocate: a call whose shape needs more than the context holds is refused.
+int need_workspace(const maaso_ctx* ctx, size_t bytes) {
+  return bytes <= ctx->ws_bytes ? MAASO_OK : MAASO_E_WORKSPACE;
+}
+
+// Set-up only (load, maaso_ctx_reserve): (re)allocates the workspace when it is too small.
+int alloc_workspace(maaso_ctx* ctx, size_t bytes) {
   if (bytes <= ctx->ws_bytes) return MAASO_OK;
   if (ctx->ws) {
     if (!hip_ok(hipDeviceSynchronize())) return MAASO_E_HIP;
@@ -105,8 +119,43 @@ int ensure_workspace(maaso_ctx* ctx, size_t bytes) {
   const size_t want = (bytes + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
   if (!hip_ok(hipMalloc(&ctx->ws, want))) { ctx->ws = nullptr; return MAASO_E_NOMEM; }
   ctx->ws_bytes = want;
+  ctx->ws_allocations += 1;
   return MAASO_OK;
 }
+
+// Exclusive use of a context by one call, and stream order between consecutive calls.  The context's
+// workspace, class counters and accumulators are shared by all its calls; calls issued on one stream
+// are ordered by the stream, and a call issued on another stream than the previous one is made to
+// wait for it: an event is recorded on the previous stream at that moment (it covers everything
+// issued there so far) and the new stream waits for it - no host synchronisation.  Should the
+// previous stream no longer exist, the device is synchronised instead.
+struct CallGuard {
+  maaso_ctx* ctx;
+  int rc;
+  CallGuard(maaso_ctx* c, hipStream_t s) : ctx(c), rc(MAASO_OK) {
+    int idle = 0;
+    if (!ctx->in_call.compare_exchange_strong(idle, 1, std::memory_order_acquire)) {
+      ctx = nullptr;
+      rc = MAASO_E_BUSY;
+      return;
+    }
+    if (ctx->has_last && ctx->last_stream != s) {
+      const bool ordered = hipEventRecord(ctx->order_ev, ctx->last_stream) == hipSuccess &&
+                           hipStreamWaitEvent(s, ctx->order_ev, 0) == hipSuccess;
+      if (!ordered) {
+        (void)hipGetLastError();
+        if (!hip_ok(hipDeviceSynchronize())) rc = MAASO_E_HIP;
+      }
+    }
+    ctx->last_stream = s;
+    ctx->has_last = true;
+  }
+  ~CallGuard() {
+    if (ctx) ctx->in_call.store(0, std::memory_order_release);
+  }
+  CallGuard(const CallGuard&) = delete;
+  CallGuard& operator=(const CallGuard&) = delete;
+};
 
 int check_common(const maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                  const maaso_params* prm) {
@@ -323,6 +372,25 @@ int plan_static_sweep(const maaso_ctx* ctx, uint32_t C, uint32_t I, uint32_t R, 
   return MAASO_OK;
 }
 
+// Workspace that no call with at most C candidates of I slots and R requests exceeds, whatever launch
+// shape it takes with the context's current knobs: the static sweep (its queue part bounded at two
+// requests per lane, where the grid has the most request tiles), the windowed distributor's
+// accumulators, the split's per-block counts.
+size_t workspace_bound(const maaso_ctx* ctx, uint32_t C, uint32_t I, uint32_t R) {
+  const uint64_t K = ctx->n_slo;
+  const size_t lbuf = up256((size_t)K * (R ? R : 1u) * sizeof(float));
+  const size_t recs = up256((size_t)C * I * sizeof(float4));
+  const uint64_t nrb = ((uint64_t)R + 2u * kSweepThreads - 1) / (2u * kSweepThreads) + K;
+  // blocks = 8 * nrb * bq with bq = floor((18 n_cu + 4 nrb) / (8 nrb)), at least 1
+  const uint64_t blocks = ctx->sweep_blocks_per_queue ? 8u * nrb * ctx->sweep_blocks_per_queue
+                                                      : (uint64_t)ctx->n_cu * 18u + 12u * nrb;
+  const size_t queue = up256((size_t)(nrb * 8u + 4u * blocks) * sizeof(uint32_t));
+  size_t need = lbuf + recs + queue;
+  if (need < sizeof(WindowWs)) need = sizeof(WindowWs);
+  const size_t split = (size_t)(((uint64_t)R + kSplitPerBlock - 1) / kSplitPerBlock + 1u) * sizeof(uint32_t);
+  return need < split ? split : need;
+}
+
 // The three launches of the static sweep on workspace `ws` (at least plan.bytes, 256-byte aligned).
 // Everything in the workspace that must start at zero is cleared by the first launch.
 int launch_static_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
@@ -431,6 +499,9 @@ const char* maaso_strerror(int status) {
     case MAASO_E_HIP: return "HIP runtime error";
     case MAASO_E_NOMEM: return "out of memory";
     case MAASO_E_TIMEOUT: return "inter-window wait timed out on the device";
+    case MAASO_E_WORKSPACE: return "workspace too small for this shape: call maaso_ctx_reserve first";
+    case MAASO_E_BUSY: return "the context is in use by another call";
+    case MAASO_E_RESIDENCY: return "the windowed distributor's blocks cannot all be resident on the device";
     default: return "unknown status";
   }
 }
@@ -462,9 +533,8 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   DeviceGuard guard(device);
   if (!guard.ok) return MAASO_E_HIP;
 
-  maaso_ctx* ctx = new (std::nothrow) maaso_ctx();
+  maaso_ctx* ctx = new (std::nothrow) maaso_ctx();  // value-initialised: every member starts at zero
   if (!ctx) return MAASO_E_NOMEM;
-  std::memset(ctx, 0, sizeof(*ctx));
   ctx->device = device;
   ctx->n_tp = d->n_tp;
   ctx->b_cap = d->b_cap;
@@ -493,6 +563,8 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   }
   ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   ctx->lds_per_block = prop.sharedMemPerBlock;
+  if (!hip_ok(hipDeviceGetAttribute(&ctx->cooperative, hipDeviceAttributeCooperativeLaunch, device)))
+    ctx->cooperative = 0;
 
   float* host = static_cast<float*>(std::malloc((size_t)3 * cells * sizeof(float)));
   if (!host) { delete ctx; return MAASO_E_NOMEM; }
@@ -503,6 +575,9 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->tab), ((size_t)3 * cells + d->n_tp) * 4)))
     rc = MAASO_E_NOMEM;
   if (rc == MAASO_OK && !hip_ok(hipMalloc(reinterpret_cast<void**>(&ctx->status), kSmallBytes))) rc = MAASO_E_NOMEM;
+  // the workspace is sized here, once: compute calls never allocate
+  if (rc == MAASO_OK) rc = alloc_workspace(ctx, (size_t)MAASO_DEFAULT_WORKSPACE_BYTES);
+  if (rc == MAASO_OK && !hip_ok(hipEventCreateWithFlags(&ctx->order_ev, hipEventDisableTiming))) rc = MAASO_E_HIP;
   if (rc == MAASO_OK) {
     // one small allocation, in 32-bit words: [0] status, [16..31] class counts, [32..35] evaluated
     // pairs of the last sweep (all; those without a wait), [36..37] admitted-count accumulator and
@@ -519,8 +594,11 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   }
   std::free(host);
   if (rc != MAASO_OK) {
+    if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
+    if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->tab) (void)hipFree(ctx->tab);
     if (ctx->status) (void)hipFree(ctx->status);
+    (void)hipGetLastError();
     delete ctx;
     return rc;
   }
@@ -536,6 +614,7 @@ void maaso_ctx_destroy(maaso_ctx* ctx) {
     if (ctx->ev_start[i]) (void)hipEventDestroy(ctx->ev_start[i]);
     if (ctx->ev_stop[i]) (void)hipEventDestroy(ctx->ev_stop[i]);
   }
+  if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
   if (ctx->ws) (void)hipFree(ctx->ws);
   if (ctx->tab) (void)hipFree(ctx->tab);
   if (ctx->status) (void)hipFree(ctx->status);
@@ -570,6 +649,25 @@ int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane,
   return MAASO_OK;
 }
 
+int maaso_ctx_reserve(maaso_ctx* ctx, uint32_t max_cand, uint32_t i_pad, uint32_t max_req) {
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  if (i_pad == 0 || i_pad > MAASO_MAX_INSTANCES || max_req > MAASO_MAX_REQUESTS) return MAASO_E_SHAPE;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  int idle = 0;
+  if (!ctx->in_call.compare_exchange_strong(idle, 1, std::memory_order_acquire)) return MAASO_E_BUSY;
+  const int rc = alloc_workspace(ctx, workspace_bound(ctx, max_cand ? max_cand : 1u, i_pad, max_req));
+  ctx->in_call.store(0, std::memory_order_release);
+  return rc;
+}
+
+int maaso_ctx_workspace(maaso_ctx* ctx, uint64_t* bytes, uint32_t* allocations) {
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  if (bytes) *bytes = ctx->ws_bytes;
+  if (allocations) *allocations = ctx->ws_allocations;
+  return MAASO_OK;
+}
+
 int maaso_placement_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_requests* rq,
                           const maaso_params* prm, uint32_t* sat_count, float* sat_ratio,
                           uint32_t* best_cand, void* hip_stream) {
@@ -598,6 +696,8 @@ int placement_sweep_impl(maaso_ctx* ctx, const maaso_placements* pl, const maaso
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
+  if (call.rc != MAASO_OK) return call.rc;
 
   const uint32_t C = pl->n_cand, I = pl->i_pad, R = rq->n_req;
 
@@ -629,7 +729,7 @@ int placement_sweep_impl(maaso_ctx* ctx, const maaso_placements* pl, const maaso
     return launch_static_sweep(ctx, pl, rq, prm, plan, ctx->scratch_ptr, sat_count, sat_ratio,
                                best_cand, s);
   }
-  rc = ensure_workspace(ctx, plan.bytes);
+  rc = need_workspace(ctx, plan.bytes);
   if (rc != MAASO_OK) return rc;
   return launch_static_sweep(ctx, pl, rq, prm, plan, ctx->ws, sat_count, sat_ratio, best_cand, s);
 }
@@ -659,6 +759,8 @@ int maaso_placement_score_sets(maaso_ctx* ctx, const maaso_placements* pl, uint3
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
+  if (call.rc != MAASO_OK) return call.rc;
   SweepWindowArgs a;
   fill_sweep_window_args(a, ctx, pl, prm);
   // longest set first: its blocks run longest, so they should start first
@@ -754,8 +856,10 @@ int maaso_split_by_slo(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
+  if (call.rc != MAASO_OK) return call.rc;
   const uint32_t n_blocks = (uint32_t)(((uint64_t)rq->n_req + kSplitPerBlock - 1) / kSplitPerBlock);
-  const int rc = ensure_workspace(ctx, (size_t)(n_blocks ? n_blocks : 1u) * sizeof(uint32_t));
+  const int rc = need_workspace(ctx, (size_t)(n_blocks ? n_blocks : 1u) * sizeof(uint32_t));
   if (rc != MAASO_OK) return rc;
   SplitArgs a;
   a.n_req = rq->n_req;
@@ -788,6 +892,8 @@ int maaso_ins_deploy_select(maaso_ctx* ctx, const maaso_placements* pl, const fl
   if (pl->i_pad == 0 || pl->i_pad > MAASO_MAX_INSTANCES || n_gpus > MAASO_MAX_GPUS) return MAASO_E_SHAPE;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
+  CallGuard call(ctx, static_cast<hipStream_t>(hip_stream));
+  if (call.rc != MAASO_OK) return call.rc;
   SelectArgs a;
   a.score = score;
   a.n_cand = pl->n_cand;
@@ -818,6 +924,8 @@ int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t
   if (n_gpus > MAASO_MAX_GPUS) return MAASO_E_SHAPE;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
+  CallGuard call(ctx, static_cast<hipStream_t>(hip_stream));
+  if (call.rc != MAASO_OK) return call.rc;
   PartitionArgs a;
   a.n_gpus = n_gpus;
   // initial share of the relaxed sub-cluster: floor(|R_l| / |R| * |G|), from the exact quotient
@@ -863,6 +971,8 @@ int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
+  if (call.rc != MAASO_OK) return call.rc;
 
   AssignArgs a;
   fill_assign_args(a, ctx, pl, rq, prm, out);
@@ -931,7 +1041,7 @@ int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t
 
   // Windowed: one persistent kernel; all blocks must be resident at once (one per compute unit at
   // most).  Each request is spread over LPR lanes so that a window fills the blocks.
-  rc = ensure_workspace(ctx, sizeof(WindowWs));
+  rc = need_workspace(ctx, sizeof(WindowWs));
   if (rc != MAASO_OK) return rc;
   WindowWs* ws = static_cast<WindowWs*>(ctx->ws);
   const uint32_t per_window = prm->window < R ? prm->window : R;
@@ -950,20 +1060,35 @@ int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t
   if (need < nb) nb = (uint32_t)(need ? need : 1);
   hipLaunchKernelGGL(window_init_kernel, dim3(1), dim3(256), 0, s, ws, a.n_satisfied);
   if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-  const uint32_t spin = ctx->spin_limit;
+  uint32_t spin = ctx->spin_limit;
+  uint32_t window_v = prm->window;
   const size_t wlds = (size_t)3 * ctx->cells * sizeof(float);  // profile tables in LDS
   TimedRegion timed(ctx, s);
+  // The kernel's device-wide barrier needs every block resident at once.  A cooperative launch
+  // guarantees that or is refused; where the device has none, the occupancy of the kernel decides on
+  // the host (and the bounded spin remains the net under other work on the device).
+  void* kargs[] = {&a, &window_v, &ws, &spin};
+  hipError_t launched = hipSuccess;
+  auto launch = [&](const void* fn) {
+    if (ctx->cooperative) {
+      launched = hipLaunchCooperativeKernel(fn, dim3(nb), dim3(kWindowThreads), kargs, (unsigned)wlds, s);
+    } else {
+      int per_cu = 0;
+      launched = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWindowThreads, wlds);
+      if (launched == hipSuccess && (uint64_t)per_cu * (uint64_t)ctx->n_cu < nb)
+        launched = hipErrorCooperativeLaunchTooLarge;
+      if (launched == hipSuccess)
+        launched = hipLaunchKernel(fn, dim3(nb), dim3(kWindowThreads), kargs, wlds, s);
+    }
+  };
 #define MAASO_LAUNCH_WINDOW(LPR)                                                                  \
   do {                                                                                            \
     if (prm->policy) /* latency outputs are null-checked in the kernel: one variant serves both */ \
-      hipLaunchKernelGGL((assign_window_kernel<LPR, true, true>), dim3(nb), dim3(kWindowThreads),  \
-                         wlds, s, a, prm->window, ws, spin);                                       \
+      launch(reinterpret_cast<const void*>(&assign_window_kernel<LPR, true, true>));               \
     else if (lat)                                                                                  \
-      hipLaunchKernelGGL((assign_window_kernel<LPR, true, false>), dim3(nb), dim3(kWindowThreads), \
-                         wlds, s, a, prm->window, ws, spin);                                       \
+      launch(reinterpret_cast<const void*>(&assign_window_kernel<LPR, true, false>));              \
     else                                                                                           \
-      hipLaunchKernelGGL((assign_window_kernel<LPR, false, false>), dim3(nb), dim3(kWindowThreads), \
-                         wlds, s, a, prm->window, ws, spin);                                       \
+      launch(reinterpret_cast<const void*>(&assign_window_kernel<LPR, false, false>));             \
   } while (0)
   switch (lpr) {
     case 1: MAASO_LAUNCH_WINDOW(1); break;
@@ -975,7 +1100,11 @@ int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t
     default: MAASO_LAUNCH_WINDOW(64); break;
   }
 #undef MAASO_LAUNCH_WINDOW
-  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+  if (launched == hipErrorCooperativeLaunchTooLarge) {
+    (void)hipGetLastError();
+    return MAASO_E_RESIDENCY;
+  }
+  return hip_ok(launched) && hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
 
 }  // namespace

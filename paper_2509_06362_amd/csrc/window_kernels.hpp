@@ -278,6 +278,8 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
     uint32_t t = 0;
     for (int wv = 0; wv < kWindowThreads / 64; ++wv) t += wave_sat[wv];
     if (t) atomicAdd(a.n_satisfied, (unsigned long long)t);
+    // a call that gave up marks its count as incomplete: the top bit survives every addition
+    if (!alive) atomicOr(a.n_satisfied, 1ull << 63);
   }
 }
 

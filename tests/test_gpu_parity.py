@@ -1222,10 +1222,14 @@ def test_inter_window_wait_gives_up_cleanly():
     dw = binding.DeviceWorkload(w)
     binding.maaso_ctx_set_launch_shape(dw.ctx, 0, 0, 0, 64)
     binding.maaso_ctx_set_wait_limit(dw.ctx, 0)
-    dw.assign(window=256)
+    occ0, q0 = dw.occ.clone(), dw.q_ticks.clone()
+    gave_up = dw.assign(window=256)
     with pytest.raises(binding.MaasoError) as e:
         binding.maaso_ctx_device_status(dw.ctx)
     assert e.value.status == -6
+    # what such a call leaves behind is defined: the count is marked incomplete, the state is as given
+    assert int(gave_up["n_satisfied"].item()) & (1 << 63) or int(gave_up["n_satisfied"].item()) < 0
+    assert torch.equal(gave_up["occ"], occ0[0:1]) and torch.equal(gave_up["q_ticks"], q0[0:1])
     binding.maaso_ctx_set_wait_limit(dw.ctx, 1 << 22)
     got = dw.assign(window=256)                      # the context is usable again
     torch.cuda.synchronize()
@@ -1233,3 +1237,124 @@ def test_inter_window_wait_gives_up_cleanly():
     ref = oracle.score_assign(w, window=256)
     assert np.array_equal(got["chosen"].cpu().numpy(), ref["chosen"])
     dw.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# the boundary's promises: no allocation in compute calls, order between streams, one call at a time
+# ------------------------------------------------------------------------------------------------
+
+def _all_compute_calls(dw, w, window):
+    """Every compute entry point once on the resident workload; returns the static sweep's counts."""
+    cnt = dw.sweep()[0].clone()
+    dw.sweep(window=window)
+    dw.sweep(noalloc=True)
+    dw.score(4.0, 0.3, 512.0, 0.5, window=window)
+    dw.score_sets([(0, w.n_req // 2), (w.n_req // 2, w.n_req)], 4.0, 0.3, 512.0, 0.5, window=window)
+    dw.assign(cand=0, window=0)
+    dw.assign(cand=0, window=window)
+    dw.assign(cand=0, window=1)
+    best = torch.zeros(1, dtype=torch.int32, device=cnt.device)
+    dw.assign_selected(best, window=0)
+    dw.resource_partition(np.array([0, w.n_cand], np.uint32), 0b1, 64, 4.0, 0.3, 512.0, 0.5, window=window)
+    torch.cuda.synchronize()
+    return u32(cnt)
+
+
+def test_compute_calls_never_allocate():
+    """After maaso_profile_tables_load (and one maaso_ctx_reserve for shapes beyond the default
+    workspace) no compute entry point changes the context's workspace, at growing shapes; a shape
+    beyond what is held is refused before anything runs."""
+    shapes = [(5, 8, 300), (60, 32, 5000), (300, 128, 20000), (20, 256, 70000)]
+    ws = [W.random_small(700 + i, c, ip, r, n_slo=3) for i, (c, ip, r) in enumerate(shapes)]
+    ws = [W.replace(w, arrival_ticks=W.poisson_arrivals(W.rng_for(700 + i, 3), 900.0, w.n_req))
+          for i, w in enumerate(ws)]
+    ctx0 = None
+    for w in ws:
+        dw = binding.DeviceWorkload(w)
+        try:
+            before = binding.maaso_ctx_workspace(dw.ctx)
+            assert before == (64 << 20, 1)
+            cnt = _all_compute_calls(dw, w, window=250)
+            assert binding.maaso_ctx_workspace(dw.ctx) == before
+            assert np.array_equal(cnt, oracle.placement_sweep(w)["sat_count"])
+            assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        finally:
+            dw.close()
+    # beyond the default: 150,000 candidates of 32 slots need 77 MB of records
+    big = W.config1(n_cand=150000, n_req=512)
+    dw = binding.DeviceWorkload(big)
+    try:
+        with pytest.raises(binding.MaasoError) as e:
+            dw.sweep()
+        assert e.value.status == -7 and "maaso_ctx_reserve" in str(e.value)
+        assert binding.maaso_ctx_workspace(dw.ctx) == (64 << 20, 1)
+        binding.maaso_ctx_reserve(dw.ctx, big.n_cand, big.i_pad, big.n_req)
+        held = binding.maaso_ctx_workspace(dw.ctx)
+        assert held[1] == 2 and held[0] >= 16 * 150000 * 32
+        for shape in ((0, 0, 0), (2, 1, 0), (16, 64, 0)):
+            binding.maaso_ctx_set_launch_shape(dw.ctx, shape[0], shape[1], shape[2], 0)
+            cnt = dw.sweep()[0]
+            torch.cuda.synchronize()
+            assert binding.maaso_ctx_workspace(dw.ctx) == held
+        binding.maaso_ctx_reserve(dw.ctx, 10, 8, 100)                 # never shrinks, nothing to do
+        assert binding.maaso_ctx_workspace(dw.ctx) == held
+        sample = [0, 77777, 149999]
+        for c in sample:
+            assert u32(cnt)[c] == oracle.placement_sweep(big, c, c + 1)["sat_count"][c]
+    finally:
+        dw.close()
+
+
+def test_calls_on_different_streams_are_ordered_by_the_library():
+    """One context, calls alternating between two streams without any wait in between: each call
+    works in the same workspace, so it must run behind the one before it."""
+    w = W.stressed(W.config1(n_cand=500, n_req=9000), seed=71)
+    ref = oracle.placement_sweep(w)
+    dw = binding.DeviceWorkload(w)
+    try:
+        streams = [torch.cuda.Stream(), torch.cuda.Stream(), None]
+        outs = []
+        for i in range(12):
+            st = streams[i % 3]
+            outs.append(dw.sweep(stream=st if st is not None else torch.cuda.default_stream()))
+        torch.cuda.synchronize()
+        for cnt, ratio, best in outs:
+            assert np.array_equal(u32(cnt), ref["sat_count"])
+            assert int(u32(best)[0]) == ref["best_cand"]
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+    finally:
+        dw.close()
+
+
+def test_a_second_thread_is_turned_away_not_mixed_in():
+    """Two host threads on one context: a call either runs (and is right) or is refused as busy."""
+    import threading
+    w = W.stressed(W.config1(n_cand=200, n_req=4000), seed=72)
+    ref = oracle.placement_sweep(w)["sat_count"]
+    dw = binding.DeviceWorkload(w)
+    results, busy, errors = [], [0], []
+
+    def worker():
+        torch.cuda.set_device(0)
+        for _ in range(60):
+            try:
+                results.append(dw.sweep()[0])
+            except binding.MaasoError as e:
+                if e.status == -8:
+                    busy[0] += 1
+                else:
+                    errors.append(e)
+    try:
+        ts = [threading.Thread(target=worker) for _ in range(2)]
+        for t in ts:
+            t.start()
+        for t in ts:
+            t.join()
+        torch.cuda.synchronize()
+        assert not errors
+        assert len(results) + busy[0] == 120 and len(results) >= 2
+        for cnt in results:
+            assert np.array_equal(u32(cnt), ref)
+        print(f"  {len(results)} calls ran, {busy[0]} were refused as busy", flush=True)
+    finally:
+        dw.close()
