@@ -178,6 +178,10 @@ int maaso_ctx_set_wait_limit(maaso_ctx* ctx, uint32_t polls);
  * Errors: INVALID_ARG, HIP. */
 int maaso_ctx_kernel_timing(maaso_ctx* ctx, int enable);
 int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches);
+/* The same series launch by launch, in the order issued: durations_ms [cap] (HOST) receives the
+ * first min(cap, recorded) durations in milliseconds, *launches their number; starts a new series.
+ * (Shows, for instance, whether the device's clock was still rising during a short series.) */
+int maaso_ctx_kernel_durations(maaso_ctx* ctx, float* durations_ms, uint32_t cap, uint32_t* launches);
 
 /* Synchronises the device and returns how many (request, instance) pairs the context's most recent
  * maaso_placement_sweep evaluated in its latency loop, i.e. the valid triples minus those whose

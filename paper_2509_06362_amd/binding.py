@@ -27,7 +27,7 @@ EXPORTS = (
     "maaso_placement_sweep", "maaso_placement_score", "maaso_split_by_slo",
     "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
     "maaso_score_assign_selected", "maaso_placement_score_sets", "maaso_placement_sweep_noalloc",
-    "maaso_ctx_reserve", "maaso_ctx_workspace",
+    "maaso_ctx_reserve", "maaso_ctx_workspace", "maaso_ctx_kernel_durations",
 )
 
 
@@ -101,6 +101,8 @@ def load_library() -> C.CDLL:
         lib.maaso_ctx_kernel_timing.argtypes = [C.c_void_p, C.c_int]
         lib.maaso_ctx_kernel_elapsed.argtypes = [C.c_void_p, C.POINTER(C.c_float),
                                                  C.POINTER(C.c_uint32)]
+        lib.maaso_ctx_kernel_durations.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_uint32,
+                                                   C.POINTER(C.c_uint32)]
         lib.maaso_ctx_sweep_evaluated.argtypes = [C.c_void_p, C.POINTER(C.c_uint64),
                                                   C.POINTER(C.c_uint64)]
         lib.maaso_score_assign.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
@@ -246,6 +248,15 @@ def maaso_ctx_kernel_elapsed(ctx: Context):
     _check(load_library().maaso_ctx_kernel_elapsed(ctx.handle, C.byref(ms), C.byref(n)),
            "maaso_ctx_kernel_elapsed")
     return float(ms.value), int(n.value)
+
+
+def maaso_ctx_kernel_durations(ctx: Context, cap: int = 256):
+    """Durations (ms) of the dominant kernel of each timed call since the last read, in issue order."""
+    buf = (C.c_float * cap)()
+    n = C.c_uint32(0)
+    _check(load_library().maaso_ctx_kernel_durations(ctx.handle, buf, cap, C.byref(n)),
+           "maaso_ctx_kernel_durations")
+    return [float(buf[i]) for i in range(n.value)]
 
 
 def maaso_ctx_sweep_evaluated(ctx: Context, split: bool = False):

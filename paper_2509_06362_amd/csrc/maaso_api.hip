@@ -1143,6 +1143,23 @@ int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches
   return MAASO_OK;
 }
 
+int maaso_ctx_kernel_durations(maaso_ctx* ctx, float* durations_ms, uint32_t cap, uint32_t* launches) {
+  if (!ctx || !durations_ms || !launches) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  const uint32_t n = ctx->n_timed < cap ? ctx->n_timed : cap;
+  for (uint32_t i = 0; i < n; ++i) {
+    float ms = 0.0f;
+    if (!hip_ok(hipEventSynchronize(ctx->ev_stop[i])) ||
+        !hip_ok(hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i])))
+      return MAASO_E_HIP;
+    durations_ms[i] = ms;
+  }
+  *launches = n;
+  ctx->n_timed = 0;
+  return MAASO_OK;
+}
+
 int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs, uint64_t* pairs_without_wait) {
   if (!ctx || !pairs) return MAASO_E_INVALID_ARG;
   *pairs = 0;
