@@ -1,48 +1,76 @@
 """CPU oracle of the profiler's least-squares fit.  TEST INFRASTRUCTURE ONLY.
 
 Throughput-decay function (Sec. IV-B, Eq. 1): F(w) = T0 * (1 - delta * log(eps + w)), w = min(B, W).
-The paper fits it to a limited set of throughput measurements by least squares and does not name a
-method; the reading taken here: for a fixed eps the model is the straight line y = alpha - beta * x in
-x = log(eps + w) (alpha = T0, beta = T0 * delta), fitted in closed form; eps minimises the remaining
-residual and is found by nested grid search on log(eps) - 256 points between the bounds, keep the best
-(lowest index on ties), continue between its two neighbours, 10 levels, answer = centre of the last
-bracket.  Plain numpy, binary64, one strategy at a time.
+The paper fits it to a limited set of throughput measurements by least squares.  This oracle is that
+definition written out: the parameters (T0, delta, eps), eps within the given bounds, that minimise
+
+    SSE(T0, delta, eps) = sum_i (F(w_i) - y_i)^2 .
+
+How the minimum is found is of no concern to the definition; here: the residual with (T0, delta)
+solved for by linear least squares (numpy.linalg.lstsq - for a fixed eps the model is linear in T0
+and T0*delta) is scanned densely over log(eps) to find the basin of the global minimum, and the
+three parameters are then refined together from there by scipy.optimize.least_squares on the
+residual vector F(w_i) - y_i with its analytic Jacobian, eps bounded.  Plain numpy/scipy, binary64,
+one strategy at a time.  The natural logarithm is taken ("logarithmic decay", base unstated).
+
+With fewer than three samples, or samples at fewer than two distinct workload levels, the fit is
+undefined (NaN).  With exactly two distinct levels the minimum is not unique in eps (every eps gives
+the same residual), so a comparison with another implementation is meaningless there.
 """
 from __future__ import annotations
 
 import numpy as np
+from scipy.optimize import least_squares
 
-GRID = 256
-LEVELS = 10
+SCAN_POINTS = 4001
 
 
-def line_fit(w, y, eps):
-    """Least-squares straight line through (log(eps + w_i), y_i): (alpha, beta, sse)."""
-    x = np.log(eps + w)
-    mx, my = x.sum() / len(x), y.sum() / len(y)
-    dx, dy = x - mx, y - my
-    sxx, sxy, syy = (dx * dx).sum(), (dx * dy).sum(), (dy * dy).sum()
-    if not sxx > 0.0:
-        return np.nan, np.nan, np.inf
-    slope = sxy / sxx
-    return my - slope * mx, -slope, syy - slope * sxy
+def model(params, w):
+    t0, delta, eps = params
+    return t0 * (1.0 - delta * np.log(eps + w))
+
+
+def sse(params, w, y):
+    r = model(params, w) - y
+    return float(r @ r)
+
+
+def _linear_part(w, y, eps):
+    """(T0, T0*delta) minimising the residual for a fixed eps, and that residual."""
+    a = np.stack([np.ones_like(w), -np.log(eps + w)], axis=1)
+    sol, *_ = np.linalg.lstsq(a, y, rcond=None)
+    r = a @ sol - y
+    return sol, float(r @ r)
 
 
 def fit_one(w, y, eps_lo, eps_hi):
     """(T0, delta, eps, sse) of one strategy's samples."""
     w = np.asarray(w, dtype=np.float64)
     y = np.asarray(y, dtype=np.float64)
-    if len(w) < 3:
+    if len(w) < 3 or len(np.unique(w)) < 2:
         return (np.nan,) * 4
     lo, hi = np.log(np.float64(eps_lo)), np.log(np.float64(eps_hi))
-    for _ in range(LEVELS):
-        les = [lo + (hi - lo) * (i / (GRID - 1)) for i in range(GRID)]
-        sse = [line_fit(w, y, np.exp(le))[2] for le in les]
-        best = int(np.argmin(sse))              # first minimum
-        lo, hi = les[max(best - 1, 0)], les[min(best + 1, GRID - 1)]
-    eps = np.exp(0.5 * (lo + hi))
-    alpha, beta, sse = line_fit(w, y, eps)
-    return alpha, beta / alpha, eps, sse
+    scan = np.linspace(lo, hi, SCAN_POINTS)
+    res = [_linear_part(w, y, np.exp(le)) for le in scan]
+    i = int(np.argmin([r[1] for r in res]))
+    (alpha, beta), _ = res[i]
+    if not np.isfinite(alpha) or alpha == 0.0:
+        return (np.nan,) * 4
+
+    def residuals(p):                       # p = (T0, delta, log eps)
+        return p[0] * (1.0 - p[1] * np.log(np.exp(p[2]) + w)) - y
+
+    def jacobian(p):
+        e = np.exp(p[2])
+        lg = np.log(e + w)
+        return np.stack([1.0 - p[1] * lg, -p[0] * lg, -p[0] * p[1] * e / (e + w)], axis=1)
+
+    out = least_squares(residuals, np.array([alpha, beta / alpha, scan[i]]), jac=jacobian,
+                        bounds=([-np.inf, -np.inf, lo], [np.inf, np.inf, hi]),
+                        xtol=1e-15, ftol=1e-15, gtol=1e-15, x_scale="jac")
+    t0, delta, le = out.x
+    eps = float(np.exp(le))
+    return float(t0), float(delta), eps, sse((t0, delta, eps), w, y)
 
 
 def profile_fit(offsets, level, thr, b_cap, eps_lo=2.0 ** -10, eps_hi=2.0 ** 10):
@@ -55,12 +83,12 @@ def profile_fit(offsets, level, thr, b_cap, eps_lo=2.0 ** -10, eps_hi=2.0 ** 10)
     b = np.arange(1, b_cap + 1, dtype=np.float64)
     for t in range(n_tp):
         s = slice(int(offsets[t]), int(offsets[t + 1]))
-        t0, delta, eps, sse = fit_one(level[s], thr[s], eps_lo, eps_hi)
-        params[t] = (t0, delta, eps, sse)
+        t0, delta, eps, res = fit_one(level[s], thr[s], eps_lo, eps_hi)
+        params[t] = (t0, delta, eps, res)
         if not np.isfinite(t0) or not t0 > 0:
             ok = False
             continue
-        f = t0 * (1.0 - delta * np.log(eps + b))
+        f = model((t0, delta, eps), b)
         ok = ok and bool((f > 0).all())
         with np.errstate(divide="ignore"):
             tbt[t, 1:] = (1.0 / f).astype(np.float32)

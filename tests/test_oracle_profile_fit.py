@@ -1,16 +1,25 @@
-"""Pins of the oracle's least-squares fit of the throughput-decay function (Sec. IV-B, Eq. 1)."""
+"""Pins of the oracle's least-squares fit of the throughput-decay function (Sec. IV-B, Eq. 1).
+
+The oracle is the definition (the parameters that minimise the squared residual); what fixes it from
+outside: noiseless samples return the parameters that generated them, no point of a brute-force grid
+around the answer or over the whole box has a smaller residual, the residual at the generating
+parameters is never below the fitted one, and the answer does not depend on where a search starts."""
 import numpy as np
 import pytest
 from scipy.optimize import least_squares
 
 import oracle
-from oracle.profile_fit import fit_one, line_fit
+from oracle.profile_fit import fit_one
 from paper_2509_06362_amd import workloads as W
 
 
 def sse_of(params, w, y):
     t0, delta, eps = params
     return float(((t0 * (1.0 - delta * np.log(eps + w)) - y) ** 2).sum())
+
+
+def samples_of(off, lv, th, t):
+    return lv[off[t]:off[t + 1]].astype(np.float64), th[off[t]:off[t + 1]].astype(np.float64)
 
 
 def test_noiseless_samples_give_the_parameters_back():
@@ -25,41 +34,59 @@ def test_noiseless_samples_give_the_parameters_back():
     assert np.isnan(tbt[:, 0]).all()
 
 
-def test_line_fit_is_the_linear_least_squares_solution():
-    rng = np.random.default_rng(2)
-    w = rng.uniform(1, 128, 40)
-    y = 100 * (1 - 0.1 * np.log(2.0 + w)) + rng.normal(0, 1, 40)
-    for eps in (0.01, 2.0, 300.0):
-        alpha, beta, sse = line_fit(w, y, eps)
-        A = np.stack([np.ones_like(w), -np.log(eps + w)], axis=1)
-        sol, res, *_ = np.linalg.lstsq(A, y, rcond=None)
-        assert np.allclose([alpha, beta], sol, rtol=1e-9)
-        assert sse == pytest.approx(float(res[0]), rel=1e-9)
+def test_a_hand_made_exact_case():
+    """Three samples on F(w) = 64 * (1 - 0.125 * log(1 + w)) at w = 1, 3, 7, i.e. log 2, 2 log 2, 3 log 2:
+    y = 64 - 8 k log 2.  Three parameters, three points: the residual must vanish there."""
+    w = np.array([1.0, 3.0, 7.0])
+    y = 64.0 - 8.0 * np.log(2.0) * np.array([1.0, 2.0, 3.0])
+    t0, delta, eps, res = fit_one(w, y, 2.0 ** -10, 2.0 ** 10)
+    assert res < 1e-18
+    assert np.allclose([t0, delta, eps], [64.0, 0.125, 1.0], rtol=1e-7)
 
 
 @pytest.mark.parametrize("seed,noise", [(3, 0.02), (4, 0.05), (5, 0.002), (6, 0.1)])
 def test_no_better_fit_exists(seed, noise):
-    """The residual at the oracle's answer is a minimum: a dense scan over eps does not beat it, a
-    three-parameter Gauss-Newton refinement started there does not move, and started elsewhere it
-    does not end lower."""
-    off, lv, th, _ = W.throughput_samples(seed, noise=noise, repeats=4)
+    off, lv, th, truth = W.throughput_samples(seed, noise=noise, repeats=4)
     params, _, ok = oracle.profile_fit(off, lv, th, 64)
     assert ok
+    rng = np.random.default_rng(seed)
     for t in range(len(off) - 1):
-        w = lv[off[t]:off[t + 1]].astype(np.float64)
-        y = th[off[t]:off[t + 1]].astype(np.float64)
-        t0, delta, eps, sse = params[t]
-        assert sse == pytest.approx(sse_of((t0, delta, eps), w, y), rel=1e-9)
-        dense = min(line_fit(w, y, e)[2] for e in np.exp(np.linspace(np.log(2.0 ** -10), np.log(2.0 ** 10), 20001)))
-        assert sse <= dense * (1 + 1e-12)
-        if 2.0 ** -10 * 1.01 < eps < 2.0 ** 10 * 0.99:           # interior minimum: stationary point
-            res = lambda p: p[0] * (1 - p[1] * np.log(p[2] + w)) - y  # noqa: E731
-            here = least_squares(res, [t0, delta, eps], xtol=1e-14, ftol=1e-14, gtol=1e-14)
-            assert 2 * here.cost >= sse * (1 - 1e-9)
-            assert np.allclose(here.x, [t0, delta, eps], rtol=1e-4)
+        w, y = samples_of(off, lv, th, t)
+        t0, delta, eps, res = params[t]
+        assert res == pytest.approx(sse_of((t0, delta, eps), w, y), rel=1e-12)
+        # the generating parameters are one admissible point
+        assert res <= sse_of(truth[t], w, y)
+        # brute force, local: no neighbour on a 3-D grid of relative steps is better
+        for step in (1e-2, 1e-4, 1e-6):
+            for d0 in (-1, 0, 1):
+                for d1 in (-1, 0, 1):
+                    for d2 in (-1, 0, 1):
+                        p = (t0 * (1 + d0 * step), delta * (1 + d1 * step), eps * (1 + d2 * step))
+                        if 2.0 ** -10 <= p[2] <= 2.0 ** 10:           # eps is bounded
+                            assert sse_of(p, w, y) >= res * (1 - 1e-12)
+        # brute force, global: random points of the whole box, each polished in (T0, delta) by the
+        # normal equations written out here
+        for le in rng.uniform(np.log(2.0 ** -10), np.log(2.0 ** 10), 300):
+            x = -np.log(np.exp(le) + w)
+            n = len(w)
+            sx, sy, sxx, sxy = x.sum(), y.sum(), (x * x).sum(), (x * y).sum()
+            beta = (n * sxy - sx * sy) / (n * sxx - sx * sx)
+            alpha = (sy - beta * sx) / n
+            assert sse_of((alpha, beta / alpha, np.exp(le)), w, y) >= res * (1 - 1e-9)
+        # a search started elsewhere does not end lower
+        if 2.0 ** -10 * 1.01 < eps < 2.0 ** 10 * 0.99:
+            fun = lambda p: p[0] * (1 - p[1] * np.log(p[2] + w)) - y  # noqa: E731
             for start in ([y.max(), 0.1, 1.0], [2 * y.max(), 0.05, 10.0]):
-                other = least_squares(res, start, bounds=([0, 0, 2.0 ** -10], [np.inf, 1, 2.0 ** 10]))
-                assert 2 * other.cost >= sse * (1 - 1e-9)
+                other = least_squares(fun, start, bounds=([0, 0, 2.0 ** -10], [np.inf, 1, 2.0 ** 10]))
+                assert 2 * other.cost >= res * (1 - 1e-9)
+
+
+def test_eps_at_a_bound():
+    """Samples whose best eps lies below the lower bound: the fit stays inside and lands on it."""
+    off, lv, th, _ = W.throughput_samples(8, noise=0.0, truth=[[100.0, 0.1, 2.0 ** -14]])
+    t0, delta, eps, res = fit_one(*samples_of(off, lv, th, 0), 2.0 ** -10, 2.0 ** 10)
+    assert eps == pytest.approx(2.0 ** -10, rel=1e-9)
+    assert np.allclose([t0, delta], [100.0, 0.1], rtol=1e-3)
 
 
 def test_degenerate_inputs():

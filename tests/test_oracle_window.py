@@ -106,3 +106,90 @@ def test_hand_worked_drain_rate():
         r = oracle.score_assign(w)
         assert r["n_satisfied"] == 2
         assert r["occ"].tolist() == [want], (occ0, gap)
+
+
+# ------------------------------------------------------------------------------------------------
+# the capacity-aware sweep (every candidate through the windowed distributor)
+# ------------------------------------------------------------------------------------------------
+
+def _windowed_case(seed, n_cand=7, i_pad=6, n_req=400, window=50):
+    w = W.stressed(W.random_small(seed, n_cand, i_pad, n_req, n_slo=3), seed=seed, deadline_scale=0.25)
+    return W.replace(w, window=window,
+                     arrival_ticks=W.poisson_arrivals(W.rng_for(seed, 3), 300.0, n_req))
+
+
+def test_windowed_sweep_of_the_hand_worked_example():
+    """Three candidates - the hand-worked instance, an empty deployment, the hand-worked instance
+    again - must give the hand-worked admitted count, zero, and the same count; the best candidate
+    is the first of the two equal ones."""
+    g = read_golden()
+    w1 = worked_example_workload(g)
+    rep3 = lambda x: np.ascontiguousarray(np.concatenate([x, x, x], axis=0))
+    w = W.replace(w1, n_inst=np.array([1, 0, 1], np.uint32), tp_idx=rep3(w1.tp_idx),
+                  max_batch=rep3(w1.max_batch), occ=rep3(w1.occ), q_ticks=rep3(w1.q_ticks))
+    s = oracle.placement_sweep_windowed(w)
+    n = int(g["n_satisfied"][0])
+    assert 0 < n < w.n_req
+    assert s["sat_count"].tolist() == [n, 0, n]
+    assert s["sat_ratio"].tolist() == [np.float32(n) / np.float32(w.n_req), 0.0,
+                                       np.float32(n) / np.float32(w.n_req)]
+    assert s["best_cand"] == 0
+    # with the loaded instance last only, it wins
+    w = W.replace(w, n_inst=np.array([0, 0, 1], np.uint32))
+    assert oracle.placement_sweep_windowed(w)["best_cand"] == 2
+
+
+@pytest.mark.parametrize("seed,window", [(31, 50), (32, 1), (33, 64), (34, 1000)])
+def test_windowed_sweep_candidate_by_candidate(seed, window):
+    """Candidate c of the sweep is the windowed distributor on that candidate alone, started from the
+    state as given; the caller's state is left alone; ratio = count / R; best = lowest index among
+    the largest counts."""
+    w = _windowed_case(seed, window=window)
+    occ0, q0 = w.occ.copy(), w.q_ticks.copy()
+    s = oracle.placement_sweep_windowed(w)
+    assert np.array_equal(w.occ, occ0) and np.array_equal(w.q_ticks, q0)
+    alone = [oracle.score_assign(w, cand=c)["n_satisfied"] for c in range(w.n_cand)]
+    assert s["sat_count"].tolist() == alone
+    assert len(set(alone)) > 1
+    assert np.array_equal(s["sat_ratio"], np.array(alone, np.float32) / np.float32(w.n_req))
+    assert s["best_cand"] == alone.index(max(alone))
+    # the admitted count is what the per-request outputs say
+    for c in (0, w.n_cand - 1):
+        r = oracle.score_assign(w, cand=c)
+        assert r["n_satisfied"] == int((r["slack"] >= 0).sum())
+
+
+def test_windowed_sweep_duplicated_candidate_goes_to_the_lowest_index():
+    w = _windowed_case(35)
+    s = oracle.placement_sweep_windowed(w)
+    top = s["best_cand"]
+    dup = lambda x: np.ascontiguousarray(np.concatenate([x, x[top:top + 1]], axis=0))
+    wd = W.replace(w, n_inst=dup(w.n_inst), tp_idx=dup(w.tp_idx), max_batch=dup(w.max_batch),
+                   occ=dup(w.occ), q_ticks=dup(w.q_ticks))
+    sd = oracle.placement_sweep_windowed(wd)
+    assert np.array_equal(sd["sat_count"][:-1], s["sat_count"])
+    assert sd["sat_count"][-1] == s["sat_count"][top]
+    assert sd["best_cand"] == top                      # the copy at the end does not displace it
+    front = lambda x: np.ascontiguousarray(np.concatenate([x[top:top + 1], x], axis=0))
+    wf = W.replace(w, n_inst=front(w.n_inst), tp_idx=front(w.tp_idx), max_batch=front(w.max_batch),
+                   occ=front(w.occ), q_ticks=front(w.q_ticks))
+    assert oracle.placement_sweep_windowed(wf)["best_cand"] == 0
+
+
+def test_windowed_sweep_subrange_is_the_full_runs_slice():
+    w = _windowed_case(36, n_cand=11)
+    full = oracle.placement_sweep_windowed(w)
+    for lo, hi in ((3, 9), (0, 1), (10, 11), (0, 11)):
+        part = oracle.placement_sweep_windowed(w, c_begin=lo, c_end=hi)
+        assert np.array_equal(part["sat_count"][lo:hi], full["sat_count"][lo:hi])
+        assert np.array_equal(part["sat_ratio"][lo:hi], full["sat_ratio"][lo:hi])
+        assert (part["sat_count"][:lo] == 0).all() and (part["sat_count"][hi:] == 0).all()
+        assert part["best_cand"] == lo + int(np.argmax(full["sat_count"][lo:hi]))
+
+
+def test_windowed_sweep_with_one_window_is_the_static_sweep():
+    w = _windowed_case(37, window=10**6)
+    a = oracle.placement_sweep(w)
+    b = oracle.placement_sweep_windowed(w)
+    assert np.array_equal(a["sat_count"], b["sat_count"]) and a["best_cand"] == b["best_cand"]
+    assert np.array_equal(a["sat_ratio"], b["sat_ratio"])
