@@ -61,6 +61,7 @@ struct maaso_ctx {
   uint32_t spin_limit;     // polls of the inter-window barrier before a block gives up
   int n_cu;
   int cooperative;      // the device launches cooperative grids (all blocks resident, or refused)
+  int sweep_resident[4];  // blocks of sweep_kernel<2|4|8|16> one compute unit holds at once
   size_t lds_per_block;
   // optional timing of the dominant kernel of each call (HIP events on the call's stream)
   bool timing;
@@ -326,6 +327,7 @@ struct SweepPlan {
   uint32_t n_items;   // ceil(C / G)
   uint32_t nrb_max;   // request-tile slots of the grid (>= tiles that exist)
   uint32_t blocks;    // 8 * nrb_max * blocks per (request tile, XCD) queue
+  uint32_t static_blocks;  // of them resident at the kernel's start
   size_t lbuf_bytes, recs_bytes, queue_words;
   size_t bytes;       // class-bucketed prompt lengths | staged records | queue heads and pair counts
 };
@@ -348,17 +350,25 @@ int plan_static_sweep(const maaso_ctx* ctx, uint32_t C, uint32_t I, uint32_t R, 
   const uint32_t n_items = (C + G - 1) / G;
   const uint32_t tile = (uint32_t)kSweepThreads * Q;
   const uint32_t nrb_max = (uint32_t)(((uint64_t)R + tile - 1) / tile) + K;  // >= tiles that exist
+  // Blocks: every (request tile, XCD) queue is served by bq persistent blocks.
+  const uint32_t per_queue = (n_items + 7u) / 8u;
   uint32_t bq = ctx->sweep_blocks_per_queue;
   if (bq == 0) {
-    // measured: about twice as many blocks as can be resident (8 per compute unit) - the late
-    // starters fill the tail of the dynamic queues
+    // measured: about twice as many blocks as can be resident (8 per compute unit) - a block that
+    // leaves makes room for one that has not started, so the compute units stay full while the
+    // queues of small request tiles run dry
     bq = ((uint32_t)ctx->n_cu * 18u + 4u * nrb_max) / (8u * nrb_max);
     if (bq == 0) bq = 1;
   }
-  const uint32_t per_queue = (n_items + 7u) / 8u;
   if (bq > per_queue) bq = per_queue ? per_queue : 1u;
   const uint64_t blocks64 = (uint64_t)8 * nrb_max * bq;
   if (blocks64 > 0x7fffffffull) return MAASO_E_SHAPE;
+  // the blocks the device holds at once start together: they take their first items without a trip
+  // to the queue
+  const int qi = Q == 2 ? 0 : (Q == 4 ? 1 : (Q == 8 ? 2 : 3));
+  uint64_t resident = (uint64_t)ctx->n_cu * (uint64_t)ctx->sweep_resident[qi];
+  if (resident > blocks64) resident = blocks64;
+  p.static_blocks = (uint32_t)(resident & ~7ull);
   p.Q = Q;
   p.G = G;
   p.n_items = n_items;
@@ -456,6 +466,7 @@ int launch_static_sweep(maaso_ctx* ctx, const maaso_placements* pl, const maaso_
     a.n_items = plan.n_items;
     a.nrb_max = plan.nrb_max;
     a.queues = queues;
+    a.static_blocks = plan.static_blocks;
     a.sat_count = sat_count;
     a.evaluated = reinterpret_cast<unsigned long long*>(queues + (size_t)plan.nrb_max * 8u);
     {
@@ -565,6 +576,15 @@ int maaso_profile_tables_load(const maaso_profile_desc* d, int device, maaso_ctx
   ctx->lds_per_block = prop.sharedMemPerBlock;
   if (!hip_ok(hipDeviceGetAttribute(&ctx->cooperative, hipDeviceAttributeCooperativeLaunch, device)))
     ctx->cooperative = 0;
+  {
+    const void* fn[4] = {reinterpret_cast<const void*>(&sweep_kernel<2>), reinterpret_cast<const void*>(&sweep_kernel<4>),
+                         reinterpret_cast<const void*>(&sweep_kernel<8>), reinterpret_cast<const void*>(&sweep_kernel<16>)};
+    for (int i = 0; i < 4; ++i) {
+      int n = 0;
+      if (!hip_ok(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn[i], kSweepThreads, 0)) || n < 1) n = 4;
+      ctx->sweep_resident[i] = n;
+    }
+  }
 
   float* host = static_cast<float*>(std::malloc((size_t)3 * cells * sizeof(float)));
   if (!host) { delete ctx; return MAASO_E_NOMEM; }

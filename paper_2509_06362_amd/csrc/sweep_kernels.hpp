@@ -84,10 +84,169 @@ __device__ __forceinline__ float min3_no_nan(float x, float y, float z) {
   return r;
 }
 
+// v[lane] = value for a uniform value and lane index (both scalar).  The instruction reads one scalar
+// register beside M0, so the lane index travels through M0.
+__device__ __forceinline__ void write_lane(uint32_t& v, uint32_t value, uint32_t lane_index) {
+  asm("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(v) : "s"(value), "s"(lane_index) : "m0");
+}
+
 __device__ __forceinline__ float max_no_nan(float x, float y) {
   float r;
   asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
   return r;
+}
+
+// First-token latency of a lane's Q requests on one listed instance: prefill (fused), plus the queue
+// wait where the instance has one.  A record is {p, a, wait, tbt}.
+template <int Q, bool kWait>
+__device__ __forceinline__ void fold_first(float (&m)[Q], const float (&L)[Q], const float4* p) {
+  const float4 r = p[0];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) m[q] = kWait ? r.z + fmaf(r.x, L[q], r.y) : fmaf(r.x, L[q], r.y);
+}
+
+template <int Q, bool kWait>
+__device__ __forceinline__ void fold_one(float (&m)[Q], const float (&L)[Q], const float4* p) {
+  const float4 r = p[0];
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    m[q] = min_no_nan(m[q], kWait ? r.z + fmaf(r.x, L[q], r.y) : fmaf(r.x, L[q], r.y));
+}
+
+// Two records folded into the running minimum with ONE three-input minimum per request: per request
+// fma, fma (each followed by the add of the queue wait where there is one), min3.  The sequence is
+// fixed here instead of being left to the compiler's scheduler: two requests are interleaved so that
+// no instruction reads the result of the one just before it, and four temporaries serve all requests
+// (scheduled freely, the 2*Q products of a pair were all formed first, and with several pairs
+// unrolled the kernel spilled).  v_fma_f32 / v_add_f32 / v_min3_f32 are the instructions the compiler
+// emits for fmaf, + and a NaN-free minimum, so the values are the same bit for bit.
+// Operands: %0-%(N-1) running minima, then 4 temporaries, then N prompt lengths, then p, a of the two
+// records (and their waits).
+#define MAASO_FOLD2(MA, MB, LA, LB, T0, T1, T2, T3, RX, RY, UX, UY)                                  \
+  "v_fma_f32 " T0 ", " RX ", " LA ", " RY "\n\t" "v_fma_f32 " T1 ", " UX ", " LA ", " UY "\n\t"        \
+  "v_fma_f32 " T2 ", " RX ", " LB ", " RY "\n\t" "v_fma_f32 " T3 ", " UX ", " LB ", " UY "\n\t"        \
+  "v_min3_f32 " MA ", " MA ", " T0 ", " T1 "\n\t" "v_min3_f32 " MB ", " MB ", " T2 ", " T3 "\n\t"
+#define MAASO_FOLD2W(MA, MB, LA, LB, T0, T1, T2, T3, RX, RY, UX, UY, RZ, UZ)                         \
+  "v_fma_f32 " T0 ", " RX ", " LA ", " RY "\n\t" "v_fma_f32 " T1 ", " UX ", " LA ", " UY "\n\t"        \
+  "v_fma_f32 " T2 ", " RX ", " LB ", " RY "\n\t" "v_fma_f32 " T3 ", " UX ", " LB ", " UY "\n\t"        \
+  "v_add_f32 " T0 ", " RZ ", " T0 "\n\t" "v_add_f32 " T1 ", " UZ ", " T1 "\n\t"                       \
+  "v_add_f32 " T2 ", " RZ ", " T2 "\n\t" "v_add_f32 " T3 ", " UZ ", " T3 "\n\t"                       \
+  "v_min3_f32 " MA ", " MA ", " T0 ", " T1 "\n\t" "v_min3_f32 " MB ", " MB ", " T2 ", " T3 "\n\t"
+
+template <bool kWait>
+__device__ __forceinline__ void fold_pair_n(float (&m)[2], const float (&L)[2], const float4& r,
+                                            const float4& u) {
+  float t0, t1, t2, t3;
+  if (kWait)
+    asm(MAASO_FOLD2W("%0", "%1", "%6", "%7", "%2", "%3", "%4", "%5", "%8", "%9", "%10", "%11", "%12", "%13")
+        : "+v"(m[0]), "+v"(m[1]), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(L[0]), "v"(L[1]), "v"(r.x), "v"(r.y), "v"(u.x), "v"(u.y), "v"(r.z), "v"(u.z));
+  else
+    asm(MAASO_FOLD2("%0", "%1", "%6", "%7", "%2", "%3", "%4", "%5", "%8", "%9", "%10", "%11")
+        : "+v"(m[0]), "+v"(m[1]), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(L[0]), "v"(L[1]), "v"(r.x), "v"(r.y), "v"(u.x), "v"(u.y));
+}
+
+template <bool kWait>
+__device__ __forceinline__ void fold_pair_n(float (&m)[4], const float (&L)[4], const float4& r,
+                                            const float4& u) {
+  float t0, t1, t2, t3;
+  if (kWait)
+    asm(MAASO_FOLD2W("%0", "%1", "%8", "%9", "%4", "%5", "%6", "%7", "%12", "%13", "%14", "%15", "%16", "%17")
+        MAASO_FOLD2W("%2", "%3", "%10", "%11", "%4", "%5", "%6", "%7", "%12", "%13", "%14", "%15", "%16", "%17")
+        : "+v"(m[0]), "+v"(m[1]), "+v"(m[2]), "+v"(m[3]), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(L[0]), "v"(L[1]), "v"(L[2]), "v"(L[3]), "v"(r.x), "v"(r.y), "v"(u.x), "v"(u.y), "v"(r.z),
+          "v"(u.z));
+  else
+    asm(MAASO_FOLD2("%0", "%1", "%8", "%9", "%4", "%5", "%6", "%7", "%12", "%13", "%14", "%15")
+        MAASO_FOLD2("%2", "%3", "%10", "%11", "%4", "%5", "%6", "%7", "%12", "%13", "%14", "%15")
+        : "+v"(m[0]), "+v"(m[1]), "+v"(m[2]), "+v"(m[3]), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(L[0]), "v"(L[1]), "v"(L[2]), "v"(L[3]), "v"(r.x), "v"(r.y), "v"(u.x), "v"(u.y));
+}
+
+template <bool kWait>
+__device__ __forceinline__ void fold_pair_n(float (&m)[8], const float (&L)[8], const float4& r,
+                                            const float4& u) {
+  float t0, t1, t2, t3;
+  if (kWait)
+    asm(MAASO_FOLD2W("%0", "%1", "%12", "%13", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23", "%24", "%25")
+        MAASO_FOLD2W("%2", "%3", "%14", "%15", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23", "%24", "%25")
+        MAASO_FOLD2W("%4", "%5", "%16", "%17", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23", "%24", "%25")
+        MAASO_FOLD2W("%6", "%7", "%18", "%19", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23", "%24", "%25")
+        : "+v"(m[0]), "+v"(m[1]), "+v"(m[2]), "+v"(m[3]), "+v"(m[4]), "+v"(m[5]), "+v"(m[6]), "+v"(m[7]),
+          "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(L[0]), "v"(L[1]), "v"(L[2]), "v"(L[3]), "v"(L[4]), "v"(L[5]), "v"(L[6]), "v"(L[7]), "v"(r.x),
+          "v"(r.y), "v"(u.x), "v"(u.y), "v"(r.z), "v"(u.z));
+  else
+    asm(MAASO_FOLD2("%0", "%1", "%12", "%13", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23")
+        MAASO_FOLD2("%2", "%3", "%14", "%15", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23")
+        MAASO_FOLD2("%4", "%5", "%16", "%17", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23")
+        MAASO_FOLD2("%6", "%7", "%18", "%19", "%8", "%9", "%10", "%11", "%20", "%21", "%22", "%23")
+        : "+v"(m[0]), "+v"(m[1]), "+v"(m[2]), "+v"(m[3]), "+v"(m[4]), "+v"(m[5]), "+v"(m[6]), "+v"(m[7]),
+          "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(L[0]), "v"(L[1]), "v"(L[2]), "v"(L[3]), "v"(L[4]), "v"(L[5]), "v"(L[6]), "v"(L[7]), "v"(r.x),
+          "v"(r.y), "v"(u.x), "v"(u.y));
+}
+
+template <int Q, bool kWait>
+__device__ __forceinline__ void fold_pair(float (&m)[Q], const float (&L)[Q], const float4* p) {
+  static_assert(Q == 2 || Q == 4 || Q == 8 || Q == 16, "requests per lane");
+  const float4 r = p[0];
+  const float4 u = p[1];
+  if constexpr (Q == 16) {  // an asm statement takes at most 30 operands: two halves of eight requests
+    fold_pair_n<kWait>(reinterpret_cast<float (&)[8]>(m[0]), reinterpret_cast<const float (&)[8]>(L[0]), r, u);
+    fold_pair_n<kWait>(reinterpret_cast<float (&)[8]>(m[8]), reinterpret_cast<const float (&)[8]>(L[8]), r, u);
+  } else {
+    fold_pair_n<kWait>(m, L, r, u);
+  }
+}
+
+// Smallest first-token latency over a list of n > 0 records (uniform n, LDS list).  `fresh`: m holds
+// nothing yet and is initialised from the list's first record(s).  After an odd record (or the
+// initialising one or two) the list is walked in pairs: blocks of eight pairs (four with 16 requests
+// per lane) in a loop, then the rest in straight-line pieces of four, two and one pairs - constant
+// LDS offsets inside a piece, so its reads are issued ahead of the arithmetic, and next to nothing is
+// spent on loop control for the short lists of typical candidate deployments.
+template <int Q, bool kWait>
+__device__ __forceinline__ void walk_list(float (&m)[Q], const float (&L)[Q], const float4* p,
+                                          uint32_t n, bool fresh) {
+  if (fresh) {
+    if (n & 1u) {
+      fold_first<Q, kWait>(m, L, p);
+      p += 1;
+    } else {
+      fold_first<Q, kWait>(m, L, p);
+      fold_one<Q, kWait>(m, L, p + 1);
+      p += 2;
+    }
+    n = (n - 1u) >> 1;
+  } else {
+    if (n & 1u) {
+      fold_one<Q, kWait>(m, L, p);
+      p += 1;
+    }
+    n >>= 1;
+  }
+  // pairs per block of the loop: the records of a block are all in flight at once (three registers
+  // each), so with 16 requests per lane a block is four pairs
+  constexpr uint32_t kBlock = Q <= 8 ? 8u : 4u;
+  for (; n >= kBlock; n -= kBlock, p += 2u * kBlock) {
+#pragma unroll
+    for (uint32_t k = 0; k < kBlock; ++k) fold_pair<Q, kWait>(m, L, p + 2u * k);
+  }
+  // what is left of a block, by the binary digits of its pair count: straight-line pieces of four,
+  // two and one pairs behind plain uniform branches
+  if (kBlock > 4u && (n & 4u)) {
+#pragma unroll
+    for (uint32_t k = 0; k < 4u; ++k) fold_pair<Q, kWait>(m, L, p + 2u * k);
+    p += 8;
+  }
+  if (n & 2u) {
+    fold_pair<Q, kWait>(m, L, p);
+    fold_pair<Q, kWait>(m, L, p + 2);
+    p += 4;
+  }
+  if (n & 1u) fold_pair<Q, kWait>(m, L, p);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -220,6 +379,8 @@ struct SweepArgs {
   uint32_t n_items;  // ceil(n_cand / G)
   uint32_t nrb_max;  // request-tile slots of the grid (>= tiles that exist)
   uint32_t* queues;  // [nrb_max][8] next position of each (request tile, XCD) queue
+  uint32_t static_blocks;  // blocks (a multiple of 8) resident at the kernel's start: they take their
+                           // first two items by rank instead of from the queue
   uint32_t* sat_count;
   unsigned long long* evaluated;  // [2][gridDim.x] per block: (request, instance) pairs that reached
                                   // the latency loop (zero on entry; summed by the finalize kernel)
@@ -236,8 +397,54 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a) {
   const uint32_t lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t xcd = blockIdx.x & 7u;
-  const uint32_t rb = (blockIdx.x >> 3) % a.nrb_max;
+  const uint32_t slot = blockIdx.x >> 3;  // this block's place among the blocks of its XCD
+  const uint32_t rb = slot % a.nrb_max;
   const uint32_t G = a.group, I = a.i_pad;
+
+  // Work items of this block.  Its (request tile, XCD) queue holds the groups xcd, xcd + 8, ...  The
+  // blocks that are resident when the kernel starts (the first a.static_blocks of the grid) take
+  // their first two items by their rank among the queue's blocks - no memory access, so the records
+  // of the first item are requested before anything else; every further item, and every item of a
+  // block that starts later, comes from the queue's counter.
+  uint32_t* queue = a.queues + (size_t)rb * 8u + xcd;
+  const uint32_t rank = slot / a.nrb_max;
+  const uint32_t static_slots = a.static_blocks >> 3;
+  const uint32_t n_static = static_slots > rb ? (static_slots - 1u - rb) / a.nrb_max + 1u : 0u;  // on this queue
+  const uint32_t dynamic_base = 2u * n_static;
+  uint32_t cur, nxt;
+  if (rank < n_static) {
+    cur = xcd + 8u * rank;
+    nxt = xcd + 8u * (rank + n_static);
+  } else {
+    if (tid == 0u) {
+      items[0] = xcd + 8u * (dynamic_base + atomicAdd(queue, 1u));
+      items[1] = xcd + 8u * (dynamic_base + atomicAdd(queue, 1u));
+    }
+    __syncthreads();
+    cur = __builtin_amdgcn_readfirstlane(items[0]);
+    nxt = __builtin_amdgcn_readfirstlane(items[1]);
+    __syncthreads();  // items[] is written again in the loop
+  }
+  if (cur >= a.n_items) return;
+
+  // staging slot(s) of this thread inside a group
+  uint32_t s_cl[kSlotsPerThread], s_j[kSlotsPerThread];
+#pragma unroll
+  for (int u = 0; u < kSlotsPerThread; ++u) {
+    const uint32_t s = u * kSweepThreads + tid;
+    s_cl[u] = s / I;
+    s_j[u] = s - s_cl[u] * I;
+  }
+  auto load_group = [&](uint32_t item, float4 (&rec)[kSlotsPerThread]) {
+#pragma unroll
+    for (int u = 0; u < kSlotsPerThread; ++u) {
+      const uint32_t c = item * G + s_cl[u];
+      rec[u] = make_float4(0.0f, 0.0f, INFINITY, INFINITY);
+      if (item < a.n_items && s_cl[u] < G && c < a.n_cand) rec[u] = a.recs[(size_t)c * I + s_j[u]];
+    }
+  };
+  float4 rec0[kSlotsPerThread];
+  load_group(cur, rec0);  // in flight while the tile is looked up
 
   // The request tile of this block: tiles of 256*Q requests, class after class.
   constexpr uint32_t kTile = kSweepThreads * Q;
@@ -271,34 +478,9 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a) {
   }
   const bool any_req = wave_reqs != 0u;
 
-  uint32_t* queue = a.queues + (size_t)rb * 8u + xcd;
-  if (tid == 0u) {
-    items[0] = xcd + 8u * atomicAdd(queue, 1u);
-    items[1] = xcd + 8u * atomicAdd(queue, 1u);
-  }
   for (uint32_t i = tid; i < 6u * kMaxGroup; i += kSweepThreads) (&lens[0][0][0])[i] = 0u;
   __syncthreads();
-  // uniform by construction; held in scalar registers so that the candidate loop is a scalar loop
-  uint32_t cur = __builtin_amdgcn_readfirstlane(items[0]);
-  uint32_t nxt = __builtin_amdgcn_readfirstlane(items[1]);
-  if (cur >= a.n_items) return;
 
-  // staging slot(s) of this thread inside a group
-  uint32_t s_cl[kSlotsPerThread], s_j[kSlotsPerThread];
-#pragma unroll
-  for (int u = 0; u < kSlotsPerThread; ++u) {
-    const uint32_t s = u * kSweepThreads + tid;
-    s_cl[u] = s / I;
-    s_j[u] = s - s_cl[u] * I;
-  }
-  auto load_group = [&](uint32_t item, float4 (&rec)[kSlotsPerThread]) {
-#pragma unroll
-    for (int u = 0; u < kSlotsPerThread; ++u) {
-      const uint32_t c = item * G + s_cl[u];
-      rec[u] = make_float4(0.0f, 0.0f, INFINITY, INFINITY);
-      if (item < a.n_items && s_cl[u] < G && c < a.n_cand) rec[u] = a.recs[(size_t)c * I + s_j[u]];
-    }
-  };
   auto file_group = [&](const float4 (&rec)[kSlotsPerThread], uint32_t it) {
 #pragma unroll
     for (int u = 0; u < kSlotsPerThread; ++u)
@@ -310,12 +492,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a) {
         lists[it & 1u][s_cl[u] * I + (nowait ? pos : I - 1u - pos)] = rec[u];
       }
   };
-
-  {
-    float4 rec[kSlotsPerThread];
-    load_group(cur, rec);
-    file_group(rec, 0u);
-  }
+  file_group(rec0, 0u);
   __syncthreads();
 
   unsigned long long evaluated = 0ull, evaluated_nowait = 0ull;
@@ -323,7 +500,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a) {
   uint32_t prev_c0 = 0, prev_n = 0;
   for (uint32_t it = 0;; ++it) {
     uint32_t after_next = 0xffffffffu;
-    if (tid == 0u && nxt < a.n_items) after_next = xcd + 8u * atomicAdd(queue, 1u);
+    if (tid == 0u && nxt < a.n_items) after_next = xcd + 8u * (dynamic_base + atomicAdd(queue, 1u));
     float4 rec[kSlotsPerThread];
     load_group(nxt, rec);
 
@@ -353,51 +530,15 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a) {
         const float4* wlst = lst + (I - n1);  // the records with a wait sit at the segment's end
         uint32_t cnt = 0;
         if (n0 + n1 != 0u) {
-          float m[Q];  // smallest first-token latency so far; the first record initialises it
-          const float4* p0 = lst;   // next record without a wait
-          const float4* p1 = wlst;  // next record with one
-          uint32_t left0 = n0, left1 = n1;
-          if (n0 != 0u) {
-            const float4 r = *p0++;
-            --left0;
-#pragma unroll
-            for (int q = 0; q < Q; ++q) m[q] = fmaf(r.x, L[q], r.y);
-          } else {
-            const float4 r = *p1++;
-            --left1;
-#pragma unroll
-            for (int q = 0; q < Q; ++q) m[q] = r.z + fmaf(r.x, L[q], r.y);
-          }
+          float m[Q];  // smallest first-token latency so far
           // wait == +0: ttft = 0 + prefill = prefill exactly (the prefill time is positive), so the
-          // add is left out - two fma and one three-way minimum per two records
-          for (uint32_t t = left0 >> 1; t != 0u; --t, p0 += 2) {
-            const float4 r = p0[0];
-            const float4 u = p0[1];
-#pragma unroll
-            for (int q = 0; q < Q; ++q)
-              m[q] = min3_no_nan(m[q], fmaf(r.x, L[q], r.y), fmaf(u.x, L[q], u.y));
-          }
-          if (left0 & 1u) {
-            const float4 r = p0[0];
-#pragma unroll
-            for (int q = 0; q < Q; ++q) m[q] = min_no_nan(m[q], fmaf(r.x, L[q], r.y));
-          }
-          for (uint32_t t = left1 >> 1; t != 0u; --t, p1 += 2) {  // one three-way minimum serves two records
-            const float4 r = p1[0];
-            const float4 u = p1[1];
-#pragma unroll
-            for (int q = 0; q < Q; ++q)
-              m[q] = min3_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y), u.z + fmaf(u.x, L[q], u.y));
-          }
-          if (left1 & 1u) {
-            const float4 r = p1[0];
-#pragma unroll
-            for (int q = 0; q < Q; ++q) m[q] = min_no_nan(m[q], r.z + fmaf(r.x, L[q], r.y));
-          }
+          // add is left out for those records
+          if (n0 != 0u) walk_list<Q, false>(m, L, lst, n0, true);
+          if (n1 != 0u) walk_list<Q, true>(m, L, wlst, n1, n0 == 0u);
 #pragma unroll
           for (int q = 0; q < Q; ++q) cnt += (uint32_t)__popcll(__ballot(m[q] <= Dt));
         }
-        acc = (lane == g) ? cnt : acc;
+        write_lane(acc, cnt, g);
       }
       evaluated += (unsigned long long)n_sum * wave_reqs;
       evaluated_nowait += (unsigned long long)n0_sum * wave_reqs;
@@ -430,8 +571,10 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a) {
         wave_eval[tid][0] + wave_eval[tid][1] + wave_eval[tid][2] + wave_eval[tid][3];
 }
 
+// Wavefronts per SIMD the register allocation must leave room for: eight with up to 8 requests per
+// lane, five with 16 (measured: one wavefront fewer costs more than the registers buy).
 template <int Q>
-__global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const SweepArgs a) {
+__global__ __launch_bounds__(kSweepThreads, (Q <= 8 ? 8 : 5)) void sweep_kernel(const SweepArgs a) {
   sweep_body<Q>(a);
 }
 
