@@ -448,6 +448,16 @@ def measure(name: str, steps: int, warmup: int, args, min_gpu_warm_ms: float = 0
                                 "is windows x per-window latency")
             roofline["windows"] = n_win
             roofline["us_per_window"] = k_avg_s * 1e6 / n_win
+            # where a window's time goes: one more call with the kernel's profiling variant (block 0
+            # sums its cycles per phase); shares of its loop, scaled to the unprofiled time per window
+            binding.maaso_ctx_window_profile(dw.ctx, True)
+            dominant()
+            ph = binding.maaso_ctx_window_phases(dw.ctx)
+            binding.maaso_ctx_window_profile(dw.ctx, False)
+            if ph["loop"]:
+                roofline["phase_us_per_window"] = {
+                    k: ph[k] / ph["loop"] * roofline["us_per_window"]
+                    for k in ("stage", "score", "exchange", "update")}
         elif w.n_req < (1 << 20):
             roofline["note"] = "launch latency: a single short kernel"
     roofline["traffic_info"] = traffic_info

@@ -183,6 +183,17 @@ int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches
  * (Shows, for instance, whether the device's clock was still rising during a short series.) */
 int maaso_ctx_kernel_durations(maaso_ctx* ctx, float* durations_ms, uint32_t cap, uint32_t* launches);
 
+/* Where the windowed distributor's time goes.  With profiling enabled, a maaso_score_assign call that
+ * runs the persistent windowed kernel (window > 4, policy 0, no latency outputs) has block 0 sum the
+ * shader clock cycles it spends, per window, on: [0] evaluating the instances' profiles for the
+ * window's state, [1] scoring its share of the window's requests, [2] exchanging the admitted load
+ * with the other blocks (device-wide barrier included), [3] advancing the state; [4] is the whole
+ * window loop, [5] the number of windows.  maaso_ctx_window_phases synchronises the device and returns
+ * the six figures of the context's most recent such call (zeros if there was none).  Results of the
+ * call are unchanged; its kernel is a few per cent slower.  Errors: INVALID_ARG, HIP. */
+int maaso_ctx_window_profile(maaso_ctx* ctx, int enable);
+int maaso_ctx_window_phases(maaso_ctx* ctx, uint64_t cycles[6]);
+
 /* Synchronises the device and returns how many (request, instance) pairs the context's most recent
  * maaso_placement_sweep evaluated in its latency loop, i.e. the valid triples minus those whose
  * instance already fails the between-token deadline of the request's class (they are settled per

@@ -28,6 +28,7 @@ EXPORTS = (
     "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
     "maaso_score_assign_selected", "maaso_placement_score_sets", "maaso_placement_sweep_noalloc",
     "maaso_ctx_reserve", "maaso_ctx_workspace", "maaso_ctx_kernel_durations",
+    "maaso_ctx_window_profile", "maaso_ctx_window_phases",
 )
 
 
@@ -103,6 +104,8 @@ def load_library() -> C.CDLL:
                                                  C.POINTER(C.c_uint32)]
         lib.maaso_ctx_kernel_durations.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_uint32,
                                                    C.POINTER(C.c_uint32)]
+        lib.maaso_ctx_window_profile.argtypes = [C.c_void_p, C.c_int]
+        lib.maaso_ctx_window_phases.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         lib.maaso_ctx_sweep_evaluated.argtypes = [C.c_void_p, C.POINTER(C.c_uint64),
                                                   C.POINTER(C.c_uint64)]
         lib.maaso_score_assign.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
@@ -257,6 +260,19 @@ def maaso_ctx_kernel_durations(ctx: Context, cap: int = 256):
     _check(load_library().maaso_ctx_kernel_durations(ctx.handle, buf, cap, C.byref(n)),
            "maaso_ctx_kernel_durations")
     return [float(buf[i]) for i in range(n.value)]
+
+
+def maaso_ctx_window_profile(ctx: Context, enable: bool) -> None:
+    _check(load_library().maaso_ctx_window_profile(ctx.handle, int(bool(enable))), "maaso_ctx_window_profile")
+
+
+def maaso_ctx_window_phases(ctx: Context):
+    """Cycles block 0 of the last profiled windowed call spent on (stage, score, exchange, update),
+    the whole loop, and the number of windows."""
+    buf = (C.c_uint64 * 6)()
+    _check(load_library().maaso_ctx_window_phases(ctx.handle, buf), "maaso_ctx_window_phases")
+    v = [int(x) for x in buf]
+    return dict(stage=v[0], score=v[1], exchange=v[2], update=v[3], loop=v[4], windows=v[5])
 
 
 def maaso_ctx_sweep_evaluated(ctx: Context, split: bool = False):

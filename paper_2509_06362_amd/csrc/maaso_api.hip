@@ -59,6 +59,8 @@ struct maaso_ctx {
   bool counters_dirty;   // class counters may be non-zero (a call failed between its launches)
   uint32_t window_blocks;  // 0 = automatic
   uint32_t spin_limit;     // polls of the inter-window barrier before a block gives up
+  bool window_profile;     // the windowed distributor records where block 0 spends its cycles
+  bool window_profiled;    // ... and the last windowed call did
   int n_cu;
   int cooperative;      // the device launches cooperative grids (all blocks resident, or refused)
   int sweep_resident[4];  // blocks of sweep_kernel<2|4|8|16> one compute unit holds at once
@@ -1066,10 +1068,15 @@ int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t
   WindowWs* ws = static_cast<WindowWs*>(ctx->ws);
   const uint32_t per_window = prm->window < R ? prm->window : R;
   // More blocks shorten a window's scoring (more lanes per request, shorter instance walks) and
-  // lengthen the barrier between windows; measured on 64 instances and windows of 4096: 4.4 ms for
-  // 1024 windows with 16 blocks, 4.0 with 32, 3.9 with 64, 4.6 with 128.  Lanes per request are then
-  // chosen so that a window is scored in one pass.
-  uint32_t nb = ctx->window_blocks ? ctx->window_blocks : 64u;
+  // lengthen the window boundary, where every block adds to every instance's accumulators and the
+  // owners of the instances read them until all blocks are counted in.  Measured per window
+  // (16 / 32 / 64 / 128 blocks): 64 instances, windows of 4096: 3.63 / 3.15 / 3.81 / 5.77 us;
+  // 256 instances, 4096: 7.2 / 5.4 / 5.7 / 7.6; 64 instances, 32768: 13.0 / 8.0 / 6.2 / 6.9;
+  // 256 instances, 32768: 39.9 / 22.0 / 13.5 / 11.5.  Lanes per request are then chosen so that a
+  // window is scored in one pass.
+  const uint64_t window_triples = (uint64_t)per_window * pl->i_pad;
+  uint32_t nb = ctx->window_blocks ? ctx->window_blocks
+                                   : (window_triples < (1ull << 21) ? 32u : (window_triples < (1ull << 23) ? 64u : 128u));
   if (nb > (uint32_t)ctx->n_cu) nb = (uint32_t)ctx->n_cu;
   if (nb == 0) nb = 1;
   uint32_t lpr = 1;
@@ -1101,12 +1108,15 @@ int score_assign_impl(maaso_ctx* ctx, const maaso_placements* pl, const uint32_t
         launched = hipLaunchKernel(fn, dim3(nb), dim3(kWindowThreads), kargs, wlds, s);
     }
   };
+  ctx->window_profiled = ctx->window_profile && !prm->policy && !lat;
 #define MAASO_LAUNCH_WINDOW(LPR)                                                                  \
   do {                                                                                            \
     if (prm->policy) /* latency outputs are null-checked in the kernel: one variant serves both */ \
       launch(reinterpret_cast<const void*>(&assign_window_kernel<LPR, true, true>));               \
     else if (lat)                                                                                  \
       launch(reinterpret_cast<const void*>(&assign_window_kernel<LPR, true, false>));              \
+    else if (ctx->window_profiled)                                                                 \
+      launch(reinterpret_cast<const void*>(&assign_window_kernel<LPR, false, false, true>));       \
     else                                                                                           \
       launch(reinterpret_cast<const void*>(&assign_window_kernel<LPR, false, false>));             \
   } while (0)
@@ -1192,6 +1202,27 @@ int maaso_ctx_sweep_evaluated(maaso_ctx* ctx, uint64_t* pairs, uint64_t* pairs_w
   if (!hip_ok(hipMemcpy(v, ctx->last_evaluated, sizeof(v), hipMemcpyDeviceToHost))) return MAASO_E_HIP;
   *pairs = v[0];
   if (pairs_without_wait) *pairs_without_wait = v[1];
+  return MAASO_OK;
+}
+
+int maaso_ctx_window_profile(maaso_ctx* ctx, int enable) {
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  ctx->window_profile = enable != 0;
+  ctx->window_profiled = false;
+  return MAASO_OK;
+}
+
+int maaso_ctx_window_phases(maaso_ctx* ctx, uint64_t cycles[6]) {
+  if (!ctx || !cycles) return MAASO_E_INVALID_ARG;
+  for (int i = 0; i < 6; ++i) cycles[i] = 0;
+  if (!ctx->window_profiled) return MAASO_OK;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  if (!hip_ok(hipDeviceSynchronize())) return MAASO_E_HIP;
+  const WindowWs* ws = static_cast<const WindowWs*>(ctx->ws);
+  unsigned long long v[6];
+  if (!hip_ok(hipMemcpy(v, ws->phase, sizeof(v), hipMemcpyDeviceToHost))) return MAASO_E_HIP;
+  for (int i = 0; i < 6; ++i) cycles[i] = v[i];
   return MAASO_OK;
 }
 

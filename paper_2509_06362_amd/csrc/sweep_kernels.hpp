@@ -85,9 +85,13 @@ __device__ __forceinline__ float min3_no_nan(float x, float y, float z) {
 }
 
 // v[lane] = value for a uniform value and lane index (both scalar).  The instruction reads one scalar
-// register beside M0, so the lane index travels through M0.
+// register beside M0, so the lane index travels through M0, whose content is put back afterwards
+// (the compiler does not track M0 across an asm statement).
 __device__ __forceinline__ void write_lane(uint32_t& v, uint32_t value, uint32_t lane_index) {
-  asm("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(v) : "s"(value), "s"(lane_index) : "m0");
+  uint32_t keep;
+  asm("s_mov_b32 %1, m0\n\ts_mov_b32 m0, %3\n\tv_writelane_b32 %0, %2, m0\n\ts_mov_b32 m0, %1"
+      : "+v"(v), "=&s"(keep)
+      : "s"(value), "s"(lane_index));
 }
 
 __device__ __forceinline__ float max_no_nan(float x, float y) {

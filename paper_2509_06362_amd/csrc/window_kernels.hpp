@@ -9,9 +9,13 @@
 // a cross-lane arg-max with lowest-index tie-break (DPP row operations inside a 16-lane row,
 // ds_bpermute across rows).  Admitted load is summed with integer atomics - first in LDS per block,
 // then once per block and instance into a small ring of global accumulators - so the sums do not
-// depend on the order of arrival.  A device-wide barrier (monotone counter, bounded spin) separates
-// the windows; after it every block reads the same sums and advances its private copy of the state
-// with the same integer / binary32 operations, so all copies stay identical.
+// depend on the order of arrival.  The accumulators count their own contributions: every block adds
+// to every instance's words at every window (zero included), each addition carrying a one in the
+// word's top bits, so the thread that owns instance j knows the sums are complete when the count
+// equals the number of blocks.  That is the whole window boundary: one round of additions and one
+// round of reads across the device, no separate arrival counter (bounded spin).  After it every
+// block holds the same sums and advances its private copy of the state with the same integer /
+// binary32 operations, so all copies stay identical.
 #pragma once
 
 #include "assign_kernels.hpp"
@@ -24,12 +28,24 @@ constexpr int kRing = 4;
 constexpr int kWindowThreads = 1024;  // 16 wavefronts: four per SIMD hide the LDS latency of the instance loop
 
 // Global scratch of the windowed kernel (zeroed by window_init_kernel before each call).
+// Accumulator words: the low 40 bits hold a sum, the bits above how many blocks have added to it.
+constexpr int kSumBits = 40;
+constexpr unsigned long long kSumMask = (1ull << kSumBits) - 1ull;
+constexpr unsigned long long kOneArrival = 1ull << kSumBits;
+
 struct WindowWs {
-  unsigned long long bar;                        // arrivals at the inter-window barrier, monotone
   uint32_t abort_flag;                           // set when a wait gave up; every block then leaves
-  uint32_t pad;
-  uint32_t ring_n[kRing][256];                   // admitted requests per instance, window w -> w % kRing
-  unsigned long long ring_t[kRing][256];         // admitted prefill ticks per instance
+  uint32_t pad[3];
+  // per instance, window w -> slot w % kRing: admitted requests (at most a window's 2^31), and the
+  // admitted prefill ticks as the sums of the low and of the high 32-bit halves of the blocks'
+  // 64-bit partial sums (each below 2^32 * 256 blocks = 2^40)
+  unsigned long long ring_n[kRing][256];
+  unsigned long long ring_tl[kRing][256];
+  unsigned long long ring_th[kRing][256];
+  // where block 0 spent its time, in shader clock cycles summed over the windows (written only by
+  // the profiling variant of the kernel): stage, score, exchange, update; then the whole loop and
+  // the number of windows
+  unsigned long long phase[8];
 };
 
 __global__ void window_init_kernel(WindowWs* ws, unsigned long long* n_satisfied) {
@@ -64,40 +80,10 @@ __device__ __forceinline__ void argmax_lanes(float& s, int32_t& i) {
   if (LPR >= 64) take_better(s, i, __shfl_xor(s, 32), __shfl_xor(i, 32));
 }
 
-// Device-wide barrier on a monotone counter.  Returns false if the wait gave up or another block
-// did; the caller must then leave the kernel.  Must be reached by all threads of the block.
-// What crosses the barrier are device-scope atomics only (the per-window sums): every thread waits for
-// its own to complete (vmcnt) before the block gathers, the arrival is an atomic issued after that, and
-// the sums are read back with device-scope atomic loads - so no cache write-back or invalidate is
-// needed, and none is issued (a full fence here writes the L2 back at every window).
-__device__ __forceinline__ bool grid_barrier(WindowWs* ws, unsigned long long target,
-                                             uint32_t spin_limit, uint32_t* status, int* lds_flag) {
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this thread's atomics on the sums have completed
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    atomicAdd(&ws->bar, 1ull);
-    bool ok = true;
-    uint32_t spins = 0;
-    while (__hip_atomic_load(&ws->bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      if (__hip_atomic_load(&ws->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u ||
-          spins >= spin_limit) {
-        ok = false;
-        __hip_atomic_store(&ws->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        raise_status(status, 4u);
-        break;
-      }
-      ++spins;
-      __builtin_amdgcn_s_sleep(4);
-    }
-    *lds_flag = ok ? 1 : 0;
-  }
-  __syncthreads();
-  return *lds_flag != 0;
-}
-
 // kSQ: shortest-queue rule (see queue_rank_value); the rank values are rebuilt at every window from
 // the queue lengths the window starts with.
-template <int LPR, bool kLat, bool kSQ>
+// kProf: block 0 also sums the shader clock cycles it spends in each phase of a window into ws->phase.
+template <int LPR, bool kLat, bool kSQ, bool kProf = false>
 __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const AssignArgs a,
                                                                        uint32_t window,
                                                                        WindowWs* ws,
@@ -109,7 +95,6 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
   __shared__ uint32_t n_blk[256];
   __shared__ unsigned long long t_blk[256];
   __shared__ uint32_t wave_sat[kWindowThreads / 64];
-  __shared__ int bar_ok;
   __shared__ int32_t occ_s[kSQ ? 256 : 1];
   __shared__ float rankv[kSQ ? 256 : 1];
 
@@ -133,23 +118,47 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
   uint32_t sat = 0;
   bool alive = true;
 
-  // The request a lane scores first in a window is fetched one window ahead, so that its load
-  // latency overlaps the inter-window barrier instead of following it.
-  uint32_t pf_pl = 0, pf_ol = 0, pf_k = 0;
+  // The request a lane scores first in a window is fetched one window ahead, and everything that
+  // depends on the request alone - its class row, the end-to-end deadline and its reciprocal (a
+  // division) - is worked out while the block waits for the other blocks at the window boundary, so
+  // that neither the load nor that arithmetic follows the barrier.
+  // The same goes for the arrival time that passes until the window after it opens (thread j needs
+  // it when it advances instance j): fetched a window ahead, it is not waited for at a window's start.
+  uint32_t pf_pl = 0, pf_ol = 0, pf_k = 0, pf_t0 = 0, pf_t1 = 0;
   auto prefetch = [&](uint64_t wn) {
     if (wn >= n_windows) return;
     const uint64_t s = wn * window;
     const uint64_t e = (s + window < R) ? s + window : R;
     const uint64_t r = s + (uint64_t)blockIdx.x * kReqPerBlock + rq_in_blk;
     if (r < e) { pf_pl = a.prompt_len[r]; pf_ol = a.out_len[r]; pf_k = a.slo_class[r]; }
+    pf_t0 = 0u;
+    pf_t1 = 0u;
+    if (tid < n && e < R) { pf_t0 = a.arrival_ticks[s]; pf_t1 = a.arrival_ticks[e]; }
+  };
+  float pre_L = 0.0f, pre_S = 0.0f;
+  Deadlines pre_d{};
+  bool pre_ok = false;
+  auto request_side = [&](uint32_t pl, uint32_t ol, uint32_t k, float& L, float& S, Deadlines& d) {
+    L = (float)pl;
+    S = (float)ol;
+    if (k >= a.n_slo) return false;
+    const ClassRow c = cls[k];
+    d.Dt = c.Dt; d.Db = c.Db; d.iDt = c.iDt; d.iDb = c.iDb;
+    d.De = fmaf(S, c.Db, c.Dt);
+    d.iDe = 1.0f / d.De;
+    return true;
   };
   prefetch(0);
+  pre_ok = request_side(pf_pl, pf_ol, pf_k, pre_L, pre_S, pre_d);
+
+  unsigned long long t_phase[4] = {0ull, 0ull, 0ull, 0ull};
+  const long long t_loop = kProf ? clock64() : 0ll;
 
   for (uint64_t w = 0; w < n_windows; ++w) {
+    const long long t0 = kProf ? clock64() : 0ll;
     const uint64_t s0 = w * window;
     const uint64_t e0 = (s0 + window < R) ? s0 + window : R;
-    uint32_t delta = 0;  // arrival time that passes until the next window opens
-    if (tid < n && e0 < R) delta = a.arrival_ticks[e0] - a.arrival_ticks[s0];
+    const uint32_t delta = pf_t1 - pf_t0;  // arrival time that passes until the next window opens
     float svc = 1.0f;
     if (tid < n) {
       Staged st;
@@ -164,17 +173,12 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
       t_blk[tid] = 0ull;
       if (kSQ) occ_s[tid] = occ;
     }
-    if (blockIdx.x == 0 && tid < 256u) {  // recycle the accumulators that window w+2 will use
-      __hip_atomic_store(&ws->ring_n[(w + 2) % kRing][tid], 0u, __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(&ws->ring_t[(w + 2) % kRing][tid], 0ull, __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-    }
     __syncthreads();
     if (kSQ) {
       if (tid < n) rankv[tid] = queue_rank_value(occ_s, n, tid);
       __syncthreads();
     }
+    const long long t1 = kProf ? clock64() : 0ll;
     // what a triple competes with: its slack, or under the shortest-queue rule its instance's rank
     // value once the slack is non-negative
     auto value = [&](float slack, uint32_t j) { return (kSQ && slack >= 0.0f) ? rankv[j] : slack; };
@@ -190,15 +194,12 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
       Deadlines d{};
       bool class_ok = false;
       if (live) {
-        L = (float)(first ? pf_pl : a.prompt_len[r]);
-        S = (float)(first ? pf_ol : a.out_len[r]);
-        const uint32_t k = first ? pf_k : (uint32_t)a.slo_class[r];
-        class_ok = k < a.n_slo;
+        if (first) {
+          L = pre_L; S = pre_S; d = pre_d; class_ok = pre_ok;
+        } else {
+          class_ok = request_side(a.prompt_len[r], a.out_len[r], a.slo_class[r], L, S, d);
+        }
         if (class_ok) {
-          const ClassRow c = cls[k];
-          d.Dt = c.Dt; d.Db = c.Db; d.iDt = c.iDt; d.iDb = c.iDb;
-          d.De = fmaf(S, c.Db, c.Dt);
-          d.iDe = 1.0f / d.De;
           uint32_t j = sl;
           for (; j + 3u * LPR < n; j += 4u * LPR) {  // four records per trip: one LDS wait for four reads
             const float4 r0 = recs[j], r1 = recs[j + LPR], r2 = recs[j + 2u * LPR], r3 = recs[j + 3u * LPR];
@@ -246,20 +247,65 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
     }
     prefetch(w + 1);
     lds_atomics_barrier();
-    if (tid < n && n_blk[tid] != 0u) {
-      atomicAdd(&ws->ring_n[w % kRing][tid], n_blk[tid]);
-      atomicAdd(&ws->ring_t[w % kRing][tid], t_blk[tid]);
+    const long long t2 = kProf ? clock64() : 0ll;
+    // Window boundary.  Thread j adds the block's sums for instance j, each with a one in the count
+    // field, then reads the three words until all blocks are counted in.  Block 0 also recycles the
+    // slot that window w + 2 will use: every block has read it (they all contributed to window w - 1
+    // after doing so), and the stores complete before block 0's wait below ends (the wait's loads are
+    // issued after them and the wait is for the thread's memory operations in full), hence before
+    // block 0 contributes to window w + 1, without which nobody reaches window w + 2.
+    unsigned long long sum_n = 0ull, sum_t = 0ull;
+    bool gave_up = false;
+    if (tid < n) {
+      const uint32_t slot = (uint32_t)(w % kRing);
+      const unsigned long long tb = t_blk[tid];
+      atomicAdd(&ws->ring_n[slot][tid], kOneArrival | (unsigned long long)n_blk[tid]);
+      atomicAdd(&ws->ring_tl[slot][tid], kOneArrival | (tb & 0xffffffffull));
+      atomicAdd(&ws->ring_th[slot][tid], kOneArrival | (tb >> 32));
+      if (blockIdx.x == 0) {
+        const uint32_t recycle = (uint32_t)((w + 2) % kRing);
+        __hip_atomic_store(&ws->ring_n[recycle][tid], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ws->ring_tl[recycle][tid], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ws->ring_th[recycle][tid], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
-
-    if (!grid_barrier(ws, (w + 1) * (unsigned long long)gridDim.x, spin_limit, a.status, &bar_ok)) {
+    // the next window's request has been requested: what depends on it alone is done while the sums
+    // of this window travel
+    pre_ok = request_side(pf_pl, pf_ol, pf_k, pre_L, pre_S, pre_d);
+    if (tid < n) {
+      const uint32_t slot = (uint32_t)(w % kRing);
+      const unsigned long long all_in = (unsigned long long)gridDim.x;
+      uint32_t spins = 0;
+      for (;;) {
+        const unsigned long long v0 = __hip_atomic_load(&ws->ring_n[slot][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long v1 = __hip_atomic_load(&ws->ring_tl[slot][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long v2 = __hip_atomic_load(&ws->ring_th[slot][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the three words, and everything this thread issued before
+        if ((v0 >> kSumBits) == all_in && (v1 >> kSumBits) == all_in && (v2 >> kSumBits) == all_in) {
+          sum_n = v0 & kSumMask;
+          sum_t = (v1 & kSumMask) + ((v2 & kSumMask) << 32);
+          break;
+        }
+        if (spins >= spin_limit ||
+            __hip_atomic_load(&ws->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+          gave_up = true;
+          __hip_atomic_store(&ws->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          raise_status(a.status, 4u);
+          break;
+        }
+        ++spins;
+        __builtin_amdgcn_s_sleep(2);
+      }
+    }
+    if (__syncthreads_or(gave_up ? 1 : 0)) {  // a wait gave up here or elsewhere: every block leaves
       alive = false;
       break;
     }
+    const long long t3 = kProf ? clock64() : 0ll;
 
     if (tid < n) {
-      occ += (int32_t)__hip_atomic_load(&ws->ring_n[w % kRing][tid], __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_AGENT);
-      q += __hip_atomic_load(&ws->ring_t[w % kRing][tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      occ += (int32_t)(uint32_t)sum_n;
+      q += sum_t;
       if (e0 < R) {  // time passes until the next window opens
         q -= (q < (uint64_t)delta) ? q : (uint64_t)delta;
         const int32_t run = min(occ, (int32_t)B);
@@ -268,6 +314,18 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
         occ -= done;
       }
     }
+    if (kProf) {
+      const long long t4 = clock64();
+      t_phase[0] += (unsigned long long)(t1 - t0);
+      t_phase[1] += (unsigned long long)(t2 - t1);
+      t_phase[2] += (unsigned long long)(t3 - t2);
+      t_phase[3] += (unsigned long long)(t4 - t3);
+    }
+  }
+  if (kProf && blockIdx.x == 0 && tid == 0) {
+    for (int i = 0; i < 4; ++i) ws->phase[i] = t_phase[i];
+    ws->phase[4] = (unsigned long long)(clock64() - t_loop);
+    ws->phase[5] = n_windows;
   }
 
   if (alive && blockIdx.x == 0 && tid < n) { row.occ[tid] = occ; row.q_ticks[tid] = q; }
