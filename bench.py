@@ -89,8 +89,9 @@ KERNEL_SOURCES = {
 }
 TRAFFIC = {
     # workload name: (kernel, bytes per launch, digest of the kernel's sources at measurement, summary)
-    "cfg1_placer_sweep": ("sweep_kernel", 5.695e6, "90eec800b4caf031", "profiles/sweep_kernel_cfg1.md"),
-    "streaming_i4": ("assign_static_kernel", 1.1410e9, "c0e11e1f486a50b7",
+    "cfg4_skewed_stress": ("sweep_kernel", 3.0879e7, "4a4d88dd875e78ec", "profiles/sweep_kernel_cfg4.md"),
+    "cfg1_placer_sweep": ("sweep_kernel", 5.641e6, "4a4d88dd875e78ec", "profiles/sweep_kernel_cfg1.md"),
+    "streaming_i4": ("assign_static_kernel", 1.1410e9, "db880294941b8bee",
                      "profiles/assign_static_kernel_stream.md"),
 }
 
@@ -284,6 +285,8 @@ def measure(name: str, steps: int, warmup: int, args, min_gpu_warm_ms: float = 0
     dw = binding.DeviceWorkload(w)
     binding.maaso_ctx_set_launch_shape(dw.ctx, args.sweep_q, args.sweep_group, args.sweep_bq,
                                        args.window_blocks)
+    if args.plain_launch:
+        binding.maaso_ctx_set_cooperative(dw.ctx, False)
     dev = dw.prompt_len.device
     stream = torch.cuda.current_stream()
 
@@ -522,6 +525,28 @@ def oracle_leg(entry, ctx, args):
     entry["oracle_agrees"] = bool(check["agrees"]) and entry["device_status"] == 0
 
 
+PROBE_PATTERNS = (
+    (0, "pair body without queue wait: fma, fma, min3 per request"),
+    (1, "pair body with queue wait: fma, fma, add, add, min3 per request"),
+    (2, "pair body without queue wait, four pairs per loop trip"),
+    (3, "compare writing a lane mask + carry add"),
+    (4, "fma with a scalar-register operand"),
+)
+
+
+def valu_probe():
+    """What the chip sustains for the sweep's instruction mix (maaso_probe_valu): vector lane operations
+    per second of loops that are nothing but the sweep's inner instruction sequence."""
+    from paper_2509_06362_amd import binding
+    out = {"peak_Tlaneops": VALU_PEAK_TLANEOPS, "patterns": []}
+    for pat, text in PROBE_PATTERNS:
+        rate, n = binding.maaso_probe_valu(pat, 65536)
+        out["patterns"].append({"pattern": pat, "what": text, "instructions_per_trip": n,
+                                "Tlaneops": rate / 1e12, "frac_of_peak": rate / 1e12 / VALU_PEAK_TLANEOPS})
+    out["sustained_frac_of_peak"] = max(p["frac_of_peak"] for p in out["patterns"][:3])
+    return out
+
+
 ALG2_GPUS = 64
 ALG2_SCORE_WEIGHTS = (4.0, 0.3, 4096.0, 2.0)
 
@@ -644,7 +669,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="report",
                     choices=["report", "cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg4w", "cfg4w1",
-                             "cfg4score", "alg2", "stream"],
+                             "cfg4score", "alg2", "stream", "probe"],
                     help="report (default): config 4 as the headline and the other workloads in per_config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-triples", type=float, default=3.0e9,
@@ -653,6 +678,9 @@ def main() -> int:
     ap.add_argument("--sweep-group", type=int, default=0)
     ap.add_argument("--sweep-bq", type=int, default=0)
     ap.add_argument("--window-blocks", type=int, default=0)
+    ap.add_argument("--plain-launch", action="store_true",
+                    help="launch the windowed distributor's kernel as an ordinary grid, not cooperatively "
+                         "(rocprofv3 crashes at exit after a cooperative launch)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB copy kernel five times (reference for HBM counters)")
     args = ap.parse_args()
@@ -670,6 +698,9 @@ def main() -> int:
     binding.load_library()
     if args.workload == "alg2":
         return bench_alg2(args)
+    if args.workload == "probe":
+        print(json.dumps(valu_probe()))
+        return 0
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
@@ -710,6 +741,7 @@ def main() -> int:
         "streaming_frac_of_hbm_peak": stream["roofline"]["frac"],
         "headline_frac_of_hbm_peak": head["roofline"]["hbm"]["frac_of_peak"],
     }
+    result["valu_probe"] = valu_probe()
     result["paper_context"] = PAPER_CONTEXT
     result["seconds"] = {"gpu_part": t_gpu, "total": time.perf_counter() - t_start}
     print(json.dumps(result))

@@ -170,6 +170,14 @@ int maaso_ctx_set_launch_shape(maaso_ctx* ctx, uint32_t sweep_requests_per_lane,
  * Errors: INVALID_ARG. */
 int maaso_ctx_set_wait_limit(maaso_ctx* ctx, uint32_t polls);
 
+/* How the windowed distributor's persistent kernel is launched.  enable != 0 (the default where the
+ * device supports it): cooperatively - the runtime guarantees that all blocks are resident together
+ * or refuses the launch.  0: as an ordinary grid, after the host has checked with the occupancy query
+ * that the device can hold all blocks at once; other work on the device can then still keep blocks
+ * from starting, which the bounded wait turns into MAASO_E_TIMEOUT.  For tools that cannot follow
+ * cooperative launches (rocprofv3 crashed at process exit after one).  Errors: INVALID_ARG, HIP. */
+int maaso_ctx_set_cooperative(maaso_ctx* ctx, int enable);
+
 /* Instrumentation.  With timing enabled, each compute call records a pair of HIP events on its
  * stream directly around its dominant kernel (the sweep kernel of maaso_placement_sweep and of
  * maaso_placement_score, the scoring kernel of maaso_score_assign), for up to 256 calls.  maaso_ctx_kernel_elapsed waits for the
@@ -182,6 +190,21 @@ int maaso_ctx_kernel_elapsed(maaso_ctx* ctx, float* total_ms, uint32_t* launches
  * first min(cap, recorded) durations in milliseconds, *launches their number; starts a new series.
  * (Shows, for instance, whether the device's clock was still rising during a short series.) */
 int maaso_ctx_kernel_durations(maaso_ctx* ctx, float* durations_ms, uint32_t cap, uint32_t* launches);
+
+/* What the chip sustains for the sweep's instruction mix.  Runs, on `device`, a kernel that is nothing
+ * but the sweep's inner instruction sequence in a loop (8 wavefronts per SIMD, no memory access) and
+ * returns the vector lane operations per second it reaches - the practical ceiling for the sweep on
+ * this device, next to the nominal peak that roofline fractions are quoted against.
+ *   pattern 0: two fma + one three-input minimum per request (a pair of records without queue wait),
+ *   1: the same with the wait's two adds, 2: pattern 0 unrolled four times, 3: compares that write a
+ *   lane mask, 4: fma with a scalar-register operand.
+ * trips: loop trips; the kernel runs three times and the last run is reported, and only runs of some
+ * tens of milliseconds (65,536 trips) see the device at its sustained clock.  *instructions_per_trip
+ * (may be NULL) receives the vector instructions of one trip.  A set-up style call: it allocates,
+ * synchronises and frees.
+ * Errors: INVALID_ARG, HIP, NOMEM. */
+int maaso_probe_valu(int device, uint32_t pattern, uint32_t trips, double* lane_ops_per_s,
+                     uint32_t* instructions_per_trip);
 
 /* Where the windowed distributor's time goes.  With profiling enabled, a maaso_score_assign call that
  * runs the persistent windowed kernel (window > 4, policy 0, no latency outputs) has block 0 sum the

@@ -28,7 +28,8 @@ EXPORTS = (
     "maaso_ins_deploy_select", "maaso_resource_partition", "maaso_profile_fit",
     "maaso_score_assign_selected", "maaso_placement_score_sets", "maaso_placement_sweep_noalloc",
     "maaso_ctx_reserve", "maaso_ctx_workspace", "maaso_ctx_kernel_durations",
-    "maaso_ctx_window_profile", "maaso_ctx_window_phases",
+    "maaso_ctx_window_profile", "maaso_ctx_window_phases", "maaso_probe_valu",
+    "maaso_ctx_set_cooperative",
 )
 
 
@@ -97,6 +98,7 @@ def load_library() -> C.CDLL:
         lib.maaso_ctx_set_launch_shape.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
                                                    C.c_uint32]
         lib.maaso_ctx_set_wait_limit.argtypes = [C.c_void_p, C.c_uint32]
+        lib.maaso_ctx_set_cooperative.argtypes = [C.c_void_p, C.c_int]
         lib.maaso_ctx_reserve.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32]
         lib.maaso_ctx_workspace.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
         lib.maaso_ctx_kernel_timing.argtypes = [C.c_void_p, C.c_int]
@@ -106,6 +108,8 @@ def load_library() -> C.CDLL:
                                                    C.POINTER(C.c_uint32)]
         lib.maaso_ctx_window_profile.argtypes = [C.c_void_p, C.c_int]
         lib.maaso_ctx_window_phases.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
+        lib.maaso_probe_valu.argtypes = [C.c_int, C.c_uint32, C.c_uint32, C.POINTER(C.c_double),
+                                         C.POINTER(C.c_uint32)]
         lib.maaso_ctx_sweep_evaluated.argtypes = [C.c_void_p, C.POINTER(C.c_uint64),
                                                   C.POINTER(C.c_uint64)]
         lib.maaso_score_assign.argtypes = [C.c_void_p, C.POINTER(Placements), C.POINTER(Requests),
@@ -224,6 +228,10 @@ def maaso_ctx_set_launch_shape(ctx: Context, sweep_requests_per_lane=0, sweep_gr
            "maaso_ctx_set_launch_shape")
 
 
+def maaso_ctx_set_cooperative(ctx: Context, enable: bool) -> None:
+    _check(load_library().maaso_ctx_set_cooperative(ctx.handle, int(bool(enable))), "maaso_ctx_set_cooperative")
+
+
 def maaso_ctx_set_wait_limit(ctx: Context, polls: int) -> None:
     _check(load_library().maaso_ctx_set_wait_limit(ctx.handle, polls), "maaso_ctx_set_wait_limit")
 
@@ -273,6 +281,14 @@ def maaso_ctx_window_phases(ctx: Context):
     _check(load_library().maaso_ctx_window_phases(ctx.handle, buf), "maaso_ctx_window_phases")
     v = [int(x) for x in buf]
     return dict(stage=v[0], score=v[1], exchange=v[2], update=v[3], loop=v[4], windows=v[5])
+
+
+def maaso_probe_valu(pattern: int, trips: int = 65536, device: int = 0):
+    """(vector lane operations per second, vector instructions per loop trip) of a probe pattern."""
+    rate, n = C.c_double(0.0), C.c_uint32(0)
+    _check(load_library().maaso_probe_valu(int(device), int(pattern), int(trips), C.byref(rate), C.byref(n)),
+           "maaso_probe_valu")
+    return float(rate.value), int(n.value)
 
 
 def maaso_ctx_sweep_evaluated(ctx: Context, split: bool = False):

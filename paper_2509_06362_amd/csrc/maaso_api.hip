@@ -15,6 +15,7 @@
 #include "assign_kernels.hpp"
 #include "sweep_kernels.hpp"
 #include "partition_kernels.hpp"
+#include "probe_kernels.hpp"
 #include "profile_fit_kernels.hpp"
 #include "sweep_window_kernels.hpp"
 #include "sweep_seq_kernels.hpp"
@@ -866,6 +867,47 @@ int maaso_profile_fit(int device, uint32_t n_tp, const uint32_t* offsets, const 
   return rc;
 }
 
+int maaso_probe_valu(int device, uint32_t pattern, uint32_t trips, double* lane_ops_per_s,
+                     uint32_t* instructions_per_trip) {
+  static const uint32_t per_trip[5] = {24u, 40u, 96u, 16u, 8u};
+  if (pattern > 4u || trips == 0u || !lane_ops_per_s) return MAASO_E_INVALID_ARG;
+  int n_dev = 0;
+  if (!hip_ok(hipGetDeviceCount(&n_dev)) || device < 0 || device >= n_dev) return MAASO_E_HIP;
+  DeviceGuard guard(device);
+  if (!guard.ok) return MAASO_E_HIP;
+  hipDeviceProp_t prop;
+  if (!hip_ok(hipGetDeviceProperties(&prop, device))) return MAASO_E_HIP;
+  const uint32_t blocks = 8u * (uint32_t)(prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256);
+  float* out = nullptr;
+  if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&out), (size_t)blocks * kProbeThreads * sizeof(float))))
+    return MAASO_E_NOMEM;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = MAASO_OK;
+  if (!hip_ok(hipEventCreate(&e0)) || !hip_ok(hipEventCreate(&e1))) rc = MAASO_E_HIP;
+  float ms = 0.0f;
+  for (int pass = 0; pass < 3 && rc == MAASO_OK; ++pass) {  // the first passes let the clock rise; the last is reported
+    if (!hip_ok(hipEventRecord(e0, nullptr))) { rc = MAASO_E_HIP; break; }
+    const dim3 g(blocks), b(kProbeThreads);
+    switch (pattern) {
+      case 0: hipLaunchKernelGGL(valu_probe_kernel<0>, g, b, 0, nullptr, out, trips, 1.0f); break;
+      case 1: hipLaunchKernelGGL(valu_probe_kernel<1>, g, b, 0, nullptr, out, trips, 1.0f); break;
+      case 2: hipLaunchKernelGGL(valu_probe_kernel<2>, g, b, 0, nullptr, out, trips, 1.0f); break;
+      case 3: hipLaunchKernelGGL(valu_probe_kernel<3>, g, b, 0, nullptr, out, trips, 1.0f); break;
+      default: hipLaunchKernelGGL(valu_probe_kernel<4>, g, b, 0, nullptr, out, trips, 1.0f); break;
+    }
+    if (!hip_ok(hipGetLastError()) || !hip_ok(hipEventRecord(e1, nullptr)) ||
+        !hip_ok(hipEventSynchronize(e1)) || !hip_ok(hipEventElapsedTime(&ms, e0, e1)))
+      rc = MAASO_E_HIP;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(out);
+  if (rc != MAASO_OK) return rc;
+  if (instructions_per_trip) *instructions_per_trip = per_trip[pattern];
+  *lane_ops_per_s = (double)blocks * kProbeThreads * (double)trips * per_trip[pattern] / ((double)ms * 1e-3);
+  return MAASO_OK;
+}
+
 int maaso_split_by_slo(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_classes,
                        uint32_t* prompt_len_out, uint32_t* out_len_out, uint8_t* slo_class_out,
                        uint32_t* arrival_ticks_out, uint32_t* n_tight, void* hip_stream) {
@@ -1223,6 +1265,16 @@ int maaso_ctx_window_phases(maaso_ctx* ctx, uint64_t cycles[6]) {
   unsigned long long v[6];
   if (!hip_ok(hipMemcpy(v, ws->phase, sizeof(v), hipMemcpyDeviceToHost))) return MAASO_E_HIP;
   for (int i = 0; i < 6; ++i) cycles[i] = v[i];
+  return MAASO_OK;
+}
+
+int maaso_ctx_set_cooperative(maaso_ctx* ctx, int enable) {
+  if (!ctx) return MAASO_E_INVALID_ARG;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  int can = 0;
+  if (enable && !hip_ok(hipDeviceGetAttribute(&can, hipDeviceAttributeCooperativeLaunch, ctx->device))) can = 0;
+  ctx->cooperative = enable ? can : 0;
   return MAASO_OK;
 }
 

@@ -1373,3 +1373,20 @@ def test_a_second_thread_is_turned_away_not_mixed_in():
         print(f"  {len(results)} calls ran, {busy[0]} were refused as busy", flush=True)
     finally:
         dw.close()
+
+
+def test_valu_probe_reports_a_plausible_rate():
+    """The instrumentation kernel that measures what the chip sustains for the sweep's instruction mix:
+    a rate between a tenth of and the whole nominal peak (256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz),
+    the scalar-operand and compare patterns clearly below the all-register ones; bad arguments refused."""
+    rates = [binding.maaso_probe_valu(p, 2048) for p in range(5)]
+    peak = 256 * 4 * 32 * 2.4e9
+    for (rate, n), expect in zip(rates, (24, 40, 96, 16, 8)):
+        assert n == expect and 0.1 * peak < rate < 1.05 * peak
+    assert rates[4][0] < 0.85 * rates[2][0] and rates[3][0] < 0.85 * rates[2][0]
+    with pytest.raises(binding.MaasoError) as e:
+        binding.maaso_probe_valu(5, 16)
+    assert e.value.status == -1
+    with pytest.raises(binding.MaasoError) as e:
+        binding.maaso_probe_valu(0, 0)
+    assert e.value.status == -1
