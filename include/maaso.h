@@ -15,8 +15,8 @@
  *     copies of the tables, a workspace, a status word).
  *   - Compute calls (maaso_score_assign, maaso_score_assign_selected, maaso_placement_sweep,
  *     maaso_placement_sweep_noalloc, maaso_placement_score, maaso_placement_score_sets,
- *     maaso_split_by_slo, maaso_ins_deploy_select, maaso_resource_partition) are asynchronous on the
- *     given HIP stream (NULL = the default stream).  They allocate nothing, free nothing and do no
+ *     maaso_split_by_slo, maaso_ins_deploy_select, maaso_resource_partition,
+ *     maaso_resource_partition_requests) are asynchronous on the given HIP stream (NULL = the default stream).  They allocate nothing, free nothing and do no
  *     host synchronisation: the context's workspace is sized at maaso_profile_tables_load
  *     (MAASO_DEFAULT_WORKSPACE_BYTES, enough for 65,536 candidates of 32 instance slots) and
  *     changed only by maaso_ctx_reserve; a call whose shape needs more is refused with
@@ -439,6 +439,46 @@ int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t
                              const int32_t* cand_t_star, const int32_t* cand_l_star,
                              const int32_t* cand_h_star, uint64_t n_req_l, uint64_t n_req,
                              uint32_t* partition, float* phi_opt, void* hip_stream);
+
+/* Arrays that maaso_resource_partition_requests works in and reports through: all DEVICE,
+ * caller-owned, distinct from each other and from the inputs.  R = rq->n_req, C = pl->n_cand. */
+typedef struct {
+  uint32_t* prompt_len_split;    /* [R] the request streams after the split: R_t first, then R_l */
+  uint32_t* out_len_split;       /* [R]                                                           */
+  uint8_t* slo_class_split;      /* [R]                                                           */
+  uint32_t* arrival_ticks_split; /* [R]; required when rq->arrival_ticks is given                 */
+  uint32_t* n_tight;             /* [1] |R_t|                                                     */
+  uint32_t* sat_t;               /* [C] admitted requests of R_t per deployment                   */
+  uint32_t* sat_l;               /* [C] ... of R_l                                                */
+  uint32_t* sat_h;               /* [C] ... of all of R; required with score_h                    */
+  float* score_t;                /* [C] Phi(I', R_t)                                              */
+  float* score_l;                /* [C] Phi(I', R_l)                                              */
+  float* score_h;                /* [C] Phi(I', R), or NULL: no homogeneous fallback              */
+  float* phi_t_star;             /* [n_gpus+1] Alg. 1's lists, as maaso_ins_deploy_select writes  */
+  float* phi_l_star;             /* [n_gpus+1]                                                    */
+  float* phi_h_star;             /* [n_gpus+1]; required with score_h                             */
+  int32_t* cand_t_star;          /* [n_gpus+1]                                                    */
+  int32_t* cand_l_star;          /* [n_gpus+1]                                                    */
+  int32_t* cand_h_star;          /* [n_gpus+1]; required with score_h                             */
+  uint32_t* partition;           /* [6] as maaso_resource_partition writes it                     */
+  float* phi_opt;                /* [1]                                                           */
+} maaso_partition_work;
+
+/* Alg. 2 from requests to partition in one call (Sec. IV-E): maaso_split_by_slo of rq by
+ * tight_classes; the composite score of every deployment in pl against R_t, against R_l and - when
+ * wk->score_h is given - against all of R, in one launch as maaso_placement_score_sets makes it;
+ * maaso_ins_deploy_select over the growth chains (chain_offsets, n_chains: as there) for each of the
+ * score lists; the scan of maaso_resource_partition with G'_l = floor(|R_l| * |G| / |R|).  |R_t| never
+ * leaves the device: the scoring kernels and the scan read it from wk->n_tight, so the call enqueues
+ * its launches and returns without waiting for any of them, and every result is what the five
+ * calls in sequence would have written.  Nothing is allocated; the placements are not written.
+ * Errors: INVALID_ARG, SHAPE, WORKSPACE, BUSY, HIP. */
+int maaso_resource_partition_requests(maaso_ctx* ctx, const maaso_placements* pl,
+                                      const uint32_t* chain_offsets, uint32_t n_chains,
+                                      uint32_t n_gpus, const maaso_requests* rq,
+                                      uint32_t tight_classes, const maaso_params* prm,
+                                      const maaso_score_weights* wts,
+                                      const maaso_partition_work* wk, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -29,7 +29,7 @@ EXPORTS = (
     "maaso_score_assign_selected", "maaso_placement_score_sets", "maaso_placement_sweep_noalloc",
     "maaso_ctx_reserve", "maaso_ctx_workspace", "maaso_ctx_kernel_durations",
     "maaso_ctx_window_profile", "maaso_ctx_window_phases", "maaso_probe_valu",
-    "maaso_ctx_set_cooperative",
+    "maaso_ctx_set_cooperative", "maaso_resource_partition_requests",
 )
 
 
@@ -74,6 +74,21 @@ class ScoreWeights(C.Structure):
 class ScoreOut(C.Structure):
     _fields_ = [("sat_count", C.c_void_p), ("phi_s", C.c_void_p), ("phi_t", C.c_void_p),
                 ("phi_l", C.c_void_p), ("score", C.c_void_p), ("best_cand", C.c_void_p)]
+
+
+# field name -> element type name of maaso_partition_work, in declaration order
+PARTITION_WORK_FIELDS = (
+    ("prompt_len_split", "int32"), ("out_len_split", "int32"), ("slo_class_split", "uint8"),
+    ("arrival_ticks_split", "int32"), ("n_tight", "int32"), ("sat_t", "int32"), ("sat_l", "int32"),
+    ("sat_h", "int32"), ("score_t", "float32"), ("score_l", "float32"), ("score_h", "float32"),
+    ("phi_t_star", "float32"), ("phi_l_star", "float32"), ("phi_h_star", "float32"),
+    ("cand_t_star", "int32"), ("cand_l_star", "int32"), ("cand_h_star", "int32"),
+    ("partition", "int32"), ("phi_opt", "float32"),
+)
+
+
+class PartitionWork(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name, _ in PARTITION_WORK_FIELDS]
 
 
 _lib = None
@@ -136,6 +151,12 @@ def load_library() -> C.CDLL:
                                                 C.c_void_p, C.c_void_p]
         lib.maaso_resource_partition.argtypes = [C.c_void_p, C.c_uint32] + [C.c_void_p] * 6 + [
             C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.maaso_resource_partition_requests.argtypes = [
+            C.c_void_p, C.POINTER(Placements), C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(Requests),
+            C.c_uint32, C.POINTER(Params), C.POINTER(ScoreWeights), C.POINTER(PartitionWork), C.c_void_p]
+        missing = [n for n in EXPORTS if n != "maaso_strerror" and getattr(lib, n).argtypes is None]
+        if missing:  # an undeclared signature would pass pointers as C ints
+            raise RuntimeError(f"binding.py declares no argument types for {missing}")
         _lib = lib
     return _lib
 
@@ -475,6 +496,25 @@ def maaso_resource_partition(ctx: Context, *, n_gpus, phi_t_star, phi_l_star, ph
         "maaso_resource_partition")
 
 
+def maaso_resource_partition_requests(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ,
+                                      q_ticks, chain_offsets=None, n_gpus, n_req, prompt_len, out_len,
+                                      slo_class, arrival_ticks=None, tight_classes, s_bar,
+                                      pen_kappa=0.0, tbt_mode=0, window=0, policy=0, alpha, beta,
+                                      gamma_t, gamma_l, work, stream=None) -> None:
+    """`work`: dict of tensors keyed by the fields of maaso_partition_work (absent or None = NULL)."""
+    import torch
+    pl = _placements(n_cand, i_pad, n_inst, tp_idx, max_batch, occ, q_ticks)
+    rq = _requests(n_req, prompt_len, out_len, slo_class, arrival_ticks)
+    prm = Params(float(s_bar), float(pen_kappa), int(tbt_mode), int(window), int(policy))
+    wts = ScoreWeights(float(alpha), float(beta), float(gamma_t), float(gamma_l))
+    wk = PartitionWork(*[_dptr(work.get(name), getattr(torch, dt)) for name, dt in PARTITION_WORK_FIELDS])
+    n_chains = 0 if chain_offsets is None else int(chain_offsets.numel()) - 1
+    _check(load_library().maaso_resource_partition_requests(
+        ctx.handle, C.byref(pl), _dptr(chain_offsets, torch.int32), n_chains, int(n_gpus), C.byref(rq),
+        int(tight_classes), C.byref(prm), C.byref(wts), C.byref(wk), _stream_handle(stream)),
+        "maaso_resource_partition_requests")
+
+
 # ------------------------------------------------------------------------------------------------
 # plumbing for tests and the benchmark: a workload's arrays as GPU tensors
 # ------------------------------------------------------------------------------------------------
@@ -586,12 +626,50 @@ class DeviceWorkload:
                            tight_classes=tight_classes, stream=stream, **out)
         return out
 
+    def partition_work(self, n_gpus: int, homogeneous: bool = True):
+        """The arrays maaso_resource_partition_requests works in, for this workload's shape."""
+        import torch
+        dev = self.prompt_len.device
+        C_, R = self.w.n_cand, self.w.n_req
+        shape = dict(prompt_len_split=R, out_len_split=R, slo_class_split=R, arrival_ticks_split=R,
+                     n_tight=1, partition=6, phi_opt=1)
+        wk = {}
+        for name, dt in PARTITION_WORK_FIELDS:
+            if name.endswith("_h") or name.endswith("_h_star"):
+                if not homogeneous:
+                    continue
+            if name == "arrival_ticks_split" and self.arrival_ticks is None:
+                continue
+            n = shape.get(name, n_gpus + 1 if name.endswith("_star") else C_)
+            wk[name] = torch.empty(n, dtype=getattr(torch, dt), device=dev)
+        return wk
+
     def resource_partition(self, chain_offsets, tight_classes: int, n_gpus: int, alpha, beta, gamma_t,
-                           gamma_l, window=0, homogeneous=True, stream=None):
-        """Alg. 2 over the resident candidates (growth chains of Alg. 1) and requests: split by SLO,
-        score every chain candidate against R_t, R_l (and all of R for the homogeneous fallback),
-        keep the best accepted deployment per GPU count, scan the partitions.  One device-to-host
-        copy (|R_t|) in the middle; everything else stays on the stream.  Returns a dict of tensors."""
+                           gamma_l, window=0, homogeneous=True, stream=None, work=None):
+        """Alg. 2 over the resident candidates (growth chains of Alg. 1) and requests in ONE call of
+        the library (maaso_resource_partition_requests): nothing comes back to the host in between.
+        `chain_offsets`: numpy array or a device tensor; `work`: arrays from partition_work (made
+        here when absent).  Returns the work dict (tensors)."""
+        import torch
+        dev = self.prompt_len.device
+        if work is None:
+            work = self.partition_work(n_gpus, homogeneous)
+        offs = chain_offsets
+        if not isinstance(offs, torch.Tensor):
+            offs = torch.from_numpy(np.ascontiguousarray(chain_offsets).view(np.int32)).to(dev)
+        maaso_resource_partition_requests(
+            self.ctx, n_cand=self.w.n_cand, i_pad=self.w.i_pad, n_inst=self.n_inst, tp_idx=self.tp_idx,
+            max_batch=self.max_batch, occ=self.occ, q_ticks=self.q_ticks, chain_offsets=offs,
+            n_gpus=n_gpus, **self.request_args(),
+            arrival_ticks=self.arrival_ticks if window else None,
+            tight_classes=tight_classes, window=window, **self.param_args(), alpha=alpha, beta=beta,
+            gamma_t=gamma_t, gamma_l=gamma_l, work=work, stream=stream)
+        return work
+
+    def resource_partition_steps(self, chain_offsets, tight_classes: int, n_gpus: int, alpha, beta,
+                                 gamma_t, gamma_l, window=0, homogeneous=True, stream=None):
+        """The same through the five separate entry points, with |R_t| read back by the host in the
+        middle (what a caller composing Alg. 2 by hand would do).  Returns a dict of tensors."""
         import torch
         dev = self.prompt_len.device
         C_, R = self.w.n_cand, self.w.n_req

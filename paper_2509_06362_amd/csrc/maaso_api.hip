@@ -500,6 +500,134 @@ bool score_weights_ok(const maaso_score_weights* wts) {
          wts->gamma_l > 0.0f && std::isfinite(wts->gamma_t) && std::isfinite(wts->gamma_l);
 }
 
+// One request set of a scoring launch: where it comes from, where its results go, and - for a side
+// of a split that only the device knows - the word holding the split position and which side.
+struct ScoreSet {
+  const maaso_requests* rq;
+  const maaso_score_out* out;
+  const uint32_t* split_at;
+  uint32_t side;
+};
+
+int check_score_sets(const maaso_ctx* ctx, const maaso_placements* pl, uint32_t n_sets,
+                     const ScoreSet* sets, const maaso_params* prm, const maaso_score_weights* wts) {
+  for (uint32_t k = 0; k < n_sets; ++k) {
+    const int rc = check_common(ctx, pl, sets[k].rq, prm);
+    if (rc != MAASO_OK) return rc;
+    if (!sets[k].out->sat_count || !sets[k].out->score) return MAASO_E_INVALID_ARG;
+    if (prm->window != 0u && sets[k].rq->n_req != 0 && !sets[k].rq->arrival_ticks)
+      return MAASO_E_INVALID_ARG;
+  }
+  return score_weights_ok(wts) ? MAASO_OK : MAASO_E_INVALID_ARG;
+}
+
+// Scores every candidate against every set in one launch (arguments checked, call guarded).
+int launch_score_sets(maaso_ctx* ctx, const maaso_placements* pl, uint32_t n_sets,
+                      const ScoreSet* sets, const maaso_params* prm, const maaso_score_weights* wts,
+                      hipStream_t s) {
+  SweepWindowArgs a;
+  fill_sweep_window_args(a, ctx, pl, prm);
+  // longest set first: its blocks run longest, so they should start first (a side of a device-side
+  // split counts with the size of the whole, its upper bound)
+  uint32_t order[MAASO_MAX_REQUEST_SETS];
+  for (uint32_t k = 0; k < n_sets; ++k) order[k] = k;
+  std::stable_sort(order, order + n_sets,
+                   [&](uint32_t x, uint32_t y) { return sets[x].rq->n_req > sets[y].rq->n_req; });
+  for (uint32_t k = 0; k < n_sets; ++k) {
+    const ScoreSet& t = sets[order[k]];
+    add_sweep_window_set(a, t.rq, prm, t.out->sat_count, t.out);
+    a.sets[a.n_sets - 1].split_at = t.split_at;
+    a.sets[a.n_sets - 1].side = t.side;
+  }
+  a.alpha = wts->alpha;
+  a.beta = wts->beta;
+  a.gamma_t = wts->gamma_t;
+  a.gamma_l = wts->gamma_l;
+  {
+    TimedRegion timed(ctx, s);
+    const int rc = launch_sweep_window<true>(a, prm->policy, (size_t)3 * ctx->cells * sizeof(float), s);
+    if (rc != MAASO_OK) return rc;
+  }
+  for (uint32_t k = 0; k < n_sets; ++k)
+    if (sets[k].out->best_cand) {
+      hipLaunchKernelGGL(score_argmax_kernel, dim3(1), dim3(1024), 0, s, sets[k].out->score,
+                         pl->n_cand, sets[k].out->best_cand);
+      if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
+    }
+  return MAASO_OK;
+}
+
+int check_split(const maaso_ctx* ctx, const maaso_requests* rq, const uint32_t* prompt_len_out,
+                const uint32_t* out_len_out, const uint8_t* slo_class_out,
+                const uint32_t* arrival_ticks_out, const uint32_t* n_tight) {
+  if (!ctx || !rq || !n_tight) return MAASO_E_INVALID_ARG;
+  if (rq->n_req > MAASO_MAX_REQUESTS) return MAASO_E_SHAPE;
+  if (rq->n_req != 0 && (!rq->prompt_len || !rq->out_len || !rq->slo_class || !prompt_len_out ||
+                         !out_len_out || !slo_class_out))
+    return MAASO_E_INVALID_ARG;
+  if (rq->n_req != 0 && rq->arrival_ticks && !arrival_ticks_out) return MAASO_E_INVALID_ARG;
+  const uint32_t n_blocks = (uint32_t)(((uint64_t)rq->n_req + kSplitPerBlock - 1) / kSplitPerBlock);
+  return need_workspace(ctx, (size_t)(n_blocks ? n_blocks : 1u) * sizeof(uint32_t));
+}
+
+// Per-block counts, their scan, the scatter: three launches (arguments checked, call guarded).
+int launch_split(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_classes,
+                 uint32_t* prompt_len_out, uint32_t* out_len_out, uint8_t* slo_class_out,
+                 uint32_t* arrival_ticks_out, uint32_t* n_tight, hipStream_t s) {
+  const uint32_t n_blocks = (uint32_t)(((uint64_t)rq->n_req + kSplitPerBlock - 1) / kSplitPerBlock);
+  SplitArgs a;
+  a.n_req = rq->n_req;
+  a.prompt_len = rq->prompt_len;
+  a.out_len = rq->out_len;
+  a.slo_class = rq->slo_class;
+  a.arrival_ticks = rq->arrival_ticks;
+  a.tight_classes = tight_classes;
+  a.n_slo = ctx->n_slo;
+  a.block_tight = static_cast<uint32_t*>(ctx->ws);
+  a.n_tight = n_tight;
+  a.prompt_out = prompt_len_out;
+  a.out_len_out = out_len_out;
+  a.class_out = slo_class_out;
+  a.arrival_out = arrival_ticks_out;
+  a.status = ctx->status;
+  if (n_blocks) hipLaunchKernelGGL(split_count_kernel, dim3(n_blocks), dim3(kPartitionThreads), 0, s, a);
+  hipLaunchKernelGGL(split_scan_kernel, dim3(1), dim3(kPartitionThreads), 0, s, a.block_tight, n_blocks,
+                     n_tight);
+  if (n_blocks) hipLaunchKernelGGL(split_scatter_kernel, dim3(n_blocks), dim3(kPartitionThreads), 0, s, a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+int check_select(const maaso_ctx* ctx, const maaso_placements* pl, const float* score, uint32_t n_gpus,
+                 const float* phi_star, const int32_t* cand_star) {
+  if (!ctx || !pl || !score || !phi_star || !cand_star) return MAASO_E_INVALID_ARG;
+  if (pl->n_cand == 0 || !pl->n_inst || !pl->tp_idx) return MAASO_E_INVALID_ARG;
+  if (!ctx->has_degree) return MAASO_E_INVALID_ARG;
+  if (pl->i_pad == 0 || pl->i_pad > MAASO_MAX_INSTANCES || n_gpus > MAASO_MAX_GPUS) return MAASO_E_SHAPE;
+  return MAASO_OK;
+}
+
+int launch_select(maaso_ctx* ctx, const maaso_placements* pl, const float* score,
+                  const uint32_t* chain_offsets, uint32_t n_chains, uint32_t n_gpus, float* phi_star,
+                  int32_t* cand_star, hipStream_t s) {
+  SelectArgs a;
+  a.score = score;
+  a.n_cand = pl->n_cand;
+  a.i_pad = pl->i_pad;
+  a.n_inst = pl->n_inst;
+  a.tp_idx = pl->tp_idx;
+  a.tp_degree = reinterpret_cast<const uint32_t*>(ctx->tab + (size_t)3 * ctx->cells);
+  a.n_tp = ctx->n_tp;
+  a.chain_offsets = chain_offsets;
+  a.n_chains = chain_offsets ? n_chains : 0u;
+  a.n_gpus = n_gpus;
+  a.phi_star = phi_star;
+  a.cand_star = cand_star;
+  a.status = ctx->status;
+  hipLaunchKernelGGL(ins_deploy_select_kernel, dim3(1), dim3(kPartitionThreads),
+                     ((size_t)n_gpus + 1) * sizeof(unsigned long long), s, a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -772,43 +900,16 @@ int maaso_placement_score_sets(maaso_ctx* ctx, const maaso_placements* pl, uint3
                                const maaso_score_weights* wts, const maaso_score_out* out,
                                void* hip_stream) {
   if (!rq || !out || n_sets == 0u || n_sets > MAASO_MAX_REQUEST_SETS) return MAASO_E_INVALID_ARG;
-  for (uint32_t k = 0; k < n_sets; ++k) {
-    const int rc = check_common(ctx, pl, &rq[k], prm);
-    if (rc != MAASO_OK) return rc;
-    if (!out[k].sat_count || !out[k].score) return MAASO_E_INVALID_ARG;
-    if (prm->window != 0u && rq[k].n_req != 0 && !rq[k].arrival_ticks) return MAASO_E_INVALID_ARG;
-  }
-  if (!score_weights_ok(wts)) return MAASO_E_INVALID_ARG;
+  ScoreSet sets[MAASO_MAX_REQUEST_SETS];
+  for (uint32_t k = 0; k < n_sets; ++k) sets[k] = ScoreSet{&rq[k], &out[k], nullptr, 0u};
+  const int rc = check_score_sets(ctx, pl, n_sets, sets, prm, wts);
+  if (rc != MAASO_OK) return rc;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   CallGuard call(ctx, s);
   if (call.rc != MAASO_OK) return call.rc;
-  SweepWindowArgs a;
-  fill_sweep_window_args(a, ctx, pl, prm);
-  // longest set first: its blocks run longest, so they should start first
-  uint32_t order[MAASO_MAX_REQUEST_SETS];
-  for (uint32_t k = 0; k < n_sets; ++k) order[k] = k;
-  std::stable_sort(order, order + n_sets,
-                   [&](uint32_t x, uint32_t y) { return rq[x].n_req > rq[y].n_req; });
-  for (uint32_t k = 0; k < n_sets; ++k)
-    add_sweep_window_set(a, &rq[order[k]], prm, out[order[k]].sat_count, &out[order[k]]);
-  a.alpha = wts->alpha;
-  a.beta = wts->beta;
-  a.gamma_t = wts->gamma_t;
-  a.gamma_l = wts->gamma_l;
-  {
-    TimedRegion timed(ctx, s);
-    const int rc = launch_sweep_window<true>(a, prm->policy, (size_t)3 * ctx->cells * sizeof(float), s);
-    if (rc != MAASO_OK) return rc;
-  }
-  for (uint32_t k = 0; k < n_sets; ++k)
-    if (out[k].best_cand) {
-      hipLaunchKernelGGL(score_argmax_kernel, dim3(1), dim3(1024), 0, s, out[k].score, pl->n_cand,
-                         out[k].best_cand);
-      if (!hip_ok(hipGetLastError())) return MAASO_E_HIP;
-    }
-  return MAASO_OK;
+  return launch_score_sets(ctx, pl, n_sets, sets, prm, wts, s);
 }
 
 int maaso_profile_fit(int device, uint32_t n_tp, const uint32_t* offsets, const float* level,
@@ -911,71 +1012,28 @@ int maaso_probe_valu(int device, uint32_t pattern, uint32_t trips, double* lane_
 int maaso_split_by_slo(maaso_ctx* ctx, const maaso_requests* rq, uint32_t tight_classes,
                        uint32_t* prompt_len_out, uint32_t* out_len_out, uint8_t* slo_class_out,
                        uint32_t* arrival_ticks_out, uint32_t* n_tight, void* hip_stream) {
-  if (!ctx || !rq || !n_tight) return MAASO_E_INVALID_ARG;
-  if (rq->n_req > MAASO_MAX_REQUESTS) return MAASO_E_SHAPE;
-  if (rq->n_req != 0 && (!rq->prompt_len || !rq->out_len || !rq->slo_class || !prompt_len_out ||
-                         !out_len_out || !slo_class_out))
-    return MAASO_E_INVALID_ARG;
-  if (rq->n_req != 0 && rq->arrival_ticks && !arrival_ticks_out) return MAASO_E_INVALID_ARG;
+  int rc = check_split(ctx, rq, prompt_len_out, out_len_out, slo_class_out, arrival_ticks_out, n_tight);
+  if (rc != MAASO_OK) return rc;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   CallGuard call(ctx, s);
   if (call.rc != MAASO_OK) return call.rc;
-  const uint32_t n_blocks = (uint32_t)(((uint64_t)rq->n_req + kSplitPerBlock - 1) / kSplitPerBlock);
-  const int rc = need_workspace(ctx, (size_t)(n_blocks ? n_blocks : 1u) * sizeof(uint32_t));
-  if (rc != MAASO_OK) return rc;
-  SplitArgs a;
-  a.n_req = rq->n_req;
-  a.prompt_len = rq->prompt_len;
-  a.out_len = rq->out_len;
-  a.slo_class = rq->slo_class;
-  a.arrival_ticks = rq->arrival_ticks;
-  a.tight_classes = tight_classes;
-  a.n_slo = ctx->n_slo;
-  a.block_tight = static_cast<uint32_t*>(ctx->ws);
-  a.n_tight = n_tight;
-  a.prompt_out = prompt_len_out;
-  a.out_len_out = out_len_out;
-  a.class_out = slo_class_out;
-  a.arrival_out = arrival_ticks_out;
-  a.status = ctx->status;
-  if (n_blocks) hipLaunchKernelGGL(split_count_kernel, dim3(n_blocks), dim3(kPartitionThreads), 0, s, a);
-  hipLaunchKernelGGL(split_scan_kernel, dim3(1), dim3(kPartitionThreads), 0, s, a.block_tight, n_blocks,
-                     n_tight);
-  if (n_blocks) hipLaunchKernelGGL(split_scatter_kernel, dim3(n_blocks), dim3(kPartitionThreads), 0, s, a);
-  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+  return launch_split(ctx, rq, tight_classes, prompt_len_out, out_len_out, slo_class_out,
+                      arrival_ticks_out, n_tight, s);
 }
 
 int maaso_ins_deploy_select(maaso_ctx* ctx, const maaso_placements* pl, const float* score,
                             const uint32_t* chain_offsets, uint32_t n_chains, uint32_t n_gpus,
                             float* phi_star, int32_t* cand_star, void* hip_stream) {
-  if (!ctx || !pl || !score || !phi_star || !cand_star) return MAASO_E_INVALID_ARG;
-  if (pl->n_cand == 0 || !pl->n_inst || !pl->tp_idx) return MAASO_E_INVALID_ARG;
-  if (!ctx->has_degree) return MAASO_E_INVALID_ARG;
-  if (pl->i_pad == 0 || pl->i_pad > MAASO_MAX_INSTANCES || n_gpus > MAASO_MAX_GPUS) return MAASO_E_SHAPE;
+  const int rc = check_select(ctx, pl, score, n_gpus, phi_star, cand_star);
+  if (rc != MAASO_OK) return rc;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
-  CallGuard call(ctx, static_cast<hipStream_t>(hip_stream));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
   if (call.rc != MAASO_OK) return call.rc;
-  SelectArgs a;
-  a.score = score;
-  a.n_cand = pl->n_cand;
-  a.i_pad = pl->i_pad;
-  a.n_inst = pl->n_inst;
-  a.tp_idx = pl->tp_idx;
-  a.tp_degree = reinterpret_cast<const uint32_t*>(ctx->tab + (size_t)3 * ctx->cells);
-  a.n_tp = ctx->n_tp;
-  a.chain_offsets = chain_offsets;
-  a.n_chains = chain_offsets ? n_chains : 0u;
-  a.n_gpus = n_gpus;
-  a.phi_star = phi_star;
-  a.cand_star = cand_star;
-  a.status = ctx->status;
-  hipLaunchKernelGGL(ins_deploy_select_kernel, dim3(1), dim3(kPartitionThreads),
-                     ((size_t)n_gpus + 1) * sizeof(unsigned long long),
-                     static_cast<hipStream_t>(hip_stream), a);
-  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+  return launch_select(ctx, pl, score, chain_offsets, n_chains, n_gpus, phi_star, cand_star, s);
 }
 
 int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t_star,
@@ -988,12 +1046,15 @@ int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t
   if (n_gpus > MAASO_MAX_GPUS) return MAASO_E_SHAPE;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return MAASO_E_HIP;
-  CallGuard call(ctx, static_cast<hipStream_t>(hip_stream));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
   if (call.rc != MAASO_OK) return call.rc;
   PartitionArgs a;
   a.n_gpus = n_gpus;
   // initial share of the relaxed sub-cluster: floor(|R_l| / |R| * |G|), from the exact quotient
   a.g_l_cap = n_req == 0 ? 0u : (uint32_t)(((unsigned __int128)n_req_l * n_gpus) / n_req);
+  a.n_tight = nullptr;
+  a.n_req = 0u;
   a.phi_t_star = phi_t_star;
   a.phi_l_star = phi_l_star;
   a.phi_h_star = phi_h_star;
@@ -1002,8 +1063,76 @@ int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t
   a.cand_h_star = cand_h_star;
   a.out = partition;
   a.phi_opt = phi_opt;
-  hipLaunchKernelGGL(resource_partition_kernel, dim3(1), dim3(kPartitionThreads), 0,
-                     static_cast<hipStream_t>(hip_stream), a);
+  hipLaunchKernelGGL(resource_partition_kernel, dim3(1), dim3(kPartitionThreads), 0, s, a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
+int maaso_resource_partition_requests(maaso_ctx* ctx, const maaso_placements* pl,
+                                      const uint32_t* chain_offsets, uint32_t n_chains,
+                                      uint32_t n_gpus, const maaso_requests* rq,
+                                      uint32_t tight_classes, const maaso_params* prm,
+                                      const maaso_score_weights* wts,
+                                      const maaso_partition_work* wk, void* hip_stream) {
+  if (!wk || !rq) return MAASO_E_INVALID_ARG;
+  if (!wk->score_t || !wk->score_l || !wk->sat_t || !wk->sat_l || !wk->phi_t_star ||
+      !wk->phi_l_star || !wk->cand_t_star || !wk->cand_l_star || !wk->partition || !wk->phi_opt)
+    return MAASO_E_INVALID_ARG;
+  const bool homogeneous = wk->score_h != nullptr;
+  if (homogeneous && (!wk->sat_h || !wk->phi_h_star || !wk->cand_h_star)) return MAASO_E_INVALID_ARG;
+  int rc = check_split(ctx, rq, wk->prompt_len_split, wk->out_len_split, wk->slo_class_split,
+                       wk->arrival_ticks_split, wk->n_tight);
+  if (rc != MAASO_OK) return rc;
+  // the split arrays as one request set of n_req requests; its two sides are cut on the device
+  maaso_requests whole = *rq;
+  whole.prompt_len = wk->prompt_len_split;
+  whole.out_len = wk->out_len_split;
+  whole.slo_class = wk->slo_class_split;
+  whole.arrival_ticks = rq->arrival_ticks ? wk->arrival_ticks_split : nullptr;
+  const maaso_score_out out_t = {wk->sat_t, nullptr, nullptr, nullptr, wk->score_t, nullptr};
+  const maaso_score_out out_l = {wk->sat_l, nullptr, nullptr, nullptr, wk->score_l, nullptr};
+  const maaso_score_out out_h = {wk->sat_h, nullptr, nullptr, nullptr, wk->score_h, nullptr};
+  ScoreSet sets[3];
+  uint32_t n_sets = 0;
+  if (homogeneous) sets[n_sets++] = ScoreSet{rq, &out_h, nullptr, 0u};
+  sets[n_sets++] = ScoreSet{&whole, &out_t, wk->n_tight, 1u};
+  sets[n_sets++] = ScoreSet{&whole, &out_l, wk->n_tight, 2u};
+  rc = check_score_sets(ctx, pl, n_sets, sets, prm, wts);
+  if (rc != MAASO_OK) return rc;
+  rc = check_select(ctx, pl, wk->score_t, n_gpus, wk->phi_t_star, wk->cand_t_star);
+  if (rc != MAASO_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
+  if (call.rc != MAASO_OK) return call.rc;
+  rc = launch_split(ctx, rq, tight_classes, wk->prompt_len_split, wk->out_len_split,
+                    wk->slo_class_split, wk->arrival_ticks_split, wk->n_tight, s);
+  if (rc != MAASO_OK) return rc;
+  rc = launch_score_sets(ctx, pl, n_sets, sets, prm, wts, s);
+  if (rc != MAASO_OK) return rc;
+  rc = launch_select(ctx, pl, wk->score_t, chain_offsets, n_chains, n_gpus, wk->phi_t_star,
+                     wk->cand_t_star, s);
+  if (rc == MAASO_OK)
+    rc = launch_select(ctx, pl, wk->score_l, chain_offsets, n_chains, n_gpus, wk->phi_l_star,
+                       wk->cand_l_star, s);
+  if (rc == MAASO_OK && homogeneous)
+    rc = launch_select(ctx, pl, wk->score_h, chain_offsets, n_chains, n_gpus, wk->phi_h_star,
+                       wk->cand_h_star, s);
+  if (rc != MAASO_OK) return rc;
+  PartitionArgs a;
+  a.n_gpus = n_gpus;
+  a.g_l_cap = 0u;
+  a.n_tight = wk->n_tight;  // G'_l = floor(|R_l| * |G| / |R|) from the device's |R_t|
+  a.n_req = rq->n_req;
+  a.phi_t_star = wk->phi_t_star;
+  a.phi_l_star = wk->phi_l_star;
+  a.phi_h_star = homogeneous ? wk->phi_h_star : nullptr;
+  a.cand_t_star = wk->cand_t_star;
+  a.cand_l_star = wk->cand_l_star;
+  a.cand_h_star = homogeneous ? wk->cand_h_star : nullptr;
+  a.out = wk->partition;
+  a.phi_opt = wk->phi_opt;
+  hipLaunchKernelGGL(resource_partition_kernel, dim3(1), dim3(kPartitionThreads), 0, s, a);
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
 

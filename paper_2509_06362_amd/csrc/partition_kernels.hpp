@@ -137,6 +137,10 @@ __global__ __launch_bounds__(kPartitionThreads) void ins_deploy_select_kernel(co
 // ------------------------------------------------------------------------------------------------
 struct PartitionArgs {
   uint32_t n_gpus, g_l_cap;
+  // with n_tight set (|R_t| as the split left it on the device) the cap is worked out here from
+  // n_req instead: floor((n_req - *n_tight) * n_gpus / n_req), exact in 64-bit integers
+  const uint32_t* n_tight;
+  uint32_t n_req;
   const float* phi_t_star;     // [n_gpus + 1]
   const float* phi_l_star;     // [n_gpus + 1]
   const float* phi_h_star;     // [n_gpus + 1] or null: homogeneous deployment of all requests
@@ -167,7 +171,13 @@ __global__ __launch_bounds__(kPartitionThreads) void resource_partition_kernel(c
   const uint32_t k_h = hk ? ~(uint32_t)(hk & 0xffffffffull) : 0u;
 
   unsigned long long pk = 0ull;
-  const uint32_t cap = min(a.g_l_cap, a.n_gpus);
+  uint32_t g_l_cap = a.g_l_cap;
+  if (a.n_tight) {
+    const uint32_t n_t = min(*a.n_tight, a.n_req);
+    g_l_cap = a.n_req == 0u ? 0u
+                            : (uint32_t)(((unsigned long long)(a.n_req - n_t) * a.n_gpus) / a.n_req);
+  }
+  const uint32_t cap = min(g_l_cap, a.n_gpus);
   for (uint32_t gl = 1u + tid; gl <= cap; gl += kPartitionThreads) {
     const float sum = a.phi_t_star[a.n_gpus - gl] + a.phi_l_star[gl];
     if (sum > opt0) {

@@ -55,11 +55,14 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
   for (uint32_t i = tid; i < 3u * a.cells; i += kSeqThreads) tab[i] = a.tab[i];
   __syncthreads();  // the only barrier: from here on a wavefront works alone
 
-  const uint64_t unit = (uint64_t)blockIdx.x * (kSeqThreads / 64) + (tid >> 6);
+  // the wavefront's number within the block, as a scalar: what follows from it (the request set,
+  // its pointers and size) then stays in scalar registers
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
+  const uint64_t unit = (uint64_t)blockIdx.x * (kSeqThreads / 64) + wave;
   if (unit >= (uint64_t)a.n_sets * a.n_cand) return;
   const uint32_t set = (uint32_t)(unit / a.n_cand);
   const uint32_t c = (uint32_t)(unit - (uint64_t)set * a.n_cand);
-  const SweepWindowSet& rs = a.sets[set];
+  const SweepWindowSet rs = resolve_set(a.sets[set]);
   const size_t base = (size_t)c * a.i_pad;
   const uint32_t n = min(a.n_inst[c], a.i_pad);
 

@@ -32,9 +32,30 @@ struct SweepWindowSet {
   float* phi_t;
   float* phi_l;
   float* score;
+  // One side of a split whose position only the device knows (Alg. 2 scores R_t and R_l straight
+  // after the split, without the host reading |R_t| back): with split_at set, the pointers above
+  // address the whole split array of n_req requests and the set is its first *split_at requests
+  // (side == 1) or the rest (side == 2).
+  const uint32_t* split_at;
+  uint32_t side;
 };
 
 constexpr int kMaxSweepSets = 4;
+
+// The set a block works on, with a device-side split applied.
+__device__ __forceinline__ SweepWindowSet resolve_set(const SweepWindowSet& in) {
+  SweepWindowSet rs = in;
+  if (in.split_at) {
+    const uint32_t at = min(*in.split_at, in.n_req);
+    const uint32_t off = in.side == 1u ? 0u : at;
+    rs.n_req = in.side == 1u ? at : in.n_req - at;
+    rs.prompt_len += off;
+    rs.out_len += off;
+    rs.slo_class += off;
+    if (rs.arrival_ticks) rs.arrival_ticks += off;
+  }
+  return rs;
+}
 
 struct SweepWindowArgs {
   const float* tab;
@@ -86,7 +107,7 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
   const uint32_t tid = threadIdx.x;
   const uint32_t set = blockIdx.x / a.n_cand;
   const uint32_t c = blockIdx.x - set * a.n_cand;
-  const SweepWindowSet& rs = a.sets[set];
+  const SweepWindowSet rs = resolve_set(a.sets[set]);
   const size_t base = (size_t)c * a.i_pad;
   const uint32_t n = min(a.n_inst[c], a.i_pad);
   uint32_t tp = 0, B = 1;

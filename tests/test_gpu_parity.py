@@ -677,8 +677,11 @@ def test_resource_partition_scan():
     (6000, 400.0, 32, 64, 0.5), (4000, 60.0, 24, 32, 0.2), (3000, 900.0, 16, 256, 0.8),
     (2000, 300.0, 12, 64, 1.0), (2000, 300.0, 12, 64, 0.0),
 ])
-def test_resource_partition_end_to_end(n_req, rate, n_gpus, window, share):
-    """Alg. 2 as one pipeline of library calls against the oracle's sequential Alg. 1 + Alg. 2."""
+@pytest.mark.parametrize("one_call", [True, False])
+def test_resource_partition_end_to_end(n_req, rate, n_gpus, window, share, one_call):
+    """Alg. 2 against the oracle's sequential Alg. 1 + Alg. 2: as ONE library call that keeps |R_t| on
+    the device (maaso_resource_partition_requests), and as the five separate calls with |R_t| read
+    back by the host in between."""
     w = W.partition_case(n_req=n_req, rate=rate, seed=30 + n_gpus, tight_share=share)
     tp, b = W.all_configs(batch_set=[4, 16, 64])
     cw, offs = W.growth_chains(w, tp, b, n_gpus)
@@ -691,10 +694,16 @@ def test_resource_partition_end_to_end(n_req, rate, n_gpus, window, share):
     dw = binding.DeviceWorkload(cw)
     try:
         print(f"alg2 R={n_req} G={n_gpus} C={cw.n_cand} window={window} share={share}", flush=True)
-        got = dw.resource_partition(offs, 0b1, n_gpus, *wts, window=window)
+        run = dw.resource_partition if one_call else dw.resource_partition_steps
+        got = run(offs, 0b1, n_gpus, *wts, window=window)
         torch.cuda.synchronize()
         assert binding.maaso_ctx_device_status(dw.ctx) == 0
-        assert got["n_tight"] == r_t.n_req
+        assert int(got["n_tight"]) == r_t.n_req
+        if one_call:
+            for name, key in (("prompt_len", "prompt_len_split"), ("out_len", "out_len_split"),
+                              ("arrival_ticks", "arrival_ticks_split")):
+                both = np.concatenate([getattr(r_t, name), getattr(r_l, name)])
+                assert np.array_equal(got[key].cpu().numpy().view(np.uint32), both), name
         for tag in ("t", "l", "h"):
             assert np.array_equal(got[f"phi_{tag}_star"].cpu().numpy(), ref[tag]["phi_star"]), tag
             cfg, cnt = star_as_config(got[f"cand_{tag}_star"].cpu().numpy(), offs)
@@ -702,6 +711,36 @@ def test_resource_partition_end_to_end(n_req, rate, n_gpus, window, share):
         p = got["partition"].cpu().numpy()
         assert p[:4].tolist() == [part["g_t"], part["g_l"], part["heterogeneous"], part["k_h"]]
         assert float(got["phi_opt"].item()) == part["phi_opt"]
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("window,homogeneous,share", [(0, True, 0.5), (64, False, 0.3), (0, False, 1.0),
+                                                      (1, True, 0.6)])
+def test_resource_partition_one_call_equals_the_five_calls(window, homogeneous, share):
+    """Static scoring, no homogeneous fallback, an empty side, request-by-request windows: the one-call
+    form writes what the step-by-step form writes, array by array."""
+    w = W.partition_case(n_req=1500, rate=300.0, seed=44, tight_share=share)
+    tp, b = W.all_configs(batch_set=[4, 16, 64])
+    cw, offs = W.growth_chains(w, tp, b, 12)
+    wts = SCORE_WEIGHTS[0]
+    dw = binding.DeviceWorkload(cw)
+    try:
+        print(f"alg2 one call vs steps window={window} homogeneous={homogeneous} share={share}", flush=True)
+        one = dw.resource_partition(offs, 0b1, 12, *wts, window=window, homogeneous=homogeneous)
+        torch.cuda.synchronize()
+        steps = dw.resource_partition_steps(offs, 0b1, 12, *wts, window=window, homogeneous=homogeneous)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        assert int(one["n_tight"]) == steps["n_tight"]
+        tags = ("t", "l", "h") if homogeneous else ("t", "l")
+        for tag in tags:
+            for key in (f"score_{tag}", f"phi_{tag}_star", f"cand_{tag}_star"):
+                assert torch.equal(one[key], steps[key]), key
+        assert torch.equal(one["partition"], steps["partition"])
+        assert torch.equal(one["phi_opt"], steps["phi_opt"])
+        assert torch.equal(one["prompt_len_split"], steps["split"]["prompt_len_out"])
+        assert torch.equal(one["slo_class_split"], steps["split"]["slo_class_out"])
     finally:
         dw.close()
 
@@ -760,6 +799,17 @@ def test_outer_algorithm_error_paths():
         with pytest.raises(binding.MaasoError) as e:
             binding.maaso_resource_partition(dw.ctx, n_gpus=4, phi_t_star=phi, phi_l_star=phi,
                                              n_req_l=5, n_req=4, partition=cand, phi_opt=phi)
+        assert e.value.status == -1
+        # the one-call form refuses a work set without a required array, before launching anything
+        work = dw.partition_work(8)
+        del work["partition"]
+        with pytest.raises(binding.MaasoError) as e:
+            dw.resource_partition(offs, 0b1, 8, 4.0, 0.3, 512.0, 0.5, window=16, work=work)
+        assert e.value.status == -1
+        work = dw.partition_work(8)
+        del work["phi_h_star"]      # score_h given, its list not
+        with pytest.raises(binding.MaasoError) as e:
+            dw.resource_partition(offs, 0b1, 8, 4.0, 0.3, 512.0, 0.5, window=16, work=work)
         assert e.value.status == -1
         # a profile loaded without GPU counts cannot drive Alg. 1's bookkeeping
         ctx = binding.maaso_profile_tables_load(cw.n_tp, cw.b_cap, cw.prefill_a, cw.prefill_p, cw.tbt,
