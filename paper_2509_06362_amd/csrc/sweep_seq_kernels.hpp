@@ -28,19 +28,24 @@ __device__ __forceinline__ float lane_value(float v, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
 
-// Arg-max of (slack, index) over the whole wavefront, lowest index among equals; every lane ends
-// with the winner.  Four DPP steps settle each row of 16 lanes; the four row winners are then read
-// with v_readlane and compared as uniform values - no trip through LDS on the per-request chain.
-__device__ __forceinline__ void argmax_wave(float& s, int32_t& i) {
-  argmax_lanes<16>(s, i);
-  float s0 = lane_value(s, 0), s1 = lane_value(s, 16), s2 = lane_value(s, 32), s3 = lane_value(s, 48);
-  int32_t i0 = __builtin_amdgcn_readlane(i, 0), i1 = __builtin_amdgcn_readlane(i, 16);
-  int32_t i2 = __builtin_amdgcn_readlane(i, 32), i3 = __builtin_amdgcn_readlane(i, 48);
-  take_better(s0, i0, s1, i1);
-  take_better(s2, i2, s3, i3);
-  take_better(s0, i0, s2, i2);
-  s = s0;
-  i = i0;
+// Arg-max of (slack, index) over the whole wavefront, lowest index among equals, as uniform values.
+// The largest slack: four DPP steps settle each row of 16 lanes, two row broadcasts carry the rows'
+// maxima into lane 63, one v_readlane fetches it.  The lowest index among the lanes that hold it:
+// a lane's index is slot * 64 + lane (S slots per lane; -1 while it has seen nothing above -inf), so
+// the lowest slot with a holder, and the first holder among its lanes, found on the scalar unit from
+// one lane mask per slot - no trip through LDS and no per-lane compare chain on the per-request path.
+template <int S>
+__device__ __forceinline__ void argmax_wave(float s, int32_t i, uint32_t lane, float& ws, int32_t& wi) {
+  float m = max_lanes<16>(s);
+  MAASO_DPP_FOLD_ROWS("v_max_f32_dpp", m, "row_bcast:15", "0xa");
+  MAASO_DPP_FOLD_ROWS("v_max_f32_dpp", m, "row_bcast:31", "0xc");
+  ws = lane_value(m, 63);
+  wi = -1;
+#pragma unroll
+  for (int sl = S - 1; sl >= 0; --sl) {
+    const unsigned long long held = __ballot((s == ws) & (i == (int32_t)((uint32_t)sl * 64u + lane)));
+    if (held != 0ull) wi = sl * 64 + (int32_t)__builtin_ctzll(held);
+  }
 }
 
 template <bool kScore, int S>
@@ -84,6 +89,7 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
   }
   unsigned long long wait_sum = 0ull;  // queue waits of the requests this lane's instances admitted, ticks
   uint32_t sat = 0;                    // uniform
+  bool bad_slot = false;               // a slot of this lane was outside the tables at some window
 
   const uint64_t R = rs.n_req;
   const uint64_t W = rs.window;
@@ -108,7 +114,7 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
       Staged st{1.0f, 1.0f, 1.0f, 1.0f, INFINITY};
       const bool ok = stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st);
       const bool use = valid[s] & ok;
-      if (valid[s] & !ok) raise_status(a.status, 2u);
+      bad_slot |= valid[s] & !ok;  // reported once, when the wavefront is done
       ra[s] = use ? st.a : 1.0f; rp[s] = use ? st.p : 1.0f; rt[s] = use ? st.tbt : 1.0f;
       rw[s] = use ? st.wait : INFINITY;
       svc[s] = use ? st.svc : 1.0f;
@@ -147,9 +153,9 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
         if (m.slack > best) { best = m.slack; idx = (int32_t)((uint32_t)s * 64u + lane); bpre = m.pre; }
       }
       if (!live) { best = -INFINITY; idx = -1; }
-      float wbest = best;
-      int32_t widx = idx;
-      argmax_wave(wbest, widx);       // every lane ends with the wavefront's winner
+      float wbest;
+      int32_t widx;
+      argmax_wave<S>(best, idx, lane, wbest, widx);  // the wavefront's winner, uniform
       if (live && wbest >= 0.0f) {    // admitted: the chosen instance takes the load at the window's end
         sat += 1u;
 #pragma unroll
@@ -181,6 +187,7 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
     }
   }
 
+  if (bad_slot) raise_status(a.status, 2u);
   // results of this (set, candidate): lane 0 writes them
   if (kScore) wait_sum = wave_sum_u64(wait_sum);
   float pt = 0.0f;
@@ -241,6 +248,7 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
     if (valid[s]) { tp[s] = row.tp_idx[j]; B[s] = row.max_batch[j]; occ[s] = row.occ[j]; q[s] = row.q_ticks[j]; }
   }
   unsigned long long sat = 0ull;  // uniform
+  bool bad_slot = false;          // a slot of this lane was outside the tables at some window
 
   const uint64_t R = a.n_req;
   const uint64_t W = window;
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
       Staged st{1.0f, 1.0f, 1.0f, 1.0f, INFINITY};
       const bool ok = stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st);
       const bool use = valid[s] & ok;
-      if (valid[s] & !ok) raise_status(a.status, 2u);
+      bad_slot |= valid[s] & !ok;  // reported once, when the wavefront is done
       ra[s] = use ? st.a : 1.0f; rp[s] = use ? st.p : 1.0f; rt[s] = use ? st.tbt : 1.0f;
       rw[s] = use ? st.wait : INFINITY;
       svc[s] = use ? st.svc : 1.0f;
@@ -310,9 +318,9 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
         }
       }
       if (!live) { best = -INFINITY; idx = -1; }
-      float wbest = best;
-      int32_t widx = idx;
-      argmax_wave(wbest, widx);
+      float wbest;
+      int32_t widx;
+      argmax_wave<S>(best, idx, lane, wbest, widx);
       // what is reported about the chosen instance comes from the lane that holds it
       const float nanv = __builtin_nanf("");
       float w_ttft = nanv, w_tbt = nanv, w_e2e = nanv;
@@ -347,6 +355,7 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
     }
   }
   flush();
+  if (bad_slot) raise_status(a.status, 2u);
 #pragma unroll
   for (int s = 0; s < S; ++s)
     if (valid[s]) { row.occ[(uint32_t)s * 64u + lane] = occ[s]; row.q_ticks[(uint32_t)s * 64u + lane] = q[s]; }
