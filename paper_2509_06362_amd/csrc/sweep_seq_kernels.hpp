@@ -115,9 +115,12 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
       const bool ok = stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st);
       const bool use = valid[s] & ok;
       bad_slot |= valid[s] & !ok;  // reported once, when the wavefront is done
-      ra[s] = use ? st.a : 1.0f; rp[s] = use ? st.p : 1.0f; rt[s] = use ? st.tbt : 1.0f;
+      // an unused slot keeps whatever finite record came out (an absent slot holds a configuration
+      // inside the tables, a rejected one the defaults above): its infinite wait alone keeps it from
+      // ever being the best, and its occupancy of zero from ever draining
+      ra[s] = st.a; rp[s] = st.p; rt[s] = st.tbt;
       rw[s] = use ? st.wait : INFINITY;
-      svc[s] = use ? st.svc : 1.0f;
+      svc[s] = st.svc;
       wait_ticks[s] = 0ull;
       if (kScore) {
         wait_ticks[s] = use ? (unsigned long long)__float2ll_rn(st.wait * 1048576.0f) : 0ull;
@@ -281,9 +284,12 @@ __global__ __launch_bounds__(64) void assign_seq_kernel(const AssignArgs a, uint
       const bool ok = stage_instance(tab, a.cells, a.mp, tp[s], B[s], occ[s], q[s], st);
       const bool use = valid[s] & ok;
       bad_slot |= valid[s] & !ok;  // reported once, when the wavefront is done
-      ra[s] = use ? st.a : 1.0f; rp[s] = use ? st.p : 1.0f; rt[s] = use ? st.tbt : 1.0f;
+      // an unused slot keeps whatever finite record came out (an absent slot holds a configuration
+      // inside the tables, a rejected one the defaults above): its infinite wait alone keeps it from
+      // ever being the best, and its occupancy of zero from ever draining
+      ra[s] = st.a; rp[s] = st.p; rt[s] = st.tbt;
       rw[s] = use ? st.wait : INFINITY;
-      svc[s] = use ? st.svc : 1.0f;
+      svc[s] = st.svc;
     }
     for (uint64_t r = s0; r < e0; ++r) {
       if ((r & ~63ull) != batch0) {
