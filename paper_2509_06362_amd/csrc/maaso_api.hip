@@ -606,11 +606,17 @@ int check_select(const maaso_ctx* ctx, const maaso_placements* pl, const float* 
   return MAASO_OK;
 }
 
-int launch_select(maaso_ctx* ctx, const maaso_placements* pl, const float* score,
-                  const uint32_t* chain_offsets, uint32_t n_chains, uint32_t n_gpus, float* phi_star,
-                  int32_t* cand_star, hipStream_t s) {
+// Alg. 1's selection over n_lists score lists of the same deployments, one block each.
+int launch_select(maaso_ctx* ctx, const maaso_placements* pl, uint32_t n_lists, const float* const* score,
+                  const uint32_t* chain_offsets, uint32_t n_chains, uint32_t n_gpus,
+                  float* const* phi_star, int32_t* const* cand_star, hipStream_t s) {
   SelectArgs a;
-  a.score = score;
+  a.n_lists = n_lists;
+  for (uint32_t l = 0; l < (uint32_t)kMaxSelectLists; ++l) {
+    a.score[l] = l < n_lists ? score[l] : nullptr;
+    a.phi_star[l] = l < n_lists ? phi_star[l] : nullptr;
+    a.cand_star[l] = l < n_lists ? cand_star[l] : nullptr;
+  }
   a.n_cand = pl->n_cand;
   a.i_pad = pl->i_pad;
   a.n_inst = pl->n_inst;
@@ -620,10 +626,8 @@ int launch_select(maaso_ctx* ctx, const maaso_placements* pl, const float* score
   a.chain_offsets = chain_offsets;
   a.n_chains = chain_offsets ? n_chains : 0u;
   a.n_gpus = n_gpus;
-  a.phi_star = phi_star;
-  a.cand_star = cand_star;
   a.status = ctx->status;
-  hipLaunchKernelGGL(ins_deploy_select_kernel, dim3(1), dim3(kPartitionThreads),
+  hipLaunchKernelGGL(ins_deploy_select_kernel, dim3(n_lists), dim3(kPartitionThreads),
                      ((size_t)n_gpus + 1) * sizeof(unsigned long long), s, a);
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
@@ -1033,7 +1037,7 @@ int maaso_ins_deploy_select(maaso_ctx* ctx, const maaso_placements* pl, const fl
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   CallGuard call(ctx, s);
   if (call.rc != MAASO_OK) return call.rc;
-  return launch_select(ctx, pl, score, chain_offsets, n_chains, n_gpus, phi_star, cand_star, s);
+  return launch_select(ctx, pl, 1u, &score, chain_offsets, n_chains, n_gpus, &phi_star, &cand_star, s);
 }
 
 int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t_star,
@@ -1110,14 +1114,13 @@ int maaso_resource_partition_requests(maaso_ctx* ctx, const maaso_placements* pl
   if (rc != MAASO_OK) return rc;
   rc = launch_score_sets(ctx, pl, n_sets, sets, prm, wts, s);
   if (rc != MAASO_OK) return rc;
-  rc = launch_select(ctx, pl, wk->score_t, chain_offsets, n_chains, n_gpus, wk->phi_t_star,
-                     wk->cand_t_star, s);
-  if (rc == MAASO_OK)
-    rc = launch_select(ctx, pl, wk->score_l, chain_offsets, n_chains, n_gpus, wk->phi_l_star,
-                       wk->cand_l_star, s);
-  if (rc == MAASO_OK && homogeneous)
-    rc = launch_select(ctx, pl, wk->score_h, chain_offsets, n_chains, n_gpus, wk->phi_h_star,
-                       wk->cand_h_star, s);
+  {
+    const float* scores[3] = {wk->score_t, wk->score_l, wk->score_h};
+    float* phis[3] = {wk->phi_t_star, wk->phi_l_star, wk->phi_h_star};
+    int32_t* cands[3] = {wk->cand_t_star, wk->cand_l_star, wk->cand_h_star};
+    rc = launch_select(ctx, pl, homogeneous ? 3u : 2u, scores, chain_offsets, n_chains, n_gpus, phis,
+                       cands, s);
+  }
   if (rc != MAASO_OK) return rc;
   PartitionArgs a;
   a.n_gpus = n_gpus;

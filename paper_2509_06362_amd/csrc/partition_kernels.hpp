@@ -46,8 +46,13 @@ __device__ inline unsigned long long block_max_u64(unsigned long long v, unsigne
 // ------------------------------------------------------------------------------------------------
 // Alg. 1 bookkeeping
 // ------------------------------------------------------------------------------------------------
+constexpr int kMaxSelectLists = 4;
+
+// Block b works on score list b: the same deployments scored against several request sets (Alg. 2
+// runs Alg. 1 on R_t, on R_l and on all of R) are selected in one launch.
 struct SelectArgs {
-  const float* score;       // [n_cand] composite score of every candidate deployment
+  uint32_t n_lists;
+  const float* score[kMaxSelectLists];  // [n_cand] composite score of every candidate deployment
   uint32_t n_cand, i_pad;
   const uint32_t* n_inst;   // [n_cand]
   const uint8_t* tp_idx;    // [n_cand][i_pad]
@@ -56,8 +61,8 @@ struct SelectArgs {
   const uint32_t* chain_offsets;  // [n_chains + 1] or null (every candidate on its own)
   uint32_t n_chains;
   uint32_t n_gpus;
-  float* phi_star;      // [n_gpus + 1]
-  int32_t* cand_star;   // [n_gpus + 1]
+  float* phi_star[kMaxSelectLists];     // [n_gpus + 1]
+  int32_t* cand_star[kMaxSelectLists];  // [n_gpus + 1]
   uint32_t* status;
 };
 
@@ -76,7 +81,7 @@ __device__ inline uint32_t gpu_count(const SelectArgs& a, uint32_t c) {
   return k > 0xfffffffeull ? 0xfffffffeu : (uint32_t)k;
 }
 
-// One block.  A chain is the growth path of one configuration in Alg. 1: its m-th candidate is the
+// One block per score list.  A chain is the growth path of one configuration in Alg. 1: its m-th candidate is the
 // deployment after m + 1 additions.  A candidate is accepted when every candidate before it in the
 // chain was accepted, it fits into n_gpus GPUs and its score is strictly larger than that of the
 // candidate before it (0 for the first): the first failure ends the chain, as the saturated model ends
@@ -87,12 +92,15 @@ __global__ __launch_bounds__(kPartitionThreads) void ins_deploy_select_kernel(co
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem);  // [n_gpus + 1]
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const float* score = a.score[blockIdx.x];
+  float* phi_star = a.phi_star[blockIdx.x];
+  int32_t* cand_star = a.cand_star[blockIdx.x];
   for (uint32_t k = tid; k <= a.n_gpus; k += kPartitionThreads) keys[k] = 0ull;
   __syncthreads();
 
   if (a.chain_offsets == nullptr) {
     for (uint32_t c = tid; c < a.n_cand; c += kPartitionThreads) {
-      const float s = a.score[c];
+      const float s = score[c];
       const uint32_t k = gpu_count(a, c);
       if (s > 0.0f && k <= a.n_gpus)
         atomicMax(&keys[k], ((unsigned long long)float_order(s) << 32) | (unsigned long long)(~c));
@@ -111,8 +119,8 @@ __global__ __launch_bounds__(kPartitionThreads) void ins_deploy_select_kernel(co
         float s = 0.0f, prev = 0.0f;
         uint32_t k = 0;
         if (in) {
-          s = a.score[c];
-          prev = (c == o0) ? 0.0f : a.score[c - 1];
+          s = score[c];
+          prev = (c == o0) ? 0.0f : score[c - 1];
           k = gpu_count(a, c);
         }
         const bool ok = in && s > prev && k <= a.n_gpus;
@@ -127,8 +135,8 @@ __global__ __launch_bounds__(kPartitionThreads) void ins_deploy_select_kernel(co
   lds_atomics_barrier();
   for (uint32_t k = tid; k <= a.n_gpus; k += kPartitionThreads) {
     const unsigned long long key = keys[k];
-    a.phi_star[k] = key ? order_float((uint32_t)(key >> 32)) : 0.0f;
-    a.cand_star[k] = key ? (int32_t)(~(uint32_t)(key & 0xffffffffull)) : -1;
+    phi_star[k] = key ? order_float((uint32_t)(key >> 32)) : 0.0f;
+    cand_star[k] = key ? (int32_t)(~(uint32_t)(key & 0xffffffffull)) : -1;
   }
 }
 
