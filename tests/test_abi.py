@@ -43,6 +43,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(binding.AssignOut) == 48
     assert C.sizeof(binding.ScoreWeights) == 16
     assert C.sizeof(binding.ScoreOut) == 48
+    assert C.sizeof(binding.PartitionWork) == 19 * 8
 
 
 def test_strerror(lib):
@@ -130,9 +131,9 @@ def test_header_is_plain_c_and_layouts_agree_with_the_binding(lib, tmp_path):
     src.write_text(
         '#include <stdio.h>\n#include "maaso.h"\n'
         "int main(void) {\n"
-        '  printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(maaso_profile_desc), sizeof(maaso_requests),\n'
+        '  printf("%zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(maaso_profile_desc), sizeof(maaso_requests),\n'
         "         sizeof(maaso_placements), sizeof(maaso_params), sizeof(maaso_assign_out),\n"
-        "         sizeof(maaso_score_weights), sizeof(maaso_score_out));\n"
+        "         sizeof(maaso_score_weights), sizeof(maaso_score_out), sizeof(maaso_partition_work));\n"
         '  printf("%s\\n", maaso_strerror(MAASO_OK));\n'
         '  printf("%d\\n", maaso_score_assign(NULL, NULL, NULL, NULL, NULL, NULL));\n'
         "  return 0;\n}\n")
@@ -145,7 +146,7 @@ def test_header_is_plain_c_and_layouts_agree_with_the_binding(lib, tmp_path):
     sizes = [int(x) for x in out[0].split()]
     assert sizes == [C.sizeof(t) for t in (binding.ProfileDesc, binding.Requests, binding.Placements,
                                            binding.Params, binding.AssignOut, binding.ScoreWeights,
-                                           binding.ScoreOut)]
+                                           binding.ScoreOut, binding.PartitionWork)]
     assert out[1] == "ok" and int(out[2]) == -1
 
 
@@ -170,3 +171,44 @@ def test_static_scratch_array_is_visible_to_the_runtime(lib, tmp_path):
     assert rows, "no scratch object in the device code object"
     assert all(r[4] == "GLOBAL" for r in rows), rows
     assert int(rows[0][2]) == binding.MAASO_NOALLOC_SCRATCH_BYTES
+
+
+def test_partition_work_fields_follow_the_header():
+    """The binding fills maaso_partition_work by position: its field list must be the header's, in order."""
+    text = HEADER.read_text()
+    body = text[text.index("typedef struct {", text.index("Arrays that maaso_resource_partition_requests")):
+                text.index("} maaso_partition_work;")]
+    import re
+    fields = re.findall(r"^\s*(?:uint32_t|uint8_t|int32_t|float)\*\s*(\w+);", body, flags=re.M)
+    assert fields == [name for name, _ in binding.PARTITION_WORK_FIELDS]
+
+
+def test_every_export_has_declared_argument_types(lib):
+    """ctypes passes an integer without a declared type as a C int: a device pointer would be cut to
+    32 bits.  The loader refuses to come up with an undeclared signature; check that it looked."""
+    for name in binding.EXPORTS:
+        if name != "maaso_strerror":
+            assert getattr(lib, name).argtypes is not None, name
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = HEADER.parent.parent
+    res = subprocess.run([sys.executable, str(root / "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, cwd=root)
+    assert res.returncode != 0
+    assert "one GPU" in (res.stdout + res.stderr)
+
+
+def test_traffic_figures_go_stale_with_the_kernel_source(monkeypatch):
+    """roofline.traffic is a counter reading of a particular kernel: it is reported while the digest of
+    that kernel's sources matches and withheld, with both digests, once they have changed."""
+    import bench
+    nbytes, info = bench.measured_traffic("cfg4_skewed_stress")
+    assert info["source"] == "profiles/sweep_kernel_cfg4.md"
+    assert (nbytes is None) == info["stale"]
+    monkeypatch.setattr(bench, "kernel_source_digest", lambda kernel: "0" * 16)
+    nbytes, info = bench.measured_traffic("cfg4_skewed_stress")
+    assert nbytes is None and info["stale"] and info["kernel_digest_now"] == "0" * 16
+    assert bench.measured_traffic("cfg0_tiny_distributor")[0] is None
