@@ -16,7 +16,8 @@
  *   - Compute calls (maaso_score_assign, maaso_score_assign_selected, maaso_placement_sweep,
  *     maaso_placement_sweep_noalloc, maaso_placement_score, maaso_placement_score_sets,
  *     maaso_split_by_slo, maaso_ins_deploy_select, maaso_resource_partition,
- *     maaso_resource_partition_requests) are asynchronous on the given HIP stream (NULL = the default stream).  They allocate nothing, free nothing and do no
+ *     maaso_resource_partition_requests, maaso_batch_size_prune) are asynchronous on the given HIP
+ *     stream (NULL = the default stream).  They allocate nothing, free nothing and do no
  *     host synchronisation: the context's workspace is sized at maaso_profile_tables_load
  *     (MAASO_DEFAULT_WORKSPACE_BYTES, enough for 65,536 candidates of 32 instance slots) and
  *     changed only by maaso_ctx_reserve; a call whose shape needs more is refused with
@@ -439,6 +440,23 @@ int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t
                              const int32_t* cand_t_star, const int32_t* cand_l_star,
                              const int32_t* cand_h_star, uint64_t n_req_l, uint64_t n_req,
                              uint32_t* partition, float* phi_opt, void* hip_stream);
+
+/* Batch-size pruning ahead of Alg. 1 (Sec. IV-E, "Inference Batch Size Pruning": for each
+ * parallelism configuration only the batch sizes with a Pareto-optimal trade-off between latency
+ * and SLO satisfaction are retained).  The candidates [group_offsets[g], group_offsets[g+1]) are the
+ * batch sizes of configuration g, each already evaluated on the request set - for example as a
+ * single-instance deployment by maaso_placement_score, with sat_count its admitted requests and
+ * latency its Phi_L.  keep[c] (DEVICE, [n_cand]) becomes 0 when candidate c meets no request's SLO
+ * (sat_count[c] == 0: the batch sizes too high to meet any deadline under load) or when another
+ * candidate j of its group has sat_count[j] >= sat_count[c] and latency[j] <= latency[c] with one of
+ * the two strict (the batch sizes too low: more latency, no more requests served), else 1; equal
+ * candidates keep each other.  n_kept[g] (DEVICE, [n_groups]) counts the retained candidates of
+ * group g.  group_offsets (DEVICE, [n_groups+1]) must be non-decreasing with its last entry at most
+ * n_cand; a group that is not raises MAASO_DEV_BAD_CHAIN, gets n_kept 0 and leaves keep untouched.
+ * Candidates outside every group are not written.  Errors: INVALID_ARG, SHAPE, BUSY, HIP. */
+int maaso_batch_size_prune(maaso_ctx* ctx, uint32_t n_cand, const uint32_t* group_offsets,
+                           uint32_t n_groups, const uint32_t* sat_count, const float* latency,
+                           uint8_t* keep, uint32_t* n_kept, void* hip_stream);
 
 /* Arrays that maaso_resource_partition_requests works in and reports through: all DEVICE,
  * caller-owned, distinct from each other and from the inputs.  R = rq->n_req, C = pl->n_cand. */

@@ -14,6 +14,7 @@ from pathlib import Path
 
 import numpy as np
 
+from .batch_prune import batch_size_prune  # noqa: F401  (definition of the batch-size pruning)
 from .profile_fit import profile_fit  # noqa: F401  (numpy oracle of the profiler's fit)
 
 _HERE = Path(__file__).resolve().parent

@@ -29,7 +29,7 @@ EXPORTS = (
     "maaso_score_assign_selected", "maaso_placement_score_sets", "maaso_placement_sweep_noalloc",
     "maaso_ctx_reserve", "maaso_ctx_workspace", "maaso_ctx_kernel_durations",
     "maaso_ctx_window_profile", "maaso_ctx_window_phases", "maaso_probe_valu",
-    "maaso_ctx_set_cooperative", "maaso_resource_partition_requests",
+    "maaso_ctx_set_cooperative", "maaso_resource_partition_requests", "maaso_batch_size_prune",
 )
 
 
@@ -154,6 +154,8 @@ def load_library() -> C.CDLL:
         lib.maaso_resource_partition_requests.argtypes = [
             C.c_void_p, C.POINTER(Placements), C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(Requests),
             C.c_uint32, C.POINTER(Params), C.POINTER(ScoreWeights), C.POINTER(PartitionWork), C.c_void_p]
+        lib.maaso_batch_size_prune.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         missing = [n for n in EXPORTS if n != "maaso_strerror" and getattr(lib, n).argtypes is None]
         if missing:  # an undeclared signature would pass pointers as C ints
             raise RuntimeError(f"binding.py declares no argument types for {missing}")
@@ -494,6 +496,16 @@ def maaso_resource_partition(ctx: Context, *, n_gpus, phi_t_star, phi_l_star, ph
         _dptr(cand_l_star, torch.int32), _dptr(cand_h_star, torch.int32), int(n_req_l), int(n_req),
         _dptr(partition, torch.int32), _dptr(phi_opt, torch.float32), _stream_handle(stream)),
         "maaso_resource_partition")
+
+
+def maaso_batch_size_prune(ctx: Context, *, n_cand, group_offsets, sat_count, latency, keep, n_kept,
+                           stream=None) -> None:
+    import torch
+    n_groups = int(group_offsets.numel()) - 1
+    _check(load_library().maaso_batch_size_prune(
+        ctx.handle, int(n_cand), _dptr(group_offsets, torch.int32), n_groups,
+        _dptr(sat_count, torch.int32), _dptr(latency, torch.float32), _dptr(keep, torch.uint8),
+        _dptr(n_kept, torch.int32), _stream_handle(stream)), "maaso_batch_size_prune")
 
 
 def maaso_resource_partition_requests(ctx: Context, *, n_cand, i_pad, n_inst, tp_idx, max_batch, occ,

@@ -1071,6 +1071,31 @@ int maaso_resource_partition(maaso_ctx* ctx, uint32_t n_gpus, const float* phi_t
   return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
 }
 
+int maaso_batch_size_prune(maaso_ctx* ctx, uint32_t n_cand, const uint32_t* group_offsets,
+                           uint32_t n_groups, const uint32_t* sat_count, const float* latency,
+                           uint8_t* keep, uint32_t* n_kept, void* hip_stream) {
+  if (!ctx || !group_offsets || !n_kept) return MAASO_E_INVALID_ARG;
+  if (n_cand != 0u && (!sat_count || !latency || !keep)) return MAASO_E_INVALID_ARG;
+  if (n_groups > 0x7fffffffu) return MAASO_E_SHAPE;
+  if (n_groups == 0u) return MAASO_OK;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return MAASO_E_HIP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CallGuard call(ctx, s);
+  if (call.rc != MAASO_OK) return call.rc;
+  PruneArgs a;
+  a.n_cand = n_cand;
+  a.group_offsets = group_offsets;
+  a.n_groups = n_groups;
+  a.sat_count = sat_count;
+  a.latency = latency;
+  a.keep = keep;
+  a.n_kept = n_kept;
+  a.status = ctx->status;
+  hipLaunchKernelGGL(batch_prune_kernel, dim3(n_groups), dim3(kPruneTile), 0, s, a);
+  return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
+}
+
 int maaso_resource_partition_requests(maaso_ctx* ctx, const maaso_placements* pl,
                                       const uint32_t* chain_offsets, uint32_t n_chains,
                                       uint32_t n_gpus, const maaso_requests* rq,

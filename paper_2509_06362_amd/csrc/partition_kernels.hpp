@@ -211,6 +211,69 @@ __global__ __launch_bounds__(kPartitionThreads) void resource_partition_kernel(c
 }
 
 // ------------------------------------------------------------------------------------------------
+// Batch-size pruning (Sec. IV-E, "Inference Batch Size Pruning"): of the batch sizes of one
+// parallelism configuration keep those that are Pareto-optimal in (SLO satisfaction, latency)
+// ------------------------------------------------------------------------------------------------
+struct PruneArgs {
+  uint32_t n_cand;
+  const uint32_t* group_offsets;  // [n_groups + 1] group g = candidates [offsets[g], offsets[g + 1])
+  uint32_t n_groups;
+  const uint32_t* sat_count;      // [n_cand] requests whose SLO the candidate meets (more is better)
+  const float* latency;           // [n_cand] its response latency (less is better)
+  uint8_t* keep;                  // [n_cand] 1: retained
+  uint32_t* n_kept;               // [n_groups] retained candidates of the group
+  uint32_t* status;
+};
+
+constexpr int kPruneTile = 256;
+
+// One block per group.  Candidate i goes when it meets no request's SLO, or when another candidate
+// of its group is at least as good in both respects and better in one: sat_j >= sat_i and
+// lat_j <= lat_i with one of them strict.  Equal candidates keep each other; a NaN latency compares
+// false either way, so such a candidate neither removes another nor is removed by one.
+__global__ __launch_bounds__(kPruneTile) void batch_prune_kernel(const PruneArgs a) {
+  __shared__ uint32_t t_sat[kPruneTile];
+  __shared__ float t_lat[kPruneTile];
+  __shared__ uint32_t wave_kept[kPruneTile / 64];
+  const uint32_t g = blockIdx.x, tid = threadIdx.x;
+  const uint32_t o0 = a.group_offsets[g], o1 = a.group_offsets[g + 1];
+  if (o0 > o1 || o1 > a.n_cand) {  // not a group: flagged, nothing written but its count
+    if (tid == 0u) { raise_status(a.status, 8u); a.n_kept[g] = 0u; }
+    return;
+  }
+  uint32_t kept = 0;
+  for (uint32_t base = o0; base < o1; base += kPruneTile) {  // uniform trip count: barriers inside
+    const uint32_t i = base + tid;
+    const bool mine = i < o1;
+    const uint32_t sat_i = mine ? a.sat_count[i] : 0u;
+    const float lat_i = mine ? a.latency[i] : 0.0f;
+    bool dominated = false;
+    for (uint32_t jb = o0; jb < o1; jb += kPruneTile) {
+      __syncthreads();
+      if (jb + tid < o1) { t_sat[tid] = a.sat_count[jb + tid]; t_lat[tid] = a.latency[jb + tid]; }
+      __syncthreads();
+      const uint32_t n = min((uint32_t)kPruneTile, o1 - jb);
+      for (uint32_t j = 0; j < n; ++j) {
+        const uint32_t sat_j = t_sat[j];
+        const float lat_j = t_lat[j];
+        dominated |= (sat_j >= sat_i) & (lat_j <= lat_i) & ((sat_j > sat_i) | (lat_j < lat_i));
+      }
+    }
+    const bool k = mine && sat_i != 0u && !dominated;
+    if (mine) a.keep[i] = k ? 1u : 0u;
+    kept += k ? 1u : 0u;
+  }
+  for (int d = 32; d >= 1; d >>= 1) kept += __shfl_xor(kept, d);
+  if ((tid & 63u) == 0u) wave_kept[tid >> 6] = kept;
+  __syncthreads();
+  if (tid == 0u) {
+    uint32_t t = 0;
+    for (int w = 0; w < kPruneTile / 64; ++w) t += wave_kept[w];
+    a.n_kept[g] = t;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Alg. 2's first step: split the request streams by SLO class, keeping arrival order on both sides
 // ------------------------------------------------------------------------------------------------
 struct SplitArgs {

@@ -777,6 +777,110 @@ def test_resource_partition_at_bench_size():
         dw.close()
 
 
+def prune_on_gpu(ctx, dev, offsets, sat, lat, n_cand=None):
+    n_cand = len(sat) if n_cand is None else n_cand
+    keep = torch.full((len(sat),), 255, dtype=torch.uint8, device=dev)
+    n_kept = torch.full((len(offsets) - 1,), -1, dtype=torch.int32, device=dev)
+    binding.maaso_batch_size_prune(
+        ctx, n_cand=n_cand, group_offsets=torch.from_numpy(np.asarray(offsets, np.uint32).view(np.int32)).to(dev),
+        sat_count=torch.from_numpy(np.ascontiguousarray(sat).view(np.int32)).to(dev),
+        latency=torch.from_numpy(np.ascontiguousarray(lat)).to(dev), keep=keep, n_kept=n_kept)
+    torch.cuda.synchronize()
+    return keep.cpu().numpy(), u32(n_kept)
+
+
+@pytest.mark.parametrize("seed,sizes", [(1, [7, 0, 19, 1, 64]), (2, [256, 257, 3]), (3, [1000]),
+                                        (4, [5] * 40), (5, [2047, 513])])
+def test_batch_size_prune_matches_the_definition(seed, sizes):
+    """Pareto pruning of batch sizes per parallelism configuration: groups of every size around the
+    kernel's tile of 256 (ragged tails, empty groups), few distinct values so that ties abound,
+    candidates that serve nobody - keep flags and per-group counts bit for bit."""
+    rng = np.random.default_rng(300 + seed)
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(offsets[-1])
+    sat = (rng.integers(0, 12, n) * rng.integers(0, 2, n) * 7).astype(np.uint32)
+    lat = (rng.integers(0, 16, n) / 16.0).astype(np.float32)
+    ref_keep, ref_n = oracle.batch_size_prune(offsets, sat, lat)
+    dw = binding.DeviceWorkload(W.config0())
+    try:
+        print(f"prune seed={seed} groups={len(sizes)} n={n}", flush=True)
+        keep, n_kept = prune_on_gpu(dw.ctx, dw.prompt_len.device, offsets, sat, lat)
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        assert np.array_equal(keep, ref_keep)
+        assert np.array_equal(n_kept, ref_n)
+    finally:
+        dw.close()
+
+
+def test_batch_size_prune_edge_cases():
+    rng = np.random.default_rng(9)
+    sat = rng.integers(1, 9, 40).astype(np.uint32)
+    lat = rng.random(40).astype(np.float32)
+    dw = binding.DeviceWorkload(W.config0())
+    try:
+        dev = dw.prompt_len.device
+        # a group that runs backwards and one that runs past the end: flagged and skipped, the
+        # others served; candidates outside every group are not written
+        offsets = [0, 10, 5, 12, 41]
+        ref_keep, ref_n = oracle.batch_size_prune(offsets, sat, lat)
+        keep, n_kept = prune_on_gpu(dw.ctx, dev, offsets, sat, lat)
+        assert binding.maaso_ctx_device_status(dw.ctx) == 8
+        assert np.array_equal(keep, ref_keep) and np.array_equal(n_kept, ref_n)
+        assert (keep[12:] == 255).all() and n_kept.tolist() == [int(ref_n[0]), 0, int(ref_n[2]), 0]
+        # NaN latency: compares false both ways, so the candidate stays and removes nobody
+        lat2 = lat.copy()
+        lat2[3] = np.nan
+        ref_keep, ref_n = oracle.batch_size_prune([0, 40], sat, lat2)
+        keep, n_kept = prune_on_gpu(dw.ctx, dev, [0, 40], sat, lat2)
+        assert np.array_equal(keep, ref_keep) and keep[3] == 1 and np.array_equal(n_kept, ref_n)
+        # no groups: nothing to do; missing arrays: refused
+        binding.maaso_batch_size_prune(dw.ctx, n_cand=0, group_offsets=torch.zeros(1, dtype=torch.int32, device=dev),
+                                       sat_count=None, latency=None, keep=None,
+                                       n_kept=torch.zeros(1, dtype=torch.int32, device=dev))
+        with pytest.raises(binding.MaasoError) as e:
+            binding.maaso_batch_size_prune(dw.ctx, n_cand=4, group_offsets=torch.zeros(2, dtype=torch.int32, device=dev),
+                                           sat_count=None, latency=None, keep=None,
+                                           n_kept=torch.zeros(1, dtype=torch.int32, device=dev))
+        assert e.value.status == -1
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("window,rate", [(64, 300.0), (16, 900.0), (0, 300.0)])
+def test_batch_size_prune_of_scored_configurations(window, rate):
+    """The step as the placer uses it: every (strategy, batch size) pair as a single fresh instance,
+    scored against the requests by maaso_placement_score, pruned per strategy on (admitted requests,
+    Phi_L) - against the oracle's score followed by the oracle's pruning."""
+    w = W.partition_case(n_req=3000, rate=rate, seed=61)
+    batch_set = [1, 2, 4, 8, 16, 32, 64, 128]
+    tp, b = W.all_configs(batch_set=batch_set)
+    cw, _ = W.growth_chains(w, tp, b, 8, max_inst=1)          # one instance per configuration
+    assert cw.n_cand == len(tp)
+    offsets = np.arange(0, len(tp) + 1, len(batch_set))       # strategy-major: one group per strategy
+    wts = SCORE_WEIGHTS[0]
+    ref = oracle.placement_score(cw, *wts, window=window)
+    ref_keep, ref_n = oracle.batch_size_prune(offsets, ref["sat_count"], ref["phi_l"])
+    dw = binding.DeviceWorkload(cw)
+    try:
+        print(f"prune scored configurations window={window} rate={rate} C={cw.n_cand}", flush=True)
+        dev = dw.prompt_len.device
+        got = dw.score(*wts, window=window)
+        keep = torch.full((cw.n_cand,), 255, dtype=torch.uint8, device=dev)
+        n_kept = torch.zeros(len(offsets) - 1, dtype=torch.int32, device=dev)
+        binding.maaso_batch_size_prune(
+            dw.ctx, n_cand=cw.n_cand, group_offsets=torch.from_numpy(offsets.astype(np.int32)).to(dev),
+            sat_count=got["sat_count"], latency=got["phi_l"], keep=keep, n_kept=n_kept)
+        torch.cuda.synchronize()
+        assert binding.maaso_ctx_device_status(dw.ctx) == 0
+        assert np.array_equal(u32(got["sat_count"]), ref["sat_count"])
+        assert np.array_equal(got["phi_l"].cpu().numpy(), ref["phi_l"])
+        assert np.array_equal(keep.cpu().numpy(), ref_keep)
+        assert np.array_equal(u32(n_kept), ref_n)
+        assert 0 < int(ref_n.sum()) < cw.n_cand or window == 0   # something goes, something stays
+    finally:
+        dw.close()
+
+
 def test_outer_algorithm_error_paths():
     w, cw, offs, tp, b = chain_case(200, 100.0, 8, seed=7)
     dw = binding.DeviceWorkload(cw)
