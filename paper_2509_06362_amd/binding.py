@@ -542,6 +542,8 @@ class DeviceWorkload:
 
         def up(a, view):
             a = np.ascontiguousarray(a)
+            if not a.flags.writeable:  # e.g. a broadcast view: torch wants a buffer of its own
+                a = a.copy()
             return torch.from_numpy(a.view(view)).to(dev)
 
         self.prompt_len = up(w.prompt_len, np.int32)
