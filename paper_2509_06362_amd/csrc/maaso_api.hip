@@ -254,13 +254,20 @@ int launch_sweep_window_v(const SweepWindowArgs& a, size_t lds, hipStream_t s) {
   for (uint32_t k = 0; k < a.n_sets; ++k) one_by_one = one_by_one && a.sets[k].window <= short_window;
   if (one_by_one) {
     const dim3 g((uint32_t)((blocks + kSeqThreads / 64 - 1) / (kSeqThreads / 64)));
+    bool one = true;  // every set request by request
+    for (uint32_t k = 0; k < a.n_sets; ++k) one = one && a.sets[k].window == 1u;
     if (!kSQ) {
-      if (a.i_pad <= 64u)
-        hipLaunchKernelGGL((sweep_seq_kernel<kScore, 1>), g, dim3(kSeqThreads), lds, s, a);
-      else if (a.i_pad <= 128u)
-        hipLaunchKernelGGL((sweep_seq_kernel<kScore, 2>), g, dim3(kSeqThreads), lds, s, a);
-      else
-        hipLaunchKernelGGL((sweep_seq_kernel<kScore, 4>), g, dim3(kSeqThreads), lds, s, a);
+      const dim3 b(kSeqThreads);
+      if (a.i_pad <= 64u) {
+        if (one) hipLaunchKernelGGL((sweep_seq_kernel<kScore, 1, true>), g, b, lds, s, a);
+        else hipLaunchKernelGGL((sweep_seq_kernel<kScore, 1>), g, b, lds, s, a);
+      } else if (a.i_pad <= 128u) {
+        if (one) hipLaunchKernelGGL((sweep_seq_kernel<kScore, 2, true>), g, b, lds, s, a);
+        else hipLaunchKernelGGL((sweep_seq_kernel<kScore, 2>), g, b, lds, s, a);
+      } else {
+        if (one) hipLaunchKernelGGL((sweep_seq_kernel<kScore, 4, true>), g, b, lds, s, a);
+        else hipLaunchKernelGGL((sweep_seq_kernel<kScore, 4>), g, b, lds, s, a);
+      }
     }
     return hip_ok(hipGetLastError()) ? MAASO_OK : MAASO_E_HIP;
   }

@@ -48,7 +48,9 @@ __device__ __forceinline__ void argmax_wave(float s, int32_t i, uint32_t lane, f
   }
 }
 
-template <bool kScore, int S>
+// kOne: every set's window is one request (the window length is then a constant: the window loop and
+// the per-window sums of admitted load fold away).
+template <bool kScore, int S, bool kOne = false>
 __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindowArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* tab = reinterpret_cast<float*>(smem);
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(kSeqThreads) void sweep_seq_kernel(const SweepWindo
   bool bad_slot = false;               // a slot of this lane was outside the tables at some window
 
   const uint64_t R = rs.n_req;
-  const uint64_t W = rs.window;
+  const uint64_t W = kOne ? 1ull : rs.window;
   // requests are fetched 64 at a time, one per lane, and handed out with v_readlane
   // what depends on the request alone (its deadlines, the reciprocal of the end-to-end one) is
   // worked out for the 64 requests of a batch at once, off the per-request chain
