@@ -129,6 +129,7 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
   __shared__ uint32_t wave_sat[kWindowThreads / 64];
   __shared__ int32_t occ_s[kSQ ? 256 : 1];
   __shared__ float rankv[kSQ ? 256 : 1];
+  __shared__ uint32_t gave_up_blk;  // a thread of this block gave up waiting at a window boundary
 
   const uint32_t tid = threadIdx.x;
   const PlacementRow row = select_row(a);
@@ -140,6 +141,7 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
   if (tid < n) { tp = row.tp_idx[tid]; B = row.max_batch[tid]; occ = row.occ[tid]; q = row.q_ticks[tid]; }
   if (tid < a.n_slo) cls[tid] = ClassRow{a.d_ttft[tid], a.d_tbt[tid], a.i_ttft[tid], a.i_tbt[tid]};
   for (uint32_t i = tid; i < 3u * a.cells; i += kWindowThreads) tab[i] = a.tab[i];
+  if (tid == 0u) gave_up_blk = 0u;
   __syncthreads();
 
   constexpr uint32_t kReqPerBlock = kWindowThreads / LPR;
@@ -206,6 +208,14 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
       if (kSQ) occ_s[tid] = occ;
     }
     __syncthreads();
+    // A wait of the previous window's boundary gave up, here or (seen through the abort flag) in
+    // another block: every block leaves before it scores anything of this window.  The verdict rides
+    // on the barrier that publishes the staged records; the state advanced above from sums that
+    // never arrived is not used and not written back.
+    if (gave_up_blk != 0u) {
+      alive = false;
+      break;
+    }
     if (kSQ) {
       if (tid < n) rankv[tid] = queue_rank_value(occ_s, n, tid);
       __syncthreads();
@@ -353,10 +363,7 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
         }
       }
     }
-    if (__syncthreads_or(gave_up ? 1 : 0)) {  // a wait gave up here or elsewhere: every block leaves
-      alive = false;
-      break;
-    }
+    if (gave_up) gave_up_blk = 1u;
     const long long t3 = kProf ? clock64() : 0ll;
 
     if (tid < n) {
@@ -378,6 +385,8 @@ __global__ __launch_bounds__(kWindowThreads) void assign_window_kernel(const Ass
       t_phase[3] += (unsigned long long)(t4 - t3);
     }
   }
+  __syncthreads();  // the last boundary's verdict
+  if (gave_up_blk != 0u) alive = false;
   if (kProf && blockIdx.x == 0 && tid == 0) {
     for (int i = 0; i < 4; ++i) ws->phase[i] = t_phase[i];
     ws->phase[4] = (unsigned long long)(clock64() - t_loop);
