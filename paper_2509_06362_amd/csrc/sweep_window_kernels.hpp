@@ -13,6 +13,7 @@
 #pragma once
 
 #include "assign_kernels.hpp"
+#include "lane_ops.hpp"
 
 #pragma clang fp contract(off)
 
@@ -232,7 +233,10 @@ __global__ __launch_bounds__(kAssignThreads) void sweep_window_kernel(const Swee
         const unsigned long long ticks = adm ? (unsigned long long)__float2ll_rn(bpre[v] * 1048576.0f) : 0ull;
         const int32_t first = __builtin_amdgcn_readlane(idx[v], __builtin_ctzll(am));
         if (__ballot(adm && idx[v] == first) == am) {  // the whole wavefront chose one instance
-          const unsigned long long tsum = wave_sum_u64(ticks);
+          // prefill times below 64 s each (2^26 ticks) add up in 32 bits: the usual case
+          const unsigned long long tsum = __ballot((ticks >> 26) != 0ull) == 0ull
+                                              ? (unsigned long long)wave_sum_u32((uint32_t)ticks)
+                                              : wave_sum_u64(ticks);
           if ((tid & 63u) == 0u) {
             atomicAdd(&n_blk[first], (uint32_t)__popcll(am));
             atomicAdd(&t_blk[first], tsum);
