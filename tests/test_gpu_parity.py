@@ -1409,6 +1409,73 @@ def test_inter_window_wait_gives_up_cleanly():
 
 
 # ------------------------------------------------------------------------------------------------
+# random shapes, every path
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_every_path(seed):
+    """Forty random small workloads per seed - slot counts around the lane and tile sizes, request
+    counts around the block sizes (zero included), 1 to 16 classes, windows from one request to more
+    than there are requests - through the static sweep (both entry points), the capacity-aware sweep,
+    the composite score and the distributor (static and windowed, both selection rules): counts, best
+    candidates, choices, slacks and final states bit for bit."""
+    from dataclasses import replace
+    rng = np.random.default_rng(seed)
+    for case in range(40):
+        s = int(rng.integers(1, 1 << 30))
+        i_pad = int(rng.choice([1, 2, 3, 7, 8, 9, 16, 31, 32, 33, 64, 65, 128, 200, 256]))
+        n_cand = int(rng.integers(1, 60))
+        n_req = int(rng.choice([0, 1, 5, 63, 64, 65, 255, 256, 257, 1000, 2049, 4100]))
+        n_slo = int(rng.choice([1, 2, 3, 5, 16]))
+        window = int(rng.choice([1, 2, 3, 4, 16, 17, 64, 256, 300, 1024, 5000]))
+        w = W.random_small(s, n_cand, i_pad, n_req, n_slo=n_slo, b_cap=int(rng.choice([8, 32, 128])),
+                           over_cap=bool(rng.integers(0, 2)), queued=bool(rng.integers(0, 2)),
+                           pen_kappa=float(rng.choice([0.0, 0.5])))
+        what = f"case {case}: seed={s} C={n_cand} I={i_pad} R={n_req} K={n_slo} window={window}"
+        print(what, flush=True)
+        dw = binding.DeviceWorkload(w)
+        try:
+            ref = oracle.placement_sweep(w)
+            cnt, _, best = dw.sweep()
+            torch.cuda.synchronize()
+            assert np.array_equal(u32(cnt), ref["sat_count"]) and int(best.item()) == int(ref["best_cand"]), what
+            cnt, _, best = dw.sweep(noalloc=True)
+            torch.cuda.synchronize()
+            assert np.array_equal(u32(cnt), ref["sat_count"]) and int(best.item()) == int(ref["best_cand"]), what
+            if n_req == 0:
+                continue
+            refw = oracle.placement_sweep_windowed(w, window=window)
+            cnt, _, best = dw.sweep(window=window)
+            torch.cuda.synchronize()
+            assert np.array_equal(u32(cnt), refw["sat_count"]) and int(best.item()) == int(refw["best_cand"]), what
+            refs = oracle.placement_score(w, *SCORE_WEIGHTS[0], window=window)
+            sc = dw.score(*SCORE_WEIGHTS[0], window=window)
+            torch.cuda.synchronize()
+            assert np.array_equal(sc["score"].cpu().numpy(), refs["score"]), what
+            assert np.array_equal(u32(sc["sat_count"]), refs["sat_count"]), what
+            c = int(rng.integers(0, n_cand))
+            for win in (0, window):
+                for policy in (0, 1):
+                    w2 = w if policy == 0 else replace(w, policy=1)
+                    dwx = dw if policy == 0 else binding.DeviceWorkload(w2)
+                    try:
+                        r = oracle.score_assign(w2, cand=c, window=win)
+                        got = dwx.assign(cand=c, window=win)
+                        torch.cuda.synchronize()
+                        assert np.array_equal(got["chosen"].cpu().numpy(), r["chosen"]), (what, win, policy)
+                        assert np.array_equal(got["slack"].cpu().numpy(), r["slack"], equal_nan=True), (what, win, policy)
+                        assert int(got["n_satisfied"].item()) == r["n_satisfied"], (what, win, policy)
+                        if win:
+                            assert np.array_equal(got["occ"].cpu().numpy()[0], r["occ"]), (what, win, policy)
+                            assert np.array_equal(got["q_ticks"].cpu().numpy()[0].view(np.uint64), r["q_ticks"])
+                    finally:
+                        if dwx is not dw:
+                            dwx.close()
+        finally:
+            dw.close()
+
+
+# ------------------------------------------------------------------------------------------------
 # the boundary's promises: no allocation in compute calls, order between streams, one call at a time
 # ------------------------------------------------------------------------------------------------
 
